@@ -1,0 +1,49 @@
+"""Build libdash.so (HIP, gfx950) in-tree.  `python -m paper_2302_06361_amd.build`"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+SO = os.path.join(HERE, "libdash.so")
+SOURCES = ["dash_ctx.hip", "dash_gates.hip", "dash_layers.hip", "dash_linear.hip"]
+HEADERS = ["dash_core.h", "dash_hostconst.h", "dash_internal.h", os.path.join("..", "..", "include", "dash.h")]
+FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+         # packed FP32 instructions are kept out of every code object of this library
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def build(force=True, verbose=False):
+    """Compile every HIP source for gfx950 and link libdash.so.  Objects are rebuilt when a source
+    or header is newer (or always with force)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    hdr_time = max(os.path.getmtime(os.path.join(CSRC, h)) for h in HEADERS)
+    objs, procs = [], []
+    for src in SOURCES:
+        s = os.path.join(CSRC, src)
+        o = os.path.join(CSRC, src.replace(".hip", ".o"))
+        objs.append(o)
+        if force or not os.path.exists(o) or os.path.getmtime(o) < max(os.path.getmtime(s), hdr_time):
+            cmd = [hipcc] + FLAGS + ["-c", s, "-o", o]
+            if verbose:
+                print(" ".join(cmd))
+            procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    failed = False
+    for src, p in procs:
+        out, _ = p.communicate()
+        # the host pass does not know the packed-fp32 feature and says so: harmless
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        if out.strip():
+            print(out)
+        if p.returncode != 0:
+            failed = True
+            print("FAILED:", src)
+    if failed:
+        raise RuntimeError("hipcc failed")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", SO] + objs)
+    return SO
+
+
+if __name__ == "__main__":
+    build(force="--incremental" not in sys.argv, verbose=True)
+    print("built", SO)

@@ -1,0 +1,412 @@
+// dash_ctx.hip -- context (CRT base, label lengths, offset labels, function tables of the sign
+// gadget), En / De kernels and the C ABI entry points of include/dash.h.
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "dash_hostconst.h"
+#include "dash_internal.h"
+
+using namespace dash;
+using namespace dash::hostconst;
+
+// ------------------------------------------------------------------------------------------------
+// Host-side constants
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+int inv_mod(int a, int p) { for (int t = 1; t < p; t++) if ((a * t) % p == 1) return t; return 0; }
+
+// Smallest-table mixed-radix digits with d_1 even, k*d_j <= 255, prod >= k*P (equal lower digits).
+bool search_digits(int k, uint64_t P, const int* primes, int rule, int* n_out, int* d_out) {
+    u128 need = (u128)k * P;
+    int dmax = 255 / k;
+    if (dmax < 2) return false;
+    double best = 1e300;
+    int sp = 0;
+    for (int i = 0; i < k; i++) sp += primes[i];
+    for (int n = 1; n <= DASH_MAX_DIGITS; n++)
+        for (int d = 2; d <= dmax; d++) {
+            u128 low = 1;
+            for (int j = 1; j < n; j++) low *= (u128)d;
+            u128 d1 = (need + low - 1) / low;
+            if (d1 < 2) d1 = 2;
+            if (d1 & 1) d1++;
+            if (d1 > 254) continue;
+            int pit_lo = 4 * ((label_length(k * d, rule) + 3) / 4), pit_1 = 4 * ((label_length((int)d1, rule) + 3) / 4);
+            double cost = (double)sp * (pit_1 + (n - 1) * pit_lo) + (double)(n > 1 ? (n - 2) * k * d * pit_lo + k * d * pit_1 : 0) +
+                          (double)d1 * 128;
+            if (cost < best) { best = cost; *n_out = n; d_out[0] = (int)d1; for (int j = 1; j < n; j++) d_out[j] = d; }
+            if (n == 1) break;
+        }
+    return best < 1e300;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// small kernels: offset-multiple tables, En, De
+// ------------------------------------------------------------------------------------------------
+namespace dash {
+
+// R_m: force the colour digit to 1, then dtab[a][i] = packed digits of a * R_m mod m
+__global__ void k_delta_tab(ModInfo M, uint8_t* delta, uint32_t* dtab) {
+    uint32_t a = blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= M.m) return;
+    for (uint32_t i = 0; i < M.ndw; i++) {
+        uint32_t w = *(const uint32_t*)(delta + (i >> 2) * 16 + (i & 3) * 4);
+        if (i == 0) w = (w & ~0xffu) | 1u;
+        dtab[a * M.ndw + i] = axpymod4(0, a, w, M);
+    }
+}
+__global__ void k_fix_colour(uint8_t* delta) { delta[0] = 1; }
+
+__global__ __launch_bounds__(kThreads) void k_encode(const ModInfo* mods, uint32_t m, const int64_t* values, uint32_t n,
+                                                     LView zero, LView out) {
+    uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    const ModInfo M = mods[m];
+    int64_t v = values[e] % (int64_t)m;
+    if (v < 0) v += m;
+    const uint32_t* dv = M.dtab + (size_t)v * M.ndw;
+    for (uint32_t i = 0; i < M.nchunk * 4; i++) {
+        uint32_t z = *(const uint32_t*)(zero.p + (int64_t)(i >> 2) * zero.cs + (uint64_t)e * 16 + (i & 3) * 4);
+        uint32_t w = i < M.ndw ? addmod4(z, dv[i], M) : 0;
+        *(uint32_t*)(out.p + (int64_t)(i >> 2) * out.cs + (uint64_t)e * 16 + (i & 3) * 4) = w;
+    }
+}
+
+struct DecodeArgs {
+    const ModInfo* mods;
+    uint32_t k, n;
+    uint32_t prime[DASH_MAX_PRIMES];
+    uint64_t crt_coef[DASH_MAX_PRIMES];   // (P/p_i) * ((P/p_i)^-1 mod p_i) mod P
+    uint64_t P;
+    LView act[DASH_MAX_PRIMES], zero[DASH_MAX_PRIMES];
+    int64_t* values;
+    uint8_t* valid;
+};
+
+__global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
+    uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= A.n) return;
+    bool ok = true;
+    unsigned __int128 acc = 0;
+    for (uint32_t i = 0; i < A.k; i++) {
+        const ModInfo M = A.mods[A.prime[i]];
+        const LView &a = A.act[i], &z = A.zero[i];
+        uint32_t a0 = *(const uint32_t*)(a.p + (uint64_t)e * 16), z0 = *(const uint32_t*)(z.p + (uint64_t)e * 16);
+        uint32_t v = mod_m((a0 & 0xff) + M.m - (z0 & 0xff), M);      // colour difference; R's colour is 1
+        const uint32_t* dv = M.dtab + (size_t)v * M.ndw;
+        for (uint32_t j = 0; j < M.ndw; j++) {
+            uint32_t aw = *(const uint32_t*)(a.p + (int64_t)(j >> 2) * a.cs + (uint64_t)e * 16 + (j & 3) * 4);
+            uint32_t zw = *(const uint32_t*)(z.p + (int64_t)(j >> 2) * z.cs + (uint64_t)e * 16 + (j & 3) * 4);
+            if (aw != addmod4(zw, dv[j], M)) ok = false;
+        }
+        acc += (unsigned __int128)A.crt_coef[i] * v;
+    }
+    uint64_t X = (uint64_t)(acc % A.P);
+    int64_t s = (2 * X >= A.P) ? (int64_t)X - (int64_t)A.P : (int64_t)X;
+    A.values[e] = ok ? s : 0;
+    A.valid[e] = ok ? 1 : 0;
+}
+
+}  // namespace dash
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* dash_strerror(int status) {
+    switch (status) {
+        case DASH_OK: return "ok";
+        case DASH_EINVAL: return "invalid argument";
+        case DASH_ESIZE: return "size not supported";
+        case DASH_EHIP: return "HIP runtime error";
+        case DASH_EUNSUPPORTED: return "not implemented";
+    }
+    return "unknown status";
+}
+
+int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_rule, const uint8_t seed[16],
+                    const uint16_t* sign_digits, int n_digits, int hip_device) {
+    if (!out || !primes || !seed || k < 1 || k > DASH_MAX_PRIMES) return DASH_EINVAL;
+    if (lambda_rule != DASH_LAMBDA_CEIL && lambda_rule != DASH_LAMBDA_FLOOR) return DASH_EINVAL;
+    for (int i = 0; i < k; i++) {
+        if (primes[i] < 2 || primes[i] > 127) return DASH_EINVAL;
+        for (int j = 0; j < i; j++) if (primes[j] == primes[i]) return DASH_EINVAL;
+        for (int t = 2; t * t <= primes[i]; t++) if (primes[i] % t == 0) return DASH_EINVAL;
+    }
+    dash_ctx* c = new (std::nothrow) dash_ctx();
+    if (!c) return DASH_EINVAL;
+    memset(c, 0, sizeof(*c));
+    c->device = hip_device; c->k = k; c->rule = lambda_rule;
+    c->P = 1;
+    for (int i = 0; i < k; i++) { c->prime[i] = primes[i]; c->P *= primes[i]; }
+
+    if (sign_digits) {
+        if (n_digits < 1 || n_digits > DASH_MAX_DIGITS) { delete c; return DASH_EINVAL; }
+        c->n = n_digits;
+        for (int j = 1; j <= n_digits; j++) c->d[j] = sign_digits[j - 1];
+    } else {
+        static const int fixed8[] = {26, 12, 12, 12, 12, 12, 12};
+        static const int fixed12[] = {46, 17, 17, 17, 17, 17, 17, 17, 17, 17, 17};
+        int dd[DASH_MAX_DIGITS];
+        bool first_primes = true;
+        static const int fp[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+        for (int i = 0; i < k && i < 12; i++) if (c->prime[i] != fp[i]) first_primes = false;
+        if (first_primes && k == 8) { c->n = 7; memcpy(dd, fixed8, sizeof(fixed8)); }
+        else if (first_primes && k == 12) { c->n = 11; memcpy(dd, fixed12, sizeof(fixed12)); }
+        else if (!search_digits(k, c->P, c->prime, lambda_rule, &c->n, dd)) { delete c; return DASH_EUNSUPPORTED; }
+        for (int j = 1; j <= c->n; j++) c->d[j] = dd[j - 1];
+    }
+    if (c->d[1] < 2 || (c->d[1] & 1) || c->d[1] > 254) { delete c; return DASH_EINVAL; }
+    c->mj[1] = c->d[1];
+    for (int j = 2; j <= c->n; j++) {
+        if (c->d[j] < 2 || k * c->d[j] > 255) { delete c; return DASH_EINVAL; }
+        c->mj[j] = k * c->d[j];
+    }
+
+    uint8_t S[256];
+    uint32_t T[1024];
+    make_sbox(S);
+    make_ttab(S, T);
+    uint8_t fixed_key[16];
+    for (int i = 0; i < 16; i++) fixed_key[i] = (uint8_t)i;
+    expand_key(fixed_key, S, c->fixed.rk);
+    expand_key(seed, S, c->seed.rk);
+
+    // moduli in use: 2, the primes, the accumulation moduli
+    bool used[256] = {false};
+    used[2] = true;
+    for (int i = 0; i < k; i++) used[c->prime[i]] = true;
+    for (int j = 1; j <= c->n; j++) used[c->mj[j]] = true;
+    for (int m = 2; m < 256; m++) fill_modinfo(c->mods[m], m, lambda_rule);
+
+    // function tables of the sign gadget (Appendix, Approximated Garbled Sign)
+    std::vector<uint8_t> phi;
+    std::vector<size_t> off_digit((size_t)k * (c->n + 1)), off_carry(c->n + 1), off_final(2), off_pm1(k);
+    u128 Mrad = 1;
+    for (int j = 1; j <= c->n; j++) Mrad *= (u128)c->d[j];
+    for (int i = 0; i < k; i++) {
+        int p = c->prime[i];
+        int inv = inv_mod((int)((c->P / p) % p), p);
+        for (int j = 1; j <= c->n; j++) {
+            off_digit[(size_t)i * (c->n + 1) + j] = phi.size();
+            u128 w = 1;
+            for (int t = c->n; t > j; t--) w *= (u128)c->d[t];
+            for (int x = 0; x < p; x++) {
+                int u = (x * inv) % p;
+                u128 N = (Mrad * (u128)u + (u128)(p - 1)) / (u128)p;    // fraction rounded up to 1/M
+                phi.push_back((uint8_t)((N / w) % (u128)c->d[j]));
+            }
+        }
+    }
+    for (int j = 2; j <= c->n; j++) {
+        off_carry[j] = phi.size();
+        for (int s = 0; s < c->mj[j]; s++) phi.push_back((uint8_t)((s / c->d[j]) % c->mj[j - 1]));
+    }
+    for (int neg = 0; neg < 2; neg++) {
+        off_final[neg] = phi.size();
+        for (int s = 0; s < c->mj[1]; s++) { int up = (2 * s >= c->d[1]); phi.push_back((uint8_t)(neg ? 1 - up : up)); }
+    }
+    size_t off_ident = phi.size();
+    phi.push_back(0); phi.push_back(1);
+    for (int i = 0; i < k; i++) { off_pm1[i] = phi.size(); phi.push_back(1); phi.push_back((uint8_t)(c->prime[i] == 2 ? 1 : c->prime[i] - 1)); }
+    while (phi.size() % 256) phi.push_back(0);
+
+    // device pool layout
+    size_t bytes = phi.size();
+    size_t off_delta[256], off_dtab[256], off_one0[DASH_MAX_PRIMES], off_one[DASH_MAX_PRIMES];
+    auto take = [&](size_t n) { size_t o = bytes; bytes += (n + 255) & ~(size_t)255; return o; };
+    for (int m = 2; m < 256; m++) if (used[m]) {
+        off_delta[m] = take(c->mods[m].nchunk * 16);
+        off_dtab[m] = take((size_t)m * c->mods[m].ndw * 4);
+    }
+    for (int i = 0; i < k; i++) { off_one0[i] = take(c->mods[c->prime[i]].nchunk * 16); off_one[i] = take(c->mods[c->prime[i]].nchunk * 16); }
+    c->pool_bytes = bytes;
+
+    int status = DASH_EHIP;
+    do {
+        if (hipSetDevice(hip_device) != hipSuccess) break;
+        if (hipMalloc((void**)&c->d_pool, bytes) != hipSuccess) break;
+        if (hipMalloc((void**)&c->d_mods, sizeof(ModInfo) * 256) != hipSuccess) break;
+        if (hipMalloc((void**)&c->d_ttab, sizeof(T)) != hipSuccess) break;
+        if (hipMemset(c->d_pool, 0, bytes) != hipSuccess) break;
+        if (hipMemcpy(c->d_pool, phi.data(), phi.size(), hipMemcpyHostToDevice) != hipSuccess) break;
+        if (hipMemcpy(c->d_ttab, T, sizeof(T), hipMemcpyHostToDevice) != hipSuccess) break;
+        for (int m = 2; m < 256; m++) if (used[m]) {
+            c->d_delta[m] = c->d_pool + off_delta[m];
+            c->mods[m].dtab = (const uint32_t*)(c->d_pool + off_dtab[m]);
+        }
+        if (hipMemcpy(c->d_mods, c->mods, sizeof(ModInfo) * 256, hipMemcpyHostToDevice) != hipSuccess) break;
+        for (int i = 0; i < k; i++) {
+            c->d_one0[i] = c->d_pool + off_one0[i];
+            c->d_one[i] = c->d_pool + off_one[i];
+            for (int j = 1; j <= c->n; j++) c->phi_digit[i][j] = c->d_pool + off_digit[(size_t)i * (c->n + 1) + j];
+            c->phi_pm1[i] = c->d_pool + off_pm1[i];
+        }
+        for (int j = 2; j <= c->n; j++) c->phi_carry[j] = c->d_pool + off_carry[j];
+        c->phi_final[0] = c->d_pool + off_final[0];
+        c->phi_final[1] = c->d_pool + off_final[1];
+        c->phi_ident = c->d_pool + off_ident;
+
+        // offset labels R_m and their multiples
+        bool fail = false;
+        for (int m = 2; m < 256 && !fail; m++) if (used[m]) {
+            DrawLaunch L;
+            memset(&L, 0, sizeof(L));
+            L.elem_base = 0; L.layer = 0; L.n_elem = 1;
+            L.jobs[0] = DrawJob{(uint32_t)m, DOM_DELTA, 0, 0, LView{c->d_delta[m], 16, 16}};
+            if (launch_draw(c, L, 1, 0) != DASH_OK) { fail = true; break; }
+            hipLaunchKernelGGL(k_delta_tab, dim3((m + 63) / 64), dim3(64), 0, 0, c->mods[m], c->d_delta[m],
+                               (uint32_t*)(c->d_pool + off_dtab[m]));
+            hipLaunchKernelGGL(k_fix_colour, dim3(1), dim3(1), 0, 0, c->d_delta[m]);
+        }
+        if (fail) break;
+        // constant-one wires: zero label from the PRG, active = zero + R_p
+        for (int i = 0; i < k && !fail; i++) {
+            int p = c->prime[i];
+            DrawLaunch L;
+            memset(&L, 0, sizeof(L));
+            L.n_elem = 1;
+            L.jobs[0] = DrawJob{(uint32_t)p, DOM_ONE, 0, 0, LView{c->d_one0[i], 16, 16}};
+            if (launch_draw(c, L, 1, 0) != DASH_OK) { fail = true; break; }
+            AffineLaunch A;
+            memset(&A, 0, sizeof(A));
+            A.n_elem = 1;
+            A.terms[0] = Term{LView{c->d_one0[i], 16, 16}, 1};
+            A.terms[1] = Term{LView{c->d_delta[p], 16, 16}, 1};
+            A.jobs[0] = AffineJob{(uint32_t)p, 0, 2, 0, LView{c->d_one[i], 16, 16}};
+            if (launch_affine(c, A, 1, 0) != DASH_OK) { fail = true; break; }
+        }
+        if (fail) break;
+        if (hipDeviceSynchronize() != hipSuccess) break;
+        status = DASH_OK;
+    } while (0);
+    if (status != DASH_OK) { dash_ctx_destroy(c); return status; }
+    *out = c;
+    return DASH_OK;
+}
+
+void dash_ctx_destroy(dash_ctx* c) {
+    if (!c) return;
+    if (c->d_pool) (void)hipFree(c->d_pool);
+    if (c->d_mods) (void)hipFree(c->d_mods);
+    if (c->d_ttab) (void)hipFree(c->d_ttab);
+    delete c;
+}
+
+int dash_lambda(const dash_ctx* c, int m) { return (c && m >= 2 && m <= 255) ? (int)c->mods[m].lam : 0; }
+
+static int copy_label_to_host(const dash_ctx* c, const uint8_t* dev, int m, uint8_t* host) {
+    uint8_t buf[128];
+    DASH_HIP(hipMemcpy(buf, dev, c->mods[m].nchunk * 16, hipMemcpyDeviceToHost));
+    memcpy(host, buf, c->mods[m].lam);
+    return DASH_OK;
+}
+int dash_ctx_offset(const dash_ctx* c, int m, uint8_t* host_out) {
+    if (!c || !host_out || m < 2 || m > 255 || !c->d_delta[m]) return DASH_EINVAL;
+    return copy_label_to_host(c, c->d_delta[m], m, host_out);
+}
+int dash_ctx_one(const dash_ctx* c, int i, int which, uint8_t* host_out) {
+    if (!c || !host_out || i < 0 || i >= c->k || which < 0 || which > 1) return DASH_EINVAL;
+    return copy_label_to_host(c, which ? c->d_one[i] : c->d_one0[i], c->prime[i], host_out);
+}
+int dash_ctx_digits(const dash_ctx* c, uint16_t* host_digits) {
+    if (!c || !host_digits) return DASH_EINVAL;
+    for (int j = 1; j <= c->n; j++) host_digits[j - 1] = (uint16_t)c->d[j];
+    return c->n;
+}
+
+static int check_labels(const dash_ctx* c, const dash_labels* t, int64_t n, int only = -1) {
+    if (!t || t->n_elem < n) return DASH_EINVAL;
+    for (int i = 0; i < c->k; i++) {
+        if (only >= 0 && i != only) continue;
+        if (n > 0 && !t->data[i]) return DASH_EINVAL;
+        if (((uintptr_t)t->data[i] & 15) || (t->chunk_stride[i] & 15) || t->chunk_stride[i] < 16 * n) return DASH_EINVAL;
+    }
+    return DASH_OK;
+}
+
+int dash_input_labels(dash_ctx* c, int64_t first_wire, dash_labels* zero, void* stream) {
+    if (!c || !zero || first_wire < 0) return DASH_EINVAL;
+    int64_t n = zero->n_elem;
+    if (n < 0 || n > 0x7fffffff) return DASH_ESIZE;
+    int st = check_labels(c, zero, n);
+    if (st) return st;
+    DrawLaunch L;
+    memset(&L, 0, sizeof(L));
+    L.elem_base = (uint64_t)first_wire; L.layer = 0; L.n_elem = (uint32_t)n;
+    for (int i = 0; i < c->k; i++) L.jobs[i] = DrawJob{(uint32_t)c->prime[i], DOM_INPUT, 0, 0, view_of(zero, i)};
+    return launch_draw(c, L, c->k, (hipStream_t)stream);
+}
+
+int dash_encode(dash_ctx* c, const int64_t* values, int64_t n, const dash_labels* zero, dash_labels* out, void* stream) {
+    if (!c || (!values && n > 0) || n < 0) return DASH_EINVAL;
+    if (n > 0x7fffffff) return DASH_ESIZE;
+    int st = check_labels(c, zero, n);
+    if (!st) st = check_labels(c, out, n);
+    if (st) return st;
+    if (n == 0) return DASH_OK;
+    for (int i = 0; i < c->k; i++) {
+        hipLaunchKernelGGL(k_encode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream,
+                           c->d_mods, (uint32_t)c->prime[i], values, (uint32_t)n, view_of(zero, i), view_of(out, i));
+    }
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+int dash_decode(dash_ctx* c, const dash_labels* act, const dash_labels* zero, int64_t n, int64_t* values, uint8_t* valid,
+                void* stream) {
+    if (!c || n < 0 || (n > 0 && (!values || !valid))) return DASH_EINVAL;
+    if (n > 0x7fffffff) return DASH_ESIZE;
+    int st = check_labels(c, act, n);
+    if (!st) st = check_labels(c, zero, n);
+    if (st) return st;
+    if (n == 0) return DASH_OK;
+    DecodeArgs A;
+    memset(&A, 0, sizeof(A));
+    A.mods = c->d_mods; A.k = c->k; A.n = (uint32_t)n; A.P = c->P; A.values = values; A.valid = valid;
+    for (int i = 0; i < c->k; i++) {
+        int p = c->prime[i];
+        uint64_t Ai = c->P / p;
+        A.prime[i] = p;
+        A.crt_coef[i] = (uint64_t)(((u128)Ai * inv_mod((int)(Ai % p), p)) % c->P);
+        A.act[i] = view_of(act, i);
+        A.zero[i] = view_of(zero, i);
+    }
+    hipLaunchKernelGGL(k_decode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream, A);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+int dash_layer_sizes(const dash_ctx* c, const dash_layer* L, int64_t* out_elems, size_t* table_bytes, size_t* scratch_bytes) {
+    if (!c || !L) return DASH_EINVAL;
+    return layer_sizes(c, L, out_elems, table_bytes, scratch_bytes);
+}
+
+static int run_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
+                     uint8_t* scratch, hipStream_t s) {
+    if (!c || !L || !in || !out) return DASH_EINVAL;
+    if (L->layer_id < 0 || L->layer_id > 65535 || L->elem_base < 0 || L->n_elem < 0) return DASH_EINVAL;
+    switch (L->kind) {
+        case DASH_DENSE: case DASH_CONV2D: case DASH_SUMPOOL: return linear_layer(c, L, garble, in, out, s);
+        case DASH_RELU: case DASH_SCALE: case DASH_SIGN: return activation_layer(c, L, garble, in, out, tables, scratch, s);
+        case DASH_PROJ: return proj_layer(c, L, garble, in, out, tables, s);
+    }
+    return DASH_EINVAL;
+}
+
+int dash_garble_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_zero, dash_labels* out_zero, void* tables,
+                      void* scratch, void* stream) {
+    return run_layer(c, L, true, in_zero, out_zero, (uint8_t*)tables, (uint8_t*)scratch, (hipStream_t)stream);
+}
+int dash_eval_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_act, const void* tables, dash_labels* out_act,
+                    void* scratch, void* stream) {
+    return run_layer(c, L, false, in_act, out_act, (uint8_t*)tables, (uint8_t*)scratch, (hipStream_t)stream);
+}
+
+}  // extern "C"

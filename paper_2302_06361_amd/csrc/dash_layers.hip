@@ -1,0 +1,469 @@
+// dash_layers.hip -- the gadget pipelines: approximated sign (Appendix, Approximated Garbled Sign and
+// Garbled Mixed-Radix Addition), ReLU = a * sgn_{0,1}(a) with mixed-modulus half gates (Appendix),
+// CRT scaling by 2 (Sec. The Scaling Operation), sign activation, raw projection-gate batches.
+//
+// Host code only: each pipeline is a fixed sequence of launches of the kernels in dash_gates.hip
+// over all elements of the layer; gates at the same depth of the gadget share one launch.
+#include <string.h>
+
+#include "dash_internal.h"
+
+namespace dash {
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline size_t pitch_of(const dash_ctx* c, int m) { return (size_t)c->mods[m].ndw * 4; }
+inline size_t label_bytes(const dash_ctx* c, int m, int64_t E) { return align256((size_t)c->mods[m].nchunk * 16 * (size_t)E); }
+
+// ---- slots of one sign gadget ---------------------------------------------------------------
+inline int sign_nslots(const dash_ctx* c) { return c->k * c->n + c->n; }
+inline int sign_slot_in(const dash_ctx* c, int s) {
+    int k = c->k, n = c->n;
+    if (s < k * n) return c->prime[s / n];
+    if (s < k * n + n - 1) return c->mj[(s - k * n) + 2];
+    return c->mj[1];
+}
+inline int sign_slot_out(const dash_ctx* c, int s) {
+    int k = c->k, n = c->n;
+    if (s < k * n) return c->mj[(s % n) + 1];
+    if (s < k * n + n - 1) return c->mj[(s - k * n) + 1];
+    return 2;
+}
+inline size_t sign_slot_bytes(const dash_ctx* c, int s, int first_res) {
+    if (s < c->k * c->n && s / c->n < first_res) return 0;
+    return (size_t)sign_slot_in(c, s) * pitch_of(c, sign_slot_out(c, s));
+}
+size_t sign_bytes(const dash_ctx* c, int first_res) {
+    size_t b = 0;
+    for (int s = 0; s < sign_nslots(c); s++) b += sign_slot_bytes(c, s, first_res);
+    return b;
+}
+size_t relu_bytes(const dash_ctx* c) {
+    size_t b = sign_bytes(c, 0);
+    for (int i = 0; i < c->k; i++) b += (size_t)(c->prime[i] + 2) * pitch_of(c, c->prime[i]) + 8;
+    return b;
+}
+size_t scale_bytes(const dash_ctx* c) {
+    size_t b = sign_bytes(c, 1);
+    for (int i = 1; i < c->k; i++) b += 2 * pitch_of(c, c->prime[i]);
+    return b;
+}
+size_t signact_bytes(const dash_ctx* c) {
+    size_t b = sign_bytes(c, 0);
+    for (int i = 0; i < c->k; i++) b += 2 * pitch_of(c, c->prime[i]);
+    return b;
+}
+
+// ---- scratch arena ---------------------------------------------------------------------------
+struct Arena {
+    uint8_t* base;
+    size_t off;
+    LView labels(const dash_ctx* c, int m, int64_t E) {
+        LView v{base ? base + off : nullptr, (int64_t)16 * E, 16u};
+        off += label_bytes(c, m, E);
+        return v;
+    }
+    uint8_t* bytes(size_t n) { uint8_t* p = base ? base + off : nullptr; off += align256(n); return p; }
+};
+
+// wires of one sign gadget
+struct SignWires {
+    LView A[DASH_MAX_PRIMES][DASH_MAX_DIGITS + 1];
+    LView C[DASH_MAX_DIGITS + 1];   // C[j]: carry into digit j (j = 1..n-1)
+    LView bit;
+};
+void plan_sign(const dash_ctx* c, Arena& ar, int64_t E, int first_res, SignWires& w) {
+    for (int i = first_res; i < c->k; i++)
+        for (int j = 1; j <= c->n; j++) w.A[i][j] = ar.labels(c, c->mj[j], E);
+    for (int j = 1; j < c->n; j++) w.C[j] = ar.labels(c, c->mj[j], E);
+    w.bit = ar.labels(c, 2, E);
+}
+
+// ---- launch batchers -------------------------------------------------------------------------
+struct GateBatcher {
+    const dash_ctx* c; bool garble; hipStream_t s;
+    GateLaunch L; int nj = 0, nt = 0, status = DASH_OK;
+    GateBatcher(const dash_ctx* c_, bool g, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_) : c(c_), garble(g), s(s_) {
+        memset(&L, 0, sizeof(L));
+        L.n_elem = E; L.layer = layer; L.elem_base = elem_base;
+    }
+    void add(GateJob J, const Term* t, int n) {
+        if (nj == kMaxJobs || nt + n > kMaxTerms) flush();
+        J.term_first = nt; J.term_count = n;
+        for (int i = 0; i < n; i++) L.terms[nt++] = t[i];
+        L.jobs[nj++] = J;
+    }
+    void flush() {
+        if (nj && status == DASH_OK) status = garble ? launch_garble(c, L, nj, s) : launch_eval(c, L, nj, s);
+        nj = nt = 0;
+    }
+};
+struct DrawBatcher {
+    const dash_ctx* c; hipStream_t s; DrawLaunch L; int nj = 0, status = DASH_OK;
+    DrawBatcher(const dash_ctx* c_, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_) : c(c_), s(s_) {
+        memset(&L, 0, sizeof(L));
+        L.n_elem = E; L.layer = layer; L.elem_base = elem_base;
+    }
+    void add(int m, int domain, uint32_t slot, LView out, bool digit0 = false) {
+        if (nj == kMaxJobs) flush();
+        L.jobs[nj++] = DrawJob{(uint32_t)m, (uint32_t)domain, slot, digit0 ? 1u : 0u, out};
+    }
+    void flush() { if (nj && status == DASH_OK) status = launch_draw(c, L, nj, s); nj = 0; }
+};
+struct AffineBatcher {
+    const dash_ctx* c; hipStream_t s; AffineLaunch L; int nj = 0, nt = 0, status = DASH_OK;
+    AffineBatcher(const dash_ctx* c_, uint32_t E, hipStream_t s_) : c(c_), s(s_) { memset(&L, 0, sizeof(L)); L.n_elem = E; }
+    void add(int m, LView out, const Term* t, int n) {
+        if (nj == kMaxJobs || nt + n > kMaxTerms) flush();
+        L.jobs[nj++] = AffineJob{(uint32_t)m, (uint32_t)nt, (uint32_t)n, 0, out};
+        for (int i = 0; i < n; i++) L.terms[nt++] = t[i];
+    }
+    void flush() { if (nj && status == DASH_OK) status = launch_affine(c, L, nj, s); nj = nt = 0; }
+};
+
+GateJob phi_job(int p, int q, const uint8_t* phi, uint32_t slot, LView out, uint8_t* table) {
+    GateJob J;
+    memset(&J, 0, sizeof(J));
+    J.p = p; J.q = q; J.phi = phi; J.phi_stride = 0; J.slot = slot; J.mode = PAY_PHI; J.out = out; J.table = table;
+    return J;
+}
+
+// One sign gadget over E elements.  x[i]: input residues (i >= first_res).  seg: start of the gadget's
+// first segment inside the layer table (already offset for the element count), offsets per slot follow
+// the slot order.  On return w.bit holds [X >= P/2] (negate = 0) or its complement.
+int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
+              int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s) {
+    const int k = c->k, n = c->n;
+    size_t off[DASH_MAX_PRIMES * DASH_MAX_DIGITS + DASH_MAX_DIGITS], cum = 0;
+    for (int sl = 0; sl < sign_nslots(c); sl++) { off[sl] = cum * E; cum += sign_slot_bytes(c, sl, first_res); }
+
+    if (garble) {   // fresh zero labels of every gate output
+        DrawBatcher db(c, E, layer, elem_base, s);
+        for (int i = first_res; i < k; i++)
+            for (int j = 1; j <= n; j++) db.add(c->mj[j], DOM_GATE, slot_base + i * n + (j - 1), w.A[i][j]);
+        for (int j = n; j >= 2; j--) db.add(c->mj[j - 1], DOM_GATE, slot_base + k * n + (j - 2), w.C[j - 1]);
+        db.add(2, DOM_GATE, slot_base + k * n + n - 1, w.bit);
+        db.flush();
+        if (db.status) return db.status;
+    }
+    GateBatcher gb(c, garble, E, layer, elem_base, s);
+    // digit gates: residue i -> digit j of its rounded CRT fraction
+    for (int i = first_res; i < k; i++)
+        for (int j = 1; j <= n; j++) {
+            int sl = i * n + (j - 1);
+            Term t{x[i], 1};
+            gb.add(phi_job(c->prime[i], c->mj[j], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]), &t, 1);
+        }
+    gb.flush();
+    // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
+    for (int j = n; j >= 1; j--) {
+        Term t[kMaxTerms];
+        int nt = 0;
+        for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
+        if (j < n) t[nt++] = Term{w.C[j], 1};
+        if (j >= 2) {
+            int sl = k * n + (j - 2);
+            gb.add(phi_job(c->mj[j], c->mj[j - 1], c->phi_carry[j], slot_base + sl, w.C[j - 1], seg + off[sl]), t, nt);
+        } else {
+            int sl = k * n + n - 1;
+            gb.add(phi_job(c->mj[1], 2, c->phi_final[negate], slot_base + sl, w.bit, seg + off[sl]), t, nt);
+        }
+        gb.flush();
+    }
+    return gb.status;
+}
+
+int check_bundle(const dash_ctx* c, const dash_labels* t, int64_t n) {
+    if (!t || t->n_elem < n) return DASH_EINVAL;
+    for (int i = 0; i < c->k; i++)
+        if (!t->data[i] || ((uintptr_t)t->data[i] & 15) || (t->chunk_stride[i] & 15) || t->chunk_stride[i] < 16 * n) return DASH_EINVAL;
+    return DASH_OK;
+}
+
+// ---- ReLU ------------------------------------------------------------------------------------
+struct ReluPlan { SignWires w; LView U[DASH_MAX_PRIMES], V[DASH_MAX_PRIMES]; uint8_t* r[DASH_MAX_PRIMES]; };
+void plan_relu(const dash_ctx* c, Arena& ar, int64_t E, ReluPlan& p) {
+    plan_sign(c, ar, E, 0, p.w);
+    for (int i = 0; i < c->k; i++) {
+        p.U[i] = ar.labels(c, c->prime[i], E);
+        p.V[i] = ar.labels(c, c->prime[i], E);
+        p.r[i] = ar.bytes((size_t)E);
+    }
+}
+
+int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
+               uint8_t* scratch, hipStream_t s) {
+    const int k = c->k, ns = sign_nslots(c);
+    const uint32_t E = (uint32_t)L->n_elem, layer = (uint32_t)L->layer_id;
+    const uint64_t eb = (uint64_t)L->elem_base;
+    Arena ar{scratch, 0};
+    ReluPlan pl;
+    plan_relu(c, ar, E, pl);
+    LView x[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) x[i] = view_of(in, i);
+    // pos = [X < P/2]
+    int st = sign_core(c, garble, E, layer, eb, x, 0, 1, 0, tables, pl.w, s);
+    if (st) return st;
+    size_t cum = sign_bytes(c, 0);
+    uint8_t *G[DASH_MAX_PRIMES], *Eh[DASH_MAX_PRIMES], *S[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) {
+        size_t pit = pitch_of(c, c->prime[i]);
+        G[i] = tables + cum * E; cum += c->prime[i] * pit;
+        Eh[i] = tables + cum * E; cum += 2 * pit;
+        S[i] = tables + cum * E; cum += 8;
+    }
+    if (garble) {
+        DrawBatcher db(c, E, layer, eb, s);
+        for (int i = 0; i < k; i++) {
+            db.add(c->prime[i], DOM_GATE, ns + 3 * i, pl.U[i]);
+            db.add(c->prime[i], DOM_GATE, ns + 3 * i + 1, pl.V[i]);
+            db.add(c->prime[i], DOM_MASK, ns + 3 * i, LView{pl.r[i], 0, 1}, true);
+        }
+        db.flush();
+        if (db.status) return db.status;
+        GateBatcher gb(c, true, E, layer, eb, s);
+        for (int i = 0; i < k; i++) {
+            int p = c->prime[i];
+            Term tx{x[i], 1}, ty{pl.w.bit, 1};
+            GateJob J = phi_job(p, p, nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
+            J.mode = PAY_MULR; J.r = pl.r[i];
+            gb.add(J, &tx, 1);
+            J = phi_job(2, p, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]);              // evaluator half: -(b+r)*x0
+            J.mode = PAY_EHALF; J.r = pl.r[i]; J.x0 = x[i];
+            gb.add(J, &ty, 1);
+            J = phi_job(2, p, nullptr, ns + 3 * i + 2, pl.V[i], S[i]);               // b + r for the evaluator
+            J.mode = PAY_SHORT; J.r = pl.r[i];
+            gb.add(J, &ty, 1);
+        }
+        gb.flush();
+        if (gb.status) return gb.status;
+        AffineBatcher ab(c, E, s);                                                    // zero label of the product: V0 - U0
+        for (int i = 0; i < k; i++) {
+            Term t[2] = {Term{pl.V[i], 1}, Term{pl.U[i], (uint32_t)c->prime[i] - 1}};
+            ab.add(c->prime[i], view_of(out, i), t, 2);
+        }
+        ab.flush();
+        return ab.status;
+    }
+    GateBatcher gb(c, false, E, layer, eb, s);
+    for (int i = 0; i < k; i++) {
+        int p = c->prime[i];
+        Term tx{x[i], 1}, ty{pl.w.bit, 1};
+        gb.add(phi_job(p, p, nullptr, ns + 3 * i, pl.U[i], G[i]), &tx, 1);
+        gb.add(phi_job(2, p, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]), &ty, 1);
+    }
+    gb.flush();
+    if (gb.status) return gb.status;
+    HgLaunch H;
+    memset(&H, 0, sizeof(H));
+    H.n_elem = E; H.layer = layer; H.elem_base = eb;
+    int nj = 0;
+    for (int i = 0; i < k; i++) {
+        H.jobs[nj++] = HgJob{(uint32_t)c->prime[i], (uint32_t)(ns + 3 * i + 2), x[i], pl.w.bit, pl.U[i], pl.V[i], view_of(out, i), S[i]};
+    }
+    return launch_hg_finish(c, H, nj, s);
+}
+
+// ---- sign activation -------------------------------------------------------------------------
+int signact_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
+                  uint8_t* scratch, hipStream_t s) {
+    const int k = c->k, ns = sign_nslots(c);
+    const uint32_t E = (uint32_t)L->n_elem, layer = (uint32_t)L->layer_id;
+    const uint64_t eb = (uint64_t)L->elem_base;
+    Arena ar{scratch, 0};
+    SignWires w;
+    plan_sign(c, ar, E, 0, w);
+    LView x[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) x[i] = view_of(in, i);
+    int st = sign_core(c, garble, E, layer, eb, x, 0, 0, 0, tables, w, s);
+    if (st) return st;
+    if (garble) {
+        DrawBatcher db(c, E, layer, eb, s);
+        for (int i = 0; i < k; i++) db.add(c->prime[i], DOM_GATE, ns + i, view_of(out, i));
+        db.flush();
+        if (db.status) return db.status;
+    }
+    size_t cum = sign_bytes(c, 0);
+    GateBatcher gb(c, garble, E, layer, eb, s);
+    for (int i = 0; i < k; i++) {
+        Term t{w.bit, 1};
+        gb.add(phi_job(2, c->prime[i], c->phi_pm1[i], ns + i, view_of(out, i), tables + cum * E), &t, 1);
+        cum += 2 * pitch_of(c, c->prime[i]);
+    }
+    gb.flush();
+    return gb.status;
+}
+
+// ---- scaling by 2, `repeat` times ------------------------------------------------------------
+struct ScalePlan { LView buf[2][DASH_MAX_PRIMES]; LView up, cast[DASH_MAX_PRIMES], b[DASH_MAX_PRIMES]; SignWires w; };
+void plan_scale(const dash_ctx* c, Arena& ar, int64_t E, ScalePlan& p) {
+    for (int t = 0; t < 2; t++)
+        for (int i = 0; i < c->k; i++) p.buf[t][i] = ar.labels(c, c->prime[i], E);
+    p.up = ar.labels(c, 2, E);
+    for (int i = 1; i < c->k; i++) { p.cast[i] = ar.labels(c, c->prime[i], E); p.b[i] = ar.labels(c, c->prime[i], E); }
+    plan_sign(c, ar, E, 1, p.w);
+}
+
+int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
+                uint8_t* scratch, hipStream_t s) {
+    const int k = c->k, ns = sign_nslots(c);
+    if (c->prime[0] != 2 || k < 2) return DASH_EUNSUPPORTED;
+    if (L->repeat < 1) return DASH_EINVAL;
+    const uint32_t E = (uint32_t)L->n_elem, layer = (uint32_t)L->layer_id;
+    const uint64_t eb = (uint64_t)L->elem_base;
+    Arena ar{scratch, 0};
+    ScalePlan pl;
+    plan_scale(c, ar, E, pl);
+    const size_t bpe = scale_bytes(c);
+    const uint32_t slots_per_rep = (uint32_t)(k - 1 + ns);
+    // constant-one wires: zero labels for the garbler, active labels for the evaluator
+    LView one[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) one[i] = LView{garble ? c->d_one0[i] : c->d_one[i], 16, 0u};
+    const uint64_t quarter = c->P / 4;
+
+    LView cur[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) cur[i] = view_of(in, i);
+    for (int rep = 0; rep < L->repeat; rep++) {
+        uint8_t* tb = tables + (size_t)rep * bpe * E;
+        const uint32_t sb = rep * slots_per_rep;
+        LView nxt[DASH_MAX_PRIMES];
+        for (int i = 0; i < k; i++) nxt[i] = (rep == L->repeat - 1) ? view_of(out, i) : pl.buf[rep & 1][i];
+        // (1) ShiftUp: + P/2, i.e. +1 on the mod-2 residue only
+        {
+            AffineBatcher ab(c, E, s);
+            Term t[2] = {Term{cur[0], 1}, Term{one[0], 1}};
+            ab.add(2, pl.up, t, 2);
+            ab.flush();
+            if (ab.status) return ab.status;
+        }
+        // (2) cast the mod-2 residue into every odd prime, b_i = (x_i - cast_i) / 2
+        if (garble) {
+            DrawBatcher db(c, E, layer, eb, s);
+            for (int i = 1; i < k; i++) db.add(c->prime[i], DOM_GATE, sb + (i - 1), pl.cast[i]);
+            db.flush();
+            if (db.status) return db.status;
+        }
+        size_t cum = 0;
+        {
+            GateBatcher gb(c, garble, E, layer, eb, s);
+            for (int i = 1; i < k; i++) {
+                Term t{pl.up, 1};
+                gb.add(phi_job(2, c->prime[i], c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E), &t, 1);
+                cum += 2 * pitch_of(c, c->prime[i]);
+            }
+            gb.flush();
+            if (gb.status) return gb.status;
+            AffineBatcher ab(c, E, s);
+            for (int i = 1; i < k; i++) {
+                uint32_t p = c->prime[i], inv2 = (p + 1) / 2;
+                Term t[2] = {Term{cur[i], inv2}, Term{pl.cast[i], p - inv2}};
+                ab.add(p, pl.b[i], t, 2);
+            }
+            ab.flush();
+            if (ab.status) return ab.status;
+        }
+        // (3) base extension: [value of (0, b_1..b_{k-1}) >= P/2] is the mod-2 residue of the halved value
+        int st = sign_core(c, garble, E, layer, eb, pl.b, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s);
+        if (st) return st;
+        // (4) ShiftDown: - floor(P/4)
+        {
+            AffineBatcher ab(c, E, s);
+            Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], (uint32_t)((2 - quarter % 2) % 2)}};
+            ab.add(2, nxt[0], t0, 2);
+            for (int i = 1; i < k; i++) {
+                uint32_t p = c->prime[i];
+                Term t[2] = {Term{pl.b[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};
+                ab.add(p, nxt[i], t, 2);
+            }
+            ab.flush();
+            if (ab.status) return ab.status;
+        }
+        for (int i = 0; i < k; i++) cur[i] = nxt[i];
+    }
+    return DASH_OK;
+}
+
+}  // namespace
+
+int layer_sizes(const dash_ctx* c, const dash_layer* L, int64_t* out_elems, size_t* table_bytes, size_t* scratch_bytes) {
+    int64_t oe = 0;
+    size_t tb = 0, sb = 0;
+    const int64_t E = L->n_elem;
+    if (E < 0) return DASH_EINVAL;
+    Arena ar{nullptr, 0};
+    switch (L->kind) {
+        case DASH_DENSE:
+            if (L->in_c < 1 || L->out_c < 1) return DASH_EINVAL;
+            oe = L->out_c; break;
+        case DASH_CONV2D: {
+            if (L->in_c < 1 || L->out_c < 1 || L->kh < 1 || L->kw < 1 || L->stride < 1 || L->pad < 0) return DASH_EINVAL;
+            int oh = (L->in_h + 2 * L->pad - L->kh) / L->stride + 1, ow = (L->in_w + 2 * L->pad - L->kw) / L->stride + 1;
+            if (oh < 1 || ow < 1) return DASH_EINVAL;
+            oe = (int64_t)oh * ow * L->out_c; break;
+        }
+        case DASH_SUMPOOL:
+            if (L->in_h < 2 || L->in_w < 2 || L->in_c < 1) return DASH_EINVAL;
+            oe = (int64_t)(L->in_h / 2) * (L->in_w / 2) * L->in_c; break;
+        case DASH_RELU: { ReluPlan p; plan_relu(c, ar, E, p); oe = E; tb = relu_bytes(c) * (size_t)E; sb = ar.off; break; }
+        case DASH_SIGN: { SignWires w; plan_sign(c, ar, E, 0, w); oe = E; tb = signact_bytes(c) * (size_t)E; sb = ar.off; break; }
+        case DASH_SCALE: {
+            if (L->repeat < 1) return DASH_EINVAL;
+            ScalePlan p; plan_scale(c, ar, E, p); oe = E; tb = scale_bytes(c) * (size_t)E * (size_t)L->repeat; sb = ar.off; break;
+        }
+        case DASH_PROJ: {
+            if (L->p_index < 0 || L->p_index >= c->k || L->q_index < 0 || L->q_index >= c->k) return DASH_EINVAL;
+            oe = E; tb = (size_t)E * c->prime[L->p_index] * pitch_of(c, c->prime[L->q_index]); break;
+        }
+        default: return DASH_EINVAL;
+    }
+    if (out_elems) *out_elems = oe;
+    if (table_bytes) *table_bytes = tb;
+    if (scratch_bytes) *scratch_bytes = sb;
+    return DASH_OK;
+}
+
+int activation_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
+                     uint8_t* scratch, hipStream_t s) {
+    if (L->n_elem > 0x7fffffff) return DASH_ESIZE;
+    if (L->n_elem == 0) return DASH_OK;
+    if (c->k > 15) return DASH_EUNSUPPORTED;     // a carry gate sums k digit wires and a carry in one launch
+    int st = check_bundle(c, in, L->n_elem);
+    if (!st) st = check_bundle(c, out, L->n_elem);
+    if (st) return st;
+    if (!tables || !scratch || ((uintptr_t)tables & 3) || ((uintptr_t)scratch & 255)) return DASH_EINVAL;
+    switch (L->kind) {
+        case DASH_RELU: return relu_layer(c, L, garble, in, out, tables, scratch, s);
+        case DASH_SIGN: return signact_layer(c, L, garble, in, out, tables, scratch, s);
+        case DASH_SCALE: return scale_layer(c, L, garble, in, out, tables, scratch, s);
+    }
+    return DASH_EINVAL;
+}
+
+// n independent gates Z_p -> Z_q with per-gate function tables (the projection-gate microbenchmark)
+int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables, hipStream_t s) {
+    if (L->n_elem > 0x7fffffff) return DASH_ESIZE;
+    if (L->n_elem == 0) return DASH_OK;
+    if (L->p_index < 0 || L->p_index >= c->k || L->q_index < 0 || L->q_index >= c->k) return DASH_EINVAL;
+    if (!L->phi || !tables || ((uintptr_t)tables & 3)) return DASH_EINVAL;
+    const int pi = L->p_index, qi = L->q_index, p = c->prime[pi], q = c->prime[qi];
+    if (L->phi_stride != 0 && L->phi_stride != p) return DASH_EINVAL;
+    if (!in->data[pi] || !out->data[qi] || in->n_elem < L->n_elem || out->n_elem < L->n_elem) return DASH_EINVAL;
+    if (((uintptr_t)in->data[pi] & 15) || ((uintptr_t)out->data[qi] & 15) || (in->chunk_stride[pi] & 15) || (out->chunk_stride[qi] & 15) ||
+        in->chunk_stride[pi] < 16 * L->n_elem || out->chunk_stride[qi] < 16 * L->n_elem) return DASH_EINVAL;
+    const uint32_t E = (uint32_t)L->n_elem;
+    if (garble) {
+        DrawBatcher db(c, E, L->layer_id, L->elem_base, s);
+        db.add(q, DOM_GATE, 0, view_of(out, qi));
+        db.flush();
+        if (db.status) return db.status;
+    }
+    GateBatcher gb(c, garble, E, L->layer_id, L->elem_base, s);
+    Term t{view_of(in, pi), 1};
+    GateJob J = phi_job(p, q, L->phi, 0, view_of(out, qi), tables);
+    J.phi_stride = (uint32_t)L->phi_stride;
+    gb.add(J, &t, 1);
+    gb.flush();
+    return gb.status;
+}
+
+}  // namespace dash

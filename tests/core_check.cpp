@@ -1,0 +1,58 @@
+// Host build of the kernels' per-lane arithmetic (dash_core.h + dash_hostconst.h) so that the CPU test
+// suite can compare it with the oracle before anything runs on a GPU.  Test code, not part of libdash.
+#include <stdint.h>
+#include <string.h>
+
+#include "../paper_2302_06361_amd/csrc/dash_hostconst.h"
+
+using namespace dash;
+using namespace dash::hostconst;
+
+namespace {
+uint32_t TT[1024];
+bool ready = false;
+uint8_t SB[256];
+struct HostTab { uint32_t operator()(int r, uint32_t x) const { return TT[r * 256 + x]; } };
+void init() { if (!ready) { make_sbox(SB); make_ttab(SB, TT); ready = true; } }
+uint32_t pack_dw(const uint8_t* lab, uint32_t lam, int i) {
+    uint32_t w = 0;
+    for (int b = 0; b < 4; b++) if ((uint32_t)(4 * i + b) < lam) w |= (uint32_t)lab[4 * i + b] << (8 * b);
+    return w;
+}
+}  // namespace
+
+extern "C" {
+int cc_lambda(int m, int rule) { return label_length(m, rule); }
+
+// H_q(label, tweak) with the fixed key 00..0f
+void cc_hash(const uint8_t* label, int p, int q, int rule, uint64_t elem, uint32_t slot, uint32_t layer, uint8_t* out, uint32_t* colour) {
+    init();
+    ModInfo Mp, Mq;
+    fill_modinfo(Mp, p, rule);
+    fill_modinfo(Mq, q, rule);
+    uint8_t key[16];
+    for (int i = 0; i < 16; i++) key[i] = (uint8_t)i;
+    uint32_t rk[44];
+    expand_key(key, SB, rk);
+    U128 K = compress(Mp, [&](int i) { return pack_dw(label, Mp.lam, i); }, colour);
+    U128 h = hash_block(K, elem, slot, layer, rk, HostTab());
+    memset(out, 0, Mq.ndw * 4);
+    decompress(Mq, h, [&](int i, uint32_t w) { memcpy(out + 4 * i, &w, 4); });
+}
+void cc_draw(const uint8_t seed[16], int domain, uint32_t layer, uint32_t slot, uint64_t elem, int m, int rule, uint8_t* out, uint32_t* digit0) {
+    init();
+    ModInfo M;
+    fill_modinfo(M, m, rule);
+    uint32_t rk[44];
+    expand_key(seed, SB, rk);
+    U128 h = prg_block(elem, slot, layer, domain, m, rk, HostTab());
+    memset(out, 0, M.ndw * 4);
+    decompress(M, h, [&](int i, uint32_t w) { memcpy(out + 4 * i, &w, 4); });
+    *digit0 = mod_u128(h, M);
+}
+// packed-digit arithmetic on one dword
+uint32_t cc_addmod4(uint32_t a, uint32_t b, int m) { ModInfo M; fill_modinfo(M, m, 0); return addmod4(a, b, M); }
+uint32_t cc_submod4(uint32_t a, uint32_t b, int m) { ModInfo M; fill_modinfo(M, m, 0); return submod4(a, b, M); }
+uint32_t cc_axpymod4(uint32_t a, uint32_t c, uint32_t b, int m) { ModInfo M; fill_modinfo(M, m, 0); return axpymod4(a, c, b, M); }
+uint32_t cc_mod_m(uint32_t n, int m) { ModInfo M; fill_modinfo(M, m, 0); return mod_m(n, M); }
+}

@@ -1,0 +1,82 @@
+"""GPU parity: batches of projection gates (garble and eval) through the C ABI against the oracle,
+bit-exact on output zero labels, ciphertext tables and evaluated labels."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import both, upload_bundle, assert_tables_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def run_proj(ctx, orc, pi, qi, n, seed, layer=9, elem_base=10 ** 9, shared_phi=False):
+    from paper_2302_06361_amd import Labels, Layer, PROJ
+    p, q = orc.primes[pi], orc.primes[qi]
+    g = np.random.default_rng(seed)
+    in0 = workloads.uniform_labels(g, n, orc.lam(p), p)
+    phi = workloads.proj_phi(g, 1 if shared_phi else n, p, q)
+    a = g.integers(0, p, n)
+    act = ((in0.astype(np.int64) + a[:, None] * orc.delta(p).astype(np.int64)[None, :]) % p).astype(np.uint8)
+    # GPU
+    tin0, tact = Labels(ctx, n, only=[pi]), Labels(ctx, n, only=[pi])
+    tin0.from_numpy(pi, in0)
+    tact.from_numpy(pi, act)
+    tout0, tout = Labels(ctx, n, only=[qi], zero=True), Labels(ctx, n, only=[qi], zero=True)
+    phid = torch.as_tensor(phi).to(ctx.device)
+    lay = Layer(PROJ, layer, n, elem_base=elem_base, p_index=pi, q_index=qi, phi=phid, phi_stride=0 if shared_phi else p)
+    oe, tb, sb = ctx.layer_sizes(lay)
+    assert oe == n and tb == n * p * ctx.pitch(q) and sb == 0
+    tables = torch.zeros(tb, dtype=torch.uint8, device=ctx.device)
+    ctx.garble_layer(lay, tin0, tout0, tables)
+    ctx.eval_layer(lay, tact, tables, tout)
+    torch.cuda.synchronize()
+    # oracle
+    rout0, rtable = orc.proj_garble(p, q, in0, phi[0] if shared_phi else phi, layer, 0, elem_base)
+    rout = orc.proj_eval(p, q, act, rtable, layer, 0, elem_base)
+    assert (tout0.to_numpy(qi) == rout0).all(), "output zero labels"
+    assert tout0.pad_is_zero(qi)
+    assert_tables_equal(tables, rtable.reshape(-1), "tables %d->%d" % (p, q))
+    assert (tout.to_numpy(qi) == rout).all(), "evaluated labels"
+    assert tout.pad_is_zero(qi)
+    # and the result is the label of phi(a)
+    f = (phi[0][a] if shared_phi else phi[np.arange(n), a]).astype(np.int64)
+    want = (rout0.astype(np.int64) + f[:, None] * orc.delta(q).astype(np.int64)[None, :]) % q
+    assert (rout == want).all()
+
+
+@pytest.mark.parametrize("pi,qi", [(0, 0), (0, 11), (1, 1), (11, 0), (11, 11), (5, 7), (2, 3), (7, 4), (10, 9), (3, 1)])
+def test_projection_gates_pairs(pi, qi):
+    ctx, orc = both(12)
+    run_proj(ctx, orc, pi, qi, 777, seed=pi * 12 + qi)      # three blocks and a ragged tail
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 256, 257, 2500])
+def test_projection_gates_sizes(n):
+    ctx, orc = both(12)
+    run_proj(ctx, orc, 6, 2, n, seed=n)
+
+
+def test_projection_gates_floor_rule_and_shared_table():
+    ctx, orc = both(12, rule=1)
+    run_proj(ctx, orc, 4, 8, 300, seed=1)
+    run_proj(ctx, orc, 1, 5, 300, seed=2, shared_phi=True)
+
+
+def test_projection_gates_empty_batch():
+    from paper_2302_06361_amd import Labels, Layer, PROJ
+    ctx, orc = both(12)
+    t = Labels(ctx, 0, only=[1, 2])
+    phid = torch.zeros(3, dtype=torch.uint8, device=ctx.device)
+    lay = Layer(PROJ, 1, 0, p_index=1, q_index=2, phi=phid, phi_stride=3)
+    assert ctx.layer_sizes(lay) == (0, 0, 0)
+    ctx.garble_layer(lay, t, t, None)
+    ctx.eval_layer(lay, t, None, t)
+    torch.cuda.synchronize()
+
+
+def test_projection_all_144_pairs_small():
+    ctx, orc = both(12)
+    for pi in range(12):
+        for qi in range(12):
+            run_proj(ctx, orc, pi, qi, 70, seed=1000 + pi * 12 + qi, elem_base=2 ** 33 + 5)

@@ -1,0 +1,80 @@
+"""GPU parity: context constants, input labels, En, De (through the C ABI, against the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import both, upload_bundle, assert_bundle_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("k,rule", [(3, 0), (5, 1), (8, 0), (12, 0), (12, 1)])
+def test_context_constants(k, rule):
+    ctx, orc = both(k, rule)
+    assert ctx.digits == list(workloads.DIGITS[k])
+    moduli = set(ctx.primes) | {2} | {orc.mj(j) for j in range(1, orc.n + 1)}
+    for m in sorted(moduli):
+        assert ctx.lam(m) == orc.lam(m)
+        assert (ctx.offset(m) == orc.delta(m)).all(), m
+    for i in range(k):
+        assert (ctx.one(i, 0) == orc.one0(i)).all()
+        assert (ctx.one(i, 1) == orc.one(i)).all()
+
+
+@pytest.mark.parametrize("n", [0, 1, 255, 256, 1000])
+def test_input_labels_encode_decode(n):
+    from paper_2302_06361_amd import Labels
+    ctx, orc = both(8)
+    zero, act = Labels(ctx, n, zero=True), Labels(ctx, n, zero=True)
+    ctx.input_labels(12345, zero)
+    g = np.random.default_rng(n)
+    x = g.integers(-2 ** 40, 2 ** 40, n)
+    xd = torch.as_tensor(x).to(ctx.device)
+    ctx.encode(xd, zero, act)
+    values = torch.zeros(n, dtype=torch.int64, device=ctx.device)
+    valid = torch.zeros(n, dtype=torch.uint8, device=ctx.device)
+    ctx.decode(act, zero, values, valid)
+    torch.cuda.synchronize()
+    if n == 0:
+        return
+    ref0 = [orc.input_labels(12345, n, i) for i in range(8)]
+    ref1 = [orc.encode(i, x, ref0[i]) for i in range(8)]
+    assert_bundle_equal(zero, ref0, "input zero labels")
+    assert_bundle_equal(act, ref1, "encoded labels")
+    rv, rok = orc.decode(ref1, ref0)
+    assert (values.cpu().numpy() == rv).all() and (valid.cpu().numpy() == rok).all() and rok.all()
+
+
+def test_decode_flags_forged_labels():
+    ctx, orc = both(5)
+    n = 300
+    g = np.random.default_rng(1)
+    x = g.integers(0, orc.P, n)
+    ref0 = [orc.input_labels(0, n, i) for i in range(5)]
+    ref1 = [orc.encode(i, x, ref0[i]) for i in range(5)]
+    forged = [a.copy() for a in ref1]
+    for e, i, j in [(3, 0, 127), (77, 2, 0), (299, 4, 10), (150, 1, 80)]:
+        p = orc.primes[i]
+        forged[i][e, j] = (forged[i][e, j] + 1) % p
+    zero, act = upload_bundle(ctx, ref0), upload_bundle(ctx, forged)
+    values = torch.zeros(n, dtype=torch.int64, device=ctx.device)
+    valid = torch.zeros(n, dtype=torch.uint8, device=ctx.device)
+    ctx.decode(act, zero, values, valid)
+    rv, rok = orc.decode(forged, ref0)
+    assert (valid.cpu().numpy() == rok).all() and rok.sum() == n - 4
+    assert (values.cpu().numpy() == rv).all()
+
+
+def test_bad_arguments_are_refused():
+    from paper_2302_06361_amd import Labels, DashError, Context
+    ctx, _ = both(3)
+    zero = Labels(ctx, 10)
+    small = Labels(ctx, 4)
+    x = torch.zeros(10, dtype=torch.int64, device=ctx.device)
+    with pytest.raises(DashError):
+        ctx.encode(x, zero, small)          # output tensor too small
+    with pytest.raises(DashError):
+        Context([2, 4, 5], bytes(16))       # 4 is not prime
+    with pytest.raises(DashError):
+        Context([2, 3, 5], bytes(16), digits=[3, 5, 9])    # d_1 must be even

@@ -1,0 +1,84 @@
+"""GPU parity: ReLU, scaling and sign-activation layers through the C ABI against the oracle: output
+labels (garbler's zero labels and evaluator's active labels) and every ciphertext byte."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import both, upload_bundle, assert_bundle_equal, assert_tables_equal
+from oracle import plain
+
+pytestmark = pytest.mark.gpu
+
+
+def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500):
+    from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN
+    ctx, orc = both(k, rule)
+    n = len(X)
+    zero = [orc.input_labels(first_wire, n, i) for i in range(k)]
+    act = [orc.encode(i, np.asarray(X), zero[i]) for i in range(k)]
+    if kind == "relu":
+        r0, rt = orc.relu_garble(layer, zero, elem_base)
+        r = orc.relu_eval(layer, act, rt, elem_base)
+        lay = Layer(RELU, layer, n, elem_base=elem_base)
+        want = plain.relu(X, orc.P)
+    elif kind == "scale":
+        r0, rt = orc.scale_garble(layer, zero, repeat, elem_base)
+        r = orc.scale_eval(layer, act, rt, repeat, elem_base)
+        lay = Layer(SCALE, layer, n, elem_base=elem_base, repeat=repeat)
+        want = plain.scale(X, orc.P, repeat)
+    else:
+        r0, rt = orc.signact_garble(layer, zero, elem_base)
+        r = orc.signact_eval(layer, act, rt, elem_base)
+        lay = Layer(SIGN, layer, n, elem_base=elem_base)
+        want = plain.sign_act(X, orc.P)
+    oe, tb, sb = ctx.layer_sizes(lay)
+    assert oe == n and tb == rt.size
+    tz, ta = upload_bundle(ctx, zero), upload_bundle(ctx, act)
+    oz, oa = Labels(ctx, n, zero=True), Labels(ctx, n, zero=True)
+    tables = torch.zeros(max(tb, 4), dtype=torch.uint8, device=ctx.device)[:tb]
+    scratch = torch.zeros(sb + 256, dtype=torch.uint8, device=ctx.device)
+    ctx.garble_layer(lay, tz, oz, tables, scratch)
+    scratch.fill_(0xA5)       # the evaluator must not depend on what the garbler left in scratch
+    ctx.eval_layer(lay, ta, tables, oa, scratch)
+    torch.cuda.synchronize()
+    assert_bundle_equal(oz, r0, kind + " zero labels")
+    assert_tables_equal(tables, rt, kind + " tables")
+    assert_bundle_equal(oa, r, kind + " active labels")
+    vals, valid = orc.decode(r, r0)
+    assert valid.all() and (vals == plain.to_signed(want, orc.P)).all()
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+@pytest.mark.parametrize("kind", ["relu", "scale", "sign"])
+def test_activation_every_value_small_bases(k, kind):
+    P = int(np.prod(workloads.PRIMES[:k]))
+    run_activation(k, kind, np.arange(P))
+
+
+@pytest.mark.parametrize("kind,repeat", [("relu", 1), ("scale", 1), ("scale", 6), ("sign", 1)])
+def test_activation_base8(kind, repeat):
+    P = int(np.prod(workloads.PRIMES[:8]))
+    g = np.random.default_rng(8)
+    X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P // 2 + 1, P - 1], g.integers(0, P, 295)])   # 301: two blocks, ragged
+    run_activation(8, kind, X, repeat=repeat, elem_base=123456789)
+
+
+@pytest.mark.parametrize("kind,repeat", [("relu", 1), ("scale", 2)])
+def test_activation_base12(kind, repeat):
+    P = int(np.prod(workloads.PRIMES[:12]))
+    g = np.random.default_rng(12)
+    X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], g.integers(0, P, 95)])
+    run_activation(12, kind, X, repeat=repeat, elem_base=2 ** 32 + 7)
+
+
+def test_activation_floor_rule():
+    P = int(np.prod(workloads.PRIMES[:5]))
+    g = np.random.default_rng(5)
+    run_activation(5, "relu", g.integers(0, P, 130), rule=1)
+    run_activation(5, "scale", g.integers(0, P, 130), repeat=2, rule=1)
+
+
+def test_activation_single_element():
+    run_activation(8, "relu", np.array([12345]))
+    run_activation(8, "scale", np.array([9699689]), repeat=3)
