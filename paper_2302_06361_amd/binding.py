@@ -18,7 +18,7 @@ LAMBDA_CEIL, LAMBDA_FLOOR = 0, 1
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_input_labels", "dash_encode", "dash_decode", "dash_strerror"]
+           "dash_input_labels", "dash_encode", "dash_decode", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
 
 
 class DashError(RuntimeError):
@@ -189,6 +189,15 @@ class Context:
         out = np.zeros(self.lam(self.primes[i]), np.uint8)
         _check(self.L.dash_ctx_one(self.h, int(i), int(which), out.ctypes.data_as(C.c_void_p)), "dash_ctx_one")
         return out
+
+    def profile_enable(self, on):
+        _check(self.L.dash_profile_enable(self.h, int(on)), "dash_profile_enable")
+
+    def profile_read(self, kind):
+        """-> dict(ms, launches, units, bytes) summed over the launches since the last read"""
+        ms, n, u, b = C.c_double(), C.c_int64(), C.c_double(), C.c_double()
+        _check(self.L.dash_profile_read(self.h, int(kind), C.byref(ms), C.byref(n), C.byref(u), C.byref(b)), "dash_profile_read")
+        return dict(ms=ms.value, launches=n.value, units=u.value, bytes=b.value)
 
     # ---- the ABI calls, same names -------------------------------------------------------------
     def layer_sizes(self, layer):

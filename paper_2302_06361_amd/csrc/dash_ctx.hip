@@ -143,6 +143,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     if (!c) return DASH_EINVAL;
     memset(c, 0, sizeof(*c));
     c->device = hip_device; c->k = k; c->rule = lambda_rule;
+    c->prof = new (std::nothrow) ProfState();
     c->P = 1;
     for (int i = 0; i < k; i++) { c->prime[i] = primes[i]; c->P *= primes[i]; }
 
@@ -296,7 +297,37 @@ void dash_ctx_destroy(dash_ctx* c) {
     if (c->d_pool) (void)hipFree(c->d_pool);
     if (c->d_mods) (void)hipFree(c->d_mods);
     if (c->d_ttab) (void)hipFree(c->d_ttab);
+    if (c->prof) {
+        for (int kd = 0; kd < DASH_PROF_KINDS; kd++)
+            for (auto& r : c->prof->rec[kd]) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (auto e : c->prof->pool) (void)hipEventDestroy(e);
+        delete c->prof;
+    }
     delete c;
+}
+
+int dash_profile_enable(dash_ctx* c, int on) {
+    if (!c || !c->prof) return DASH_EINVAL;
+    c->prof->on = on != 0;
+    return DASH_OK;
+}
+int dash_profile_read(dash_ctx* c, int kind, double* ms, int64_t* launches, double* units, double* alg_bytes) {
+    if (!c || !c->prof || kind < 0 || kind >= DASH_PROF_KINDS) return DASH_EINVAL;
+    double t = 0, u = 0, b = 0;
+    auto& v = c->prof->rec[kind];
+    for (auto& r : v) {
+        DASH_HIP(hipEventSynchronize(r.b));
+        float dt = 0;
+        DASH_HIP(hipEventElapsedTime(&dt, r.a, r.b));
+        t += dt; u += r.units; b += r.bytes;
+        c->prof->pool.push_back(r.a); c->prof->pool.push_back(r.b);
+    }
+    if (ms) *ms = t;
+    if (launches) *launches = (int64_t)v.size();
+    if (units) *units = u;
+    if (alg_bytes) *alg_bytes = b;
+    v.clear();
+    return DASH_OK;
 }
 
 int dash_lambda(const dash_ctx* c, int m) { return (c && m >= 2 && m <= 255) ? (int)c->mods[m].lam : 0; }

@@ -151,6 +151,14 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     uint64_t blocks = (rows + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffull) return DASH_ESIZE;
     dim3 grid((uint32_t)blocks, njobs);
+    double units = 0, bytes = 0;
+    for (int j = 0; j < njobs; j++) {
+        const GateJob& J = L.jobs[j];
+        double lp = c->mods[J.p].lam, lq = J.mode == PAY_SHORT ? 1 : c->mods[J.q].lam;
+        units += (double)L.n_elem * J.p;
+        bytes += (double)L.n_elem * (J.term_count * lp + (J.phi_stride ? J.p : 0) + lq + J.p * lq + (J.mode == PAY_EHALF ? lq : 0));
+    }
+    ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
     hipLaunchKernelGGL(k_proj_garble, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
@@ -183,6 +191,9 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
         if (J.term_first + J.term_count > (uint32_t)kMaxTerms || J.term_count == 0) return DASH_EINVAL;
     }
     dim3 grid((L.n_elem + kThreads - 1) / kThreads, njobs);
+    double bytes = 0;
+    for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (L.jobs[j].term_count * c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
     hipLaunchKernelGGL(k_proj_eval, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;

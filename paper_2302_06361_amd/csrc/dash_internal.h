@@ -104,8 +104,34 @@ struct HgLaunch {
 
 }  // namespace dash
 
+namespace dash {
+// benchmark instrumentation: event pairs around the launches of one kernel class
+struct ProfRec { hipEvent_t a, b; double units, bytes; };
+struct ProfState {
+    bool on = false;
+    std::vector<ProfRec> rec[DASH_PROF_KINDS];
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+};
+struct ProfScope {      // records the first event at construction, the second at destruction
+    ProfState* p; int kind; hipStream_t s; ProfRec r;
+    ProfScope(ProfState* p_, int kind_, hipStream_t s_, double units, double bytes) : p(p_ && p_->on ? p_ : nullptr), kind(kind_), s(s_) {
+        if (!p) return;
+        r.a = p->get(); r.b = p->get(); r.units = units; r.bytes = bytes;
+        (void)hipEventRecord(r.a, s);
+    }
+    ~ProfScope() { if (p) { (void)hipEventRecord(r.b, s); p->rec[kind].push_back(r); } }
+};
+}  // namespace dash
+
 struct dash_ctx {
     int device;
+    dash::ProfState* prof;
     int k;
     int prime[DASH_MAX_PRIMES];
     int rule;

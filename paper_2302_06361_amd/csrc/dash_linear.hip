@@ -176,6 +176,8 @@ int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_label
         A.batch = (int)batch; A.in_h = in_h; A.in_w = in_w; A.in_c = L->in_c; A.out_c = out_c;
         A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.out_h = out_h; A.out_w = out_w;
         int64_t lanes = n_out * c->mods[c->prime[i]].nchunk;
+        double lam = c->mods[c->prime[i]].lam;
+        ProfScope ps(c->prof, DASH_PROF_LINEAR, s, (double)n_out * K * lam, ((double)n_in + n_out) * lam + (double)out_c * K);
         hipLaunchKernelGGL(k_linear_direct, dim3((uint32_t)((lanes + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, A);
     }
     DASH_HIP(hipGetLastError());
