@@ -5,6 +5,11 @@
 //
 // Everything here is a forceinline host+device function with no memory access of its own except
 // through the functors it is given, so the same code is exercised by a host self-check.
+//
+// Every routine is a template over the modulus description: either the runtime ModInfo (any
+// modulus 2..255, loops with wave-uniform trip counts) or CMod<m, lam> whose fields are
+// compile-time constants, so that the same source unrolls completely and all divisions become
+// multiplications by literals.
 #pragma once
 #include <stdint.h>
 
@@ -17,7 +22,7 @@
 
 namespace dash {
 
-// Constants of one modulus m (2..255), computed on the host (dash_ctx.hip).
+// Constants of one modulus m (2..255), computed on the host (dash_hostconst.h).
 struct ModInfo {
     uint32_t m;       // modulus
     uint32_t lam;     // digits per label
@@ -26,25 +31,70 @@ struct ModInfo {
     uint32_t mmagic;  // ceil(2^32 / m): floor(n / m) = mulhi(n, mmagic) for n < 2^24
     uint32_t m4;      // m replicated in 4 bytes
     uint32_t c4;      // (128 - m) replicated (m <= 128), else 0
-    uint32_t gc;      // digits per 32-bit super-digit of compress: m^(gc-1) <= 2^24, m^gc < 2^32
-    uint32_t Qc;      // m^gc
+    uint32_t gc;      // dwords (4 digits each) per 32-bit super-digit of compress: m^(4 gc) < 2^32
+    uint32_t Qc;      // m^(4 gc)
     uint32_t gd;      // digits per super-digit of decompress: m^gd <= 2^15
     uint32_t Qd;      // m^gd
     uint32_t Qdmagic; // ceil(2^(31+L) / Qd), L = ceil(log2 Qd): floor(n / Qd) = mulhi(n, Qdmagic) >> (L-1), n < 2^31
     uint32_t Qdshift; // L - 1
-    uint32_t pad_;
+    uint32_t Qdbits;  // floor(log2 Qd): every division by Qd shortens the dividend by at least this many bits
     const uint32_t* dtab;  // device: [a = 0..m-1][ndw] packed digits of a * R_m mod m
 };
+
+// ---- the same constants at compile time ---------------------------------------------------------
+namespace cm {
+constexpr uint32_t ceil_log2(uint64_t v) { uint32_t l = 0; while ((1ull << l) < v) l++; return l; }
+constexpr uint32_t floor_log2(uint64_t v) { uint32_t l = 0; while ((2ull << l) <= v) l++; return l; }
+constexpr uint64_t ipow(uint64_t b, uint32_t e) { uint64_t r = 1; for (uint32_t i = 0; i < e; i++) r *= b; return r; }
+constexpr uint32_t gc_of(uint32_t m) { uint32_t g = 0; while (g < 8 && ipow(m, 4 * (g + 1)) < (1ull << 32)) g++; return g; }
+constexpr uint32_t gd_of(uint32_t m) { uint32_t g = 0; while (ipow(m, g + 1) <= (1ull << 15)) g++; return g; }
+}  // namespace cm
+
+template <uint32_t MOD, uint32_t LAM>
+struct CMod {
+    static constexpr uint32_t m = MOD, lam = LAM, nchunk = (LAM + 15) / 16, ndw = (LAM + 3) / 4;
+    static constexpr uint32_t mmagic = (uint32_t)(((1ull << 32) + MOD - 1) / MOD);
+    static constexpr uint32_t m4 = MOD * 0x01010101u, c4 = MOD <= 128 ? (128 - MOD) * 0x01010101u : 0;
+    static constexpr uint32_t gc = cm::gc_of(MOD), Qc = (uint32_t)cm::ipow(MOD, 4 * gc);
+    static constexpr uint32_t gd = cm::gd_of(MOD), Qd = (uint32_t)cm::ipow(MOD, gd);
+    static constexpr uint32_t Qdshift = cm::ceil_log2(Qd) - 1;
+    static constexpr uint32_t Qdmagic = (uint32_t)(((1ull << (32 + Qdshift)) + Qd - 1) / Qd);
+    static constexpr uint32_t Qdbits = cm::floor_log2(Qd);
+    const uint32_t* dtab;
+};
+
+// the modulus of a compile-time description, 0 for the run-time one
+template <class T> struct cmod_m { static constexpr uint32_t value = 0; };
+template <uint32_t MOD, uint32_t LAM> struct cmod_m<CMod<MOD, LAM>> { static constexpr uint32_t value = MOD; };
 
 struct U128 { uint32_t w[4]; };
 
 DASH_HD uint32_t mulhi(uint32_t a, uint32_t b) { return (uint32_t)(((uint64_t)a * b) >> 32); }
-DASH_HD uint32_t div_m(uint32_t n, const ModInfo& M) { return mulhi(n, M.mmagic); }          // n < 2^24
-DASH_HD uint32_t mod_m(uint32_t n, const ModInfo& M) { return n - div_m(n, M) * M.m; }       // n < 2^24
+// 24-bit multiply (both operands below 2^24, product below 2^32): full rate on the vector ALU
+DASH_HD uint32_t mul24(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umul24(a, b);
+#else
+    return a * b;
+#endif
+}
+// sum of byte products a.b0*b.b0 + .. + a.b3*b.b3
+DASH_HD uint32_t dot4(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__) && __has_builtin(__builtin_amdgcn_udot4)
+    return __builtin_amdgcn_udot4(a, b, 0u, false);
+#else
+    uint32_t s = 0;
+    for (int i = 0; i < 4; i++) s += ((a >> (8 * i)) & 0xff) * ((b >> (8 * i)) & 0xff);
+    return s;
+#endif
+}
+template <class MI> DASH_HD uint32_t div_m(uint32_t n, const MI& M) { return mulhi(n, M.mmagic); }           // n < 2^24
+template <class MI> DASH_HD uint32_t mod_m(uint32_t n, const MI& M) { return n - mul24(div_m(n, M), M.m); }  // n < 2^24
 DASH_HD uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xffu; }
 
 // (a + b) mod m on 4 packed digits, a, b < m per byte.
-DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const ModInfo& M) {
+template <class MI>
+DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
     if (M.m <= 128) {
         uint32_t t = a + b;                                       // bytes <= 2m-2 <= 254
         uint32_t ge = ((t + M.c4) & 0x80808080u) >> 7;            // 1 where byte >= m
@@ -59,7 +109,8 @@ DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const ModInfo& M) {
     return r;
 }
 // (a - b) mod m on 4 packed digits.
-DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const ModInfo& M) {
+template <class MI>
+DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const MI& M) {
     if (M.m <= 128) {
         uint32_t t = a + (M.m4 - b);                              // bytes in [1, 2m-1] <= 255
         uint32_t ge = ((t + M.c4) & 0x80808080u) >> 7;
@@ -74,9 +125,10 @@ DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const ModInfo& M) {
     return r;
 }
 // (a + c * b) mod m on 4 packed digits, c < m.
-DASH_HD uint32_t axpymod4(uint32_t a, uint32_t c, uint32_t b, const ModInfo& M) {
+template <class MI>
+DASH_HD uint32_t axpymod4(uint32_t a, uint32_t c, uint32_t b, const MI& M) {
     uint32_t r = 0;
-    for (int b8 = 0; b8 < 4; b8++) r |= mod_m(byte_of(a, b8) + c * byte_of(b, b8), M) << (8 * b8);
+    for (int b8 = 0; b8 < 4; b8++) r |= mod_m(byte_of(a, b8) + mul24(c, byte_of(b, b8)), M) << (8 * b8);
     return r;
 }
 
@@ -90,24 +142,38 @@ DASH_HD void muladd128(U128& a, uint32_t mul, uint32_t add) {
 }
 
 // compress(l) = sum_j l[j] m^j mod 2^128 (Horner from the top digit).  dw(i) returns packed digits
-// 4i..4i+3 of the label (digits >= lam ignored).  *colour receives digit 0.
-template <class LoadDw>
-DASH_HD U128 compress(const ModInfo& M, LoadDw dw, uint32_t* colour) {
+// 4i..4i+3 of the label, digits past lam zero.  *colour receives digit 0.
+// Four digits at a time: v = d0 + m d1 + m^2 d2 + m^3 d3 by two byte dot products; gc such values
+// make one 32-bit super-digit; the 128-bit accumulator is multiplied once per super-digit.  The top
+// dword may hold fewer than 4 digits: its missing digits are zero, which Horner ignores.
+template <class MI, class LoadDw>
+DASH_HD U128 compress(const MI& M, LoadDw dw, uint32_t* colour) {
     U128 acc = {{0, 0, 0, 0}};
-    uint32_t S = 0;
-    uint32_t left = M.lam % M.gc;           // digits still to take into the current super-digit;
-    if (left == 0) left = M.gc;             // the first (top) group may be short: acc is still 0
-    uint32_t d = 0;
+    if constexpr (cmod_m<MI>::value == 2) {   // digits are bits: pack them (compile-time description only:
+                                                        // with run-time trip counts the word index would be dynamic)
+        uint32_t w0 = 0;
+#pragma unroll
+        for (int i = (int)M.ndw - 1; i >= 0; i--) {
+            uint32_t w = dw(i);
+            if (i == 0) w0 = w;
+            acc.w[i >> 3] |= dot4(w, 0x08040201u) << (4 * (i & 7));
+        }
+        *colour = w0 & 0xffu;
+        return acc;
+    }
+    const uint32_t wlo = 1u | (M.m << 8), whi = (1u << 16) | (M.m << 24), m2 = M.m * M.m, m4 = m2 * m2;
+    uint32_t S = 0, w0 = 0;
+    uint32_t left = M.ndw % M.gc;        // dwords still to take into the current super-digit;
+    if (left == 0) left = M.gc;          // the first (top) group may be short: acc is still 0
+#pragma unroll
     for (int i = (int)M.ndw - 1; i >= 0; i--) {
         uint32_t w = dw(i);
-        for (int b = 3; b >= 0; b--) {
-            if ((uint32_t)(4 * i + b) >= M.lam) continue;
-            d = byte_of(w, b);
-            S = S * M.m + d;
-            if (--left == 0) { muladd128(acc, M.Qc, S); S = 0; left = M.gc; }
-        }
+        if (i == 0) w0 = w;
+        uint32_t v = dot4(w, wlo) + m2 * dot4(w, whi);      // < m^4
+        S = S * m4 + v;
+        if (--left == 0) { muladd128(acc, M.Qc, S); S = 0; left = M.gc; }
     }
-    *colour = d;
+    *colour = w0 & 0xffu;
     return acc;
 }
 
@@ -120,6 +186,7 @@ DASH_HD U128 compress(const ModInfo& M, LoadDw dw, uint32_t* colour) {
 template <class Tab>
 DASH_HD void aes128_encrypt(uint32_t s[4], const uint32_t* rk, const Tab& T) {
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
+#pragma unroll
     for (int r = 1; r < 10; r++) {
         uint32_t b0 = T(0, a0 & 0xff) ^ T(1, (a1 >> 8) & 0xff) ^ T(2, (a2 >> 16) & 0xff) ^ T(3, a3 >> 24) ^ rk[4 * r + 0];
         uint32_t b1 = T(0, a1 & 0xff) ^ T(1, (a2 >> 8) & 0xff) ^ T(2, (a3 >> 16) & 0xff) ^ T(3, a0 >> 24) ^ rk[4 * r + 1];
@@ -156,36 +223,55 @@ DASH_HD U128 prg_block(uint64_t elem, uint32_t slot, uint32_t layer, uint32_t do
 // decompress: digits floor(h / m^j) mod m, j = 0..lam-1, delivered as packed dwords emit(i, w)
 // for i = 0..ndw-1.  Long division of eight 16-bit limbs by the super-digit base Qd = m^gd <= 2^15
 // (every partial dividend r * 2^16 + limb is below 2^31, where the magic division is exact), then
-// gd digits out of every remainder.
+// gd digits out of every remainder.  After t divisions the dividend is below 2^(128 - t*Qdbits), so
+// the upper limbs are known to be zero and are skipped.
 // ---------------------------------------------------------------------------------------------
 struct Limbs { uint32_t l[8]; };
 
 DASH_HD Limbs to_limbs(const U128& h) {
     Limbs x;
+#pragma unroll
     for (int i = 0; i < 4; i++) { x.l[2 * i] = h.w[i] & 0xffffu; x.l[2 * i + 1] = h.w[i] >> 16; }
     return x;
 }
-// x = floor(x / Qd), returns x mod Qd
-DASH_HD uint32_t divrem_Qd(Limbs& x, const ModInfo& M) {
+// x = floor(x / Qd) over the nl low limbs, returns x mod Qd
+template <class MI>
+DASH_HD uint32_t divrem_Qd(Limbs& x, const MI& M, uint32_t nl) {
     uint32_t r = 0;
+#pragma unroll
     for (int i = 7; i >= 0; i--) {
+        if ((uint32_t)i >= nl) continue;
         uint32_t cur = (r << 16) | x.l[i];
         uint32_t q = mulhi(cur, M.Qdmagic) >> M.Qdshift;
-        r = cur - q * M.Qd;
+        r = cur - mul24(q, M.Qd);
         x.l[i] = q;
     }
     return r;
 }
 
-template <class Emit>
-DASH_HD void decompress(const ModInfo& M, const U128& h, Emit emit) {
+template <class MI, class Emit>
+DASH_HD void decompress(const MI& M, const U128& h, Emit emit) {
+    if constexpr (cmod_m<MI>::value == 2) {   // digits are bits: spread 4 bits into 4 bytes
+#pragma unroll
+        for (int i = 0; i < (int)M.ndw; i++) {
+            uint32_t nib = (h.w[i >> 3] >> (4 * (i & 7))) & 0xfu;
+            emit(i, (nib * 0x00204081u) & 0x01010101u);
+        }
+        return;
+    }
     Limbs x = to_limbs(h);
     uint32_t S = 0, have = 0;     // digits left in the current super-digit
+    uint32_t bits = 128;          // the dividend is below 2^bits
     uint32_t w = 0;
+#pragma unroll
     for (uint32_t j = 0; j < M.lam; j++) {
-        if (have == 0) { S = divrem_Qd(x, M); have = M.gd; }
-        uint32_t q = div_m(S, M);
-        uint32_t d = S - q * M.m;
+        if (have == 0) {
+            S = divrem_Qd(x, M, (bits + 15) / 16);
+            bits = bits > M.Qdbits ? bits - M.Qdbits : 0;
+            have = M.gd;
+        }
+        uint32_t q = mulhi(S, M.mmagic);
+        uint32_t d = S - mul24(q, M.m);
         S = q; have--;
         w |= d << (8 * (j & 3));
         if ((j & 3) == 3) { emit((int)(j >> 2), w); w = 0; }
@@ -194,11 +280,44 @@ DASH_HD void decompress(const ModInfo& M, const U128& h, Emit emit) {
 }
 
 // digit 0 alone: h mod m
-DASH_HD uint32_t mod_u128(const U128& h, const ModInfo& M) {
+template <class MI>
+DASH_HD uint32_t mod_u128(const U128& h, const MI& M) {
     Limbs x = to_limbs(h);
     uint32_t r = 0;
+#pragma unroll
     for (int i = 7; i >= 0; i--) r = mod_m((r << 16) | x.l[i], M);    // r < 256, (r<<16)|limb < 2^24
     return r;
+}
+
+// The moduli with a compile-time description: the CRT primes up to 37 and the accumulation moduli of
+// the default digit sets, with their label lengths under the ceil rule.
+#define DASH_HOT_MODS(X) \
+    X(2, 128) X(3, 81) X(5, 56) X(7, 46) X(11, 38) X(13, 35) X(17, 32) X(19, 31) X(23, 29) X(29, 27) X(31, 26) X(37, 25) \
+    X(26, 28) X(96, 20) X(46, 24) X(204, 17)
+
+// f(description of M): compile-time description for the hot moduli, run-time otherwise
+template <class F>
+DASH_HD void with_mod(const ModInfo& M, F&& f) {
+#define DASH_MOD_CASE(MOD, LAM) case MOD: if (M.lam == LAM) { f(CMod<MOD, LAM>{M.dtab}); return; } break;
+    switch (M.m) {
+        DASH_HOT_MODS(DASH_MOD_CASE)
+        default: break;
+    }
+#undef DASH_MOD_CASE
+    f(M);
+}
+
+// description of type QD (ModInfo itself, or a CMod) built from the run-time record
+template <class QD> struct make_mod { static DASH_HD QD from(const ModInfo& M) { return QD{M.dtab}; } };
+template <> struct make_mod<ModInfo> { static DASH_HD ModInfo from(const ModInfo& M) { return M; } };
+
+// index of the compile-time description that fits M (1..), 0 if none
+DASH_HD int hot_mod_index(const ModInfo& M) {
+    int idx = 0;
+#define DASH_MOD_IDX(MOD, LAM) idx++; if (M.m == MOD && M.lam == LAM) return idx;
+    DASH_HOT_MODS(DASH_MOD_IDX)
+#undef DASH_MOD_IDX
+    return 0;
 }
 
 }  // namespace dash

@@ -83,15 +83,13 @@ inline void fill_modinfo(ModInfo& M, int m, int rule) {
     M.mmagic = (uint32_t)(((1ull << 32) + m - 1) / m);
     M.m4 = (uint32_t)m * 0x01010101u;
     M.c4 = m <= 128 ? (uint32_t)(128 - m) * 0x01010101u : 0;
-    uint64_t pw = 1; uint32_t g = 0;
-    while (pw <= (1ull << 24) && pw * m < (1ull << 32)) { pw *= m; g++; }   // m^(g-1) <= 2^24, m^g < 2^32
-    M.gc = g; M.Qc = (uint32_t)pw;
-    pw = 1; g = 0;
-    while (pw * m <= (1ull << 15)) { pw *= m; g++; }
-    M.gd = g; M.Qd = (uint32_t)pw;
+    // the compile-time descriptions (CMod) use the same formulas
+    M.gc = cm::gc_of(m); M.Qc = (uint32_t)cm::ipow(m, 4 * M.gc);
+    M.gd = cm::gd_of(m); M.Qd = (uint32_t)cm::ipow(m, M.gd);
     uint32_t L = ceil_log2(M.Qd);
     M.Qdmagic = (uint32_t)((((u128)1 << (31 + L)) + M.Qd - 1) / M.Qd);
     M.Qdshift = L - 1;
+    M.Qdbits = cm::floor_log2(M.Qd);
 }
 
 }  // namespace hostconst

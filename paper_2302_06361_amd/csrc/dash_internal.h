@@ -7,102 +7,7 @@
 
 #include "../../include/dash.h"
 #include "dash_core.h"
-
-namespace dash {
-
-constexpr int kMaxJobs = 16;    // gate batches per launch (blockIdx.y)
-constexpr int kMaxTerms = 16;   // label terms per launch, shared by its jobs
-constexpr int kThreads = 256;
-
-// PRG domains (byte 14 of the counter block)
-enum { DOM_DELTA = 0, DOM_INPUT = 1, DOM_GATE = 2, DOM_MASK = 3, DOM_ONE = 4 };
-
-// A view of a LabelTensor of one modulus: digit j of element e at p + (j/16)*cs + e*es + j%16.
-struct LView {
-    uint8_t* p;
-    int64_t cs;    // chunk stride in bytes
-    uint32_t es;   // element stride in bytes: 16, or 0 for a single label broadcast to all elements
-};
-struct Term {
-    LView v;
-    uint32_t coef;   // in [0, m)
-};
-
-// Payload modes of the garble kernel
-enum { PAY_PHI = 0,     // out0 + phi(a) * R_q
-       PAY_MULR = 1,    // out0 + (a * r mod q) * R_q            (garbler half gate)
-       PAY_EHALF = 2,   // out0 - ((a + r) mod q) * x0           (evaluator half gate)
-       PAY_SHORT = 3 }; // one digit: (a + r) mod q, 4-byte rows  (evaluator's known input)
-
-struct GateJob {
-    uint32_t p, q;            // input / output modulus
-    uint32_t term_first, term_count;
-    const uint8_t* phi;       // PAY_PHI
-    uint32_t phi_stride;
-    uint32_t slot;
-    uint32_t mode;
-    uint32_t pad_;
-    LView out;                // garble: zero labels of the output wires (read); eval: output labels (written)
-    uint8_t* table;           // segment base
-    const uint8_t* r;         // PAY_MULR / EHALF / SHORT: mask per element
-    LView x0;                 // PAY_EHALF: zero labels of the x wire
-};
-
-struct AesKey { uint32_t rk[44]; };
-
-struct GateLaunch {
-    AesKey key;
-    const uint32_t* ttab;       // device [4][256]
-    const ModInfo* mods;        // device [256]
-    uint64_t elem_base;
-    uint32_t layer;
-    uint32_t n_elem;
-    Term terms[kMaxTerms];
-    GateJob jobs[kMaxJobs];
-};
-
-struct DrawJob {
-    uint32_t m, domain, slot, digit0_only;
-    LView out;       // digit0_only: out.p is a byte array [n_elem]
-};
-struct DrawLaunch {
-    AesKey key;
-    const uint32_t* ttab;
-    const ModInfo* mods;
-    uint64_t elem_base;
-    uint32_t layer;
-    uint32_t n_elem;
-    DrawJob jobs[kMaxJobs];
-};
-
-struct AffineJob {
-    uint32_t m, term_first, term_count, pad_;
-    LView out;
-};
-struct AffineLaunch {
-    const ModInfo* mods;
-    uint32_t n_elem;
-    Term terms[kMaxTerms];
-    AffineJob jobs[kMaxJobs];
-};
-
-// half-gate evaluation: z = V + beta * x - U, beta = S[colour(y)] - H_p(y, slot)[0]
-struct HgJob {
-    uint32_t p, slot;
-    LView x, y, U, V, z;
-    const uint8_t* S;     // [elem][2][4]
-};
-struct HgLaunch {
-    AesKey key;
-    const uint32_t* ttab;
-    const ModInfo* mods;
-    uint64_t elem_base;
-    uint32_t layer;
-    uint32_t n_elem;
-    HgJob jobs[kMaxJobs];
-};
-
-}  // namespace dash
+#include "dash_launch.h"
 
 namespace dash {
 // benchmark instrumentation: event pairs around the launches of one kernel class

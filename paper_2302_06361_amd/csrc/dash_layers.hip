@@ -70,33 +70,45 @@ struct Arena {
 struct SignWires {
     LView A[DASH_MAX_PRIMES][DASH_MAX_DIGITS + 1];
     LView C[DASH_MAX_DIGITS + 1];   // C[j]: carry into digit j (j = 1..n-1)
+    LView S[DASH_MAX_DIGITS + 1];   // S[j]: free sum of the digit wires of digit j and the carry into it
     LView bit;
 };
 void plan_sign(const dash_ctx* c, Arena& ar, int64_t E, int first_res, SignWires& w) {
     for (int i = first_res; i < c->k; i++)
         for (int j = 1; j <= c->n; j++) w.A[i][j] = ar.labels(c, c->mj[j], E);
     for (int j = 1; j < c->n; j++) w.C[j] = ar.labels(c, c->mj[j], E);
+    for (int j = 1; j <= c->n; j++) w.S[j] = ar.labels(c, c->mj[j], E);
     w.bit = ar.labels(c, 2, E);
 }
 
 // ---- launch batchers -------------------------------------------------------------------------
+// Collects independent gate jobs and launches them grouped by output modulus (a launch runs one
+// instantiation of the gate kernel, chosen by the output modulus), up to kMaxJobs per launch.
 struct GateBatcher {
+    static constexpr int kSlots = 4;
     const dash_ctx* c; bool garble; hipStream_t s;
-    GateLaunch L; int nj = 0, nt = 0, status = DASH_OK;
+    GateLaunch L[kSlots]; int nj[kSlots]; int status = DASH_OK;
     GateBatcher(const dash_ctx* c_, bool g, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_) : c(c_), garble(g), s(s_) {
-        memset(&L, 0, sizeof(L));
-        L.n_elem = E; L.layer = layer; L.elem_base = elem_base;
+        memset(L, 0, sizeof(L));
+        for (int t = 0; t < kSlots; t++) { L[t].n_elem = E; L[t].layer = layer; L[t].elem_base = elem_base; nj[t] = 0; }
     }
-    void add(GateJob J, const Term* t, int n) {
-        if (nj == kMaxJobs || nt + n > kMaxTerms) flush();
-        J.term_first = nt; J.term_count = n;
-        for (int i = 0; i < n; i++) L.terms[nt++] = t[i];
-        L.jobs[nj++] = J;
+    void launch(int t) {
+        if (nj[t] && status == DASH_OK) status = garble ? launch_garble(c, L[t], nj[t], s) : launch_eval(c, L[t], nj[t], s);
+        nj[t] = 0;
     }
-    void flush() {
-        if (nj && status == DASH_OK) status = garble ? launch_garble(c, L, nj, s) : launch_eval(c, L, nj, s);
-        nj = nt = 0;
+    void add(const GateJob& J) {
+        int t = -1, free_slot = -1;
+        for (int u = 0; u < kSlots; u++) {
+            if (nj[u] && L[u].jobs[0].q == J.q) t = u;
+            if (!nj[u] && free_slot < 0) free_slot = u;
+        }
+        if (t < 0) {
+            if (free_slot < 0) { launch(0); free_slot = 0; }
+            t = free_slot;
+        } else if (nj[t] == kMaxJobs) launch(t);
+        L[t].jobs[nj[t]++] = J;
     }
+    void flush() { for (int t = 0; t < kSlots; t++) launch(t); }
 };
 struct DrawBatcher {
     const dash_ctx* c; hipStream_t s; DrawLaunch L; int nj = 0, status = DASH_OK;
@@ -121,10 +133,10 @@ struct AffineBatcher {
     void flush() { if (nj && status == DASH_OK) status = launch_affine(c, L, nj, s); nj = nt = 0; }
 };
 
-GateJob phi_job(int p, int q, const uint8_t* phi, uint32_t slot, LView out, uint8_t* table) {
+GateJob phi_job(int p, int q, LView in, const uint8_t* phi, uint32_t slot, LView out, uint8_t* table) {
     GateJob J;
     memset(&J, 0, sizeof(J));
-    J.p = p; J.q = q; J.phi = phi; J.phi_stride = 0; J.slot = slot; J.mode = PAY_PHI; J.out = out; J.table = table;
+    J.p = p; J.q = q; J.in = in; J.phi = phi; J.phi_stride = 0; J.slot = slot; J.mode = PAY_PHI; J.out = out; J.table = table;
     return J;
 }
 
@@ -151,23 +163,43 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     for (int i = first_res; i < k; i++)
         for (int j = 1; j <= n; j++) {
             int sl = i * n + (j - 1);
-            Term t{x[i], 1};
-            gb.add(phi_job(c->prime[i], c->mj[j], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]), &t, 1);
+            gb.add(phi_job(c->prime[i], c->mj[j], x[i], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]));
         }
     gb.flush();
     // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
-    for (int j = n; j >= 1; j--) {
+    // The garbler knows every zero label up front, so it sums all digits first and garbles the n
+    // gates of the chain in one launch; the evaluator has to follow the chain.
+    auto sum_digit = [&](AffineBatcher& ab, int j) {
         Term t[kMaxTerms];
         int nt = 0;
         for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
         if (j < n) t[nt++] = Term{w.C[j], 1};
+        ab.add(c->mj[j], w.S[j], t, nt);
+    };
+    auto chain_gate = [&](int j) {
         if (j >= 2) {
             int sl = k * n + (j - 2);
-            gb.add(phi_job(c->mj[j], c->mj[j - 1], c->phi_carry[j], slot_base + sl, w.C[j - 1], seg + off[sl]), t, nt);
+            gb.add(phi_job(c->mj[j], c->mj[j - 1], w.S[j], c->phi_carry[j], slot_base + sl, w.C[j - 1], seg + off[sl]));
         } else {
             int sl = k * n + n - 1;
-            gb.add(phi_job(c->mj[1], 2, c->phi_final[negate], slot_base + sl, w.bit, seg + off[sl]), t, nt);
+            gb.add(phi_job(c->mj[1], 2, w.S[1], c->phi_final[negate], slot_base + sl, w.bit, seg + off[sl]));
         }
+    };
+    if (garble) {
+        AffineBatcher ab(c, E, s);
+        for (int j = n; j >= 1; j--) sum_digit(ab, j);
+        ab.flush();
+        if (ab.status) return ab.status;
+        for (int j = n; j >= 1; j--) chain_gate(j);
+        gb.flush();
+        return gb.status;
+    }
+    for (int j = n; j >= 1; j--) {
+        AffineBatcher ab(c, E, s);
+        sum_digit(ab, j);
+        ab.flush();
+        if (ab.status) return ab.status;
+        chain_gate(j);
         gb.flush();
     }
     return gb.status;
@@ -224,16 +256,15 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         GateBatcher gb(c, true, E, layer, eb, s);
         for (int i = 0; i < k; i++) {
             int p = c->prime[i];
-            Term tx{x[i], 1}, ty{pl.w.bit, 1};
-            GateJob J = phi_job(p, p, nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
+            GateJob J = phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
             J.mode = PAY_MULR; J.r = pl.r[i];
-            gb.add(J, &tx, 1);
-            J = phi_job(2, p, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]);              // evaluator half: -(b+r)*x0
+            gb.add(J);
+            J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]);         // evaluator half: -(b+r)*x0
             J.mode = PAY_EHALF; J.r = pl.r[i]; J.x0 = x[i];
-            gb.add(J, &ty, 1);
-            J = phi_job(2, p, nullptr, ns + 3 * i + 2, pl.V[i], S[i]);               // b + r for the evaluator
+            gb.add(J);
+            J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 2, pl.V[i], S[i]);          // b + r for the evaluator
             J.mode = PAY_SHORT; J.r = pl.r[i];
-            gb.add(J, &ty, 1);
+            gb.add(J);
         }
         gb.flush();
         if (gb.status) return gb.status;
@@ -248,9 +279,8 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
     GateBatcher gb(c, false, E, layer, eb, s);
     for (int i = 0; i < k; i++) {
         int p = c->prime[i];
-        Term tx{x[i], 1}, ty{pl.w.bit, 1};
-        gb.add(phi_job(p, p, nullptr, ns + 3 * i, pl.U[i], G[i]), &tx, 1);
-        gb.add(phi_job(2, p, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]), &ty, 1);
+        gb.add(phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]));
+        gb.add(phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]));
     }
     gb.flush();
     if (gb.status) return gb.status;
@@ -286,8 +316,7 @@ int signact_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labe
     size_t cum = sign_bytes(c, 0);
     GateBatcher gb(c, garble, E, layer, eb, s);
     for (int i = 0; i < k; i++) {
-        Term t{w.bit, 1};
-        gb.add(phi_job(2, c->prime[i], c->phi_pm1[i], ns + i, view_of(out, i), tables + cum * E), &t, 1);
+        gb.add(phi_job(2, c->prime[i], w.bit, c->phi_pm1[i], ns + i, view_of(out, i), tables + cum * E));
         cum += 2 * pitch_of(c, c->prime[i]);
     }
     gb.flush();
@@ -347,8 +376,7 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         {
             GateBatcher gb(c, garble, E, layer, eb, s);
             for (int i = 1; i < k; i++) {
-                Term t{pl.up, 1};
-                gb.add(phi_job(2, c->prime[i], c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E), &t, 1);
+                gb.add(phi_job(2, c->prime[i], pl.up, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
                 cum += 2 * pitch_of(c, c->prime[i]);
             }
             gb.flush();
@@ -458,10 +486,9 @@ int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         if (db.status) return db.status;
     }
     GateBatcher gb(c, garble, E, L->layer_id, L->elem_base, s);
-    Term t{view_of(in, pi), 1};
-    GateJob J = phi_job(p, q, L->phi, 0, view_of(out, qi), tables);
+    GateJob J = phi_job(p, q, view_of(in, pi), L->phi, 0, view_of(out, qi), tables);
     J.phi_stride = (uint32_t)L->phi_stride;
-    gb.add(J, &t, 1);
+    gb.add(J);
     gb.flush();
     return gb.status;
 }

@@ -39,6 +39,22 @@ void cc_hash(const uint8_t* label, int p, int q, int rule, uint64_t elem, uint32
     memset(out, 0, Mq.ndw * 4);
     decompress(Mq, h, [&](int i, uint32_t w) { memcpy(out + 4 * i, &w, 4); });
 }
+// the same through the compile-time modulus descriptions where one exists
+void cc_hash_spec(const uint8_t* label, int p, int q, int rule, uint64_t elem, uint32_t slot, uint32_t layer, uint8_t* out, uint32_t* colour) {
+    init();
+    ModInfo Mp, Mq;
+    fill_modinfo(Mp, p, rule);
+    fill_modinfo(Mq, q, rule);
+    uint8_t key[16];
+    for (int i = 0; i < 16; i++) key[i] = (uint8_t)i;
+    uint32_t rk[44];
+    expand_key(key, SB, rk);
+    U128 K;
+    with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return pack_dw(label, P.lam, i); }, colour); });
+    U128 h = hash_block(K, elem, slot, layer, rk, HostTab());
+    memset(out, 0, Mq.ndw * 4);
+    with_mod(Mq, [&](auto Q) { decompress(Q, h, [&](int i, uint32_t w) { memcpy(out + 4 * i, &w, 4); }); });
+}
 void cc_draw(const uint8_t seed[16], int domain, uint32_t layer, uint32_t slot, uint64_t elem, int m, int rule, uint8_t* out, uint32_t* digit0) {
     init();
     ModInfo M;

@@ -43,11 +43,13 @@ def test_hash_matches_oracle(cc, rule):
             elem, slot, layer = int(g.integers(0, 2 ** 62)), int(g.integers(0, 2 ** 32)), int(g.integers(0, 2 ** 16))
             out = np.zeros(4 * ((lq + 3) // 4), np.uint8)
             col = C.c_uint32()
-            cc.cc_hash(lab.ctypes.data_as(C.c_void_p), p, q, rule, C.c_uint64(elem), C.c_uint32(slot), C.c_uint32(layer),
-                       out.ctypes.data_as(C.c_void_p), C.byref(col))
             want = orc.hash(lab, p, layer, slot, elem, q)
-            assert (out[:lq] == want).all(), (p, q)
-            assert (out[lq:] == 0).all() and col.value == lab[0]
+            for fn in (cc.cc_hash, cc.cc_hash_spec):      # run-time and compile-time modulus descriptions
+                out[:] = 0xEE
+                fn(lab.ctypes.data_as(C.c_void_p), p, q, rule, C.c_uint64(elem), C.c_uint32(slot), C.c_uint32(layer),
+                   out.ctypes.data_as(C.c_void_p), C.byref(col))
+                assert (out[:lq] == want).all(), (p, q)
+                assert (out[lq:] == 0).all() and col.value == lab[0]
 
 
 def test_draw_matches_oracle(cc):
