@@ -9,11 +9,16 @@
 namespace dash {
 
 // dword i (digits 4i..4i+3) of element e of a label view
+// The chunk base is wave-uniform (scalar registers); the lane part is a 32-bit byte offset, so the
+// access is "scalar base + 32-bit vector offset" (elements per view are limited to 2^28 for this).
+DASH_HD uint32_t lane_off(const LView& v, uint32_t e) { return v.es ? e << 4 : 0u; }   // es is 16 or 0
 DASH_HD uint32_t ld_dw(const LView& v, uint32_t e, int i) {
-    return *(const uint32_t*)(v.p + (int64_t)(i >> 2) * v.cs + (uint64_t)e * v.es + (i & 3) * 4);
+    const uint8_t* base = v.p + (int64_t)(i >> 2) * v.cs + (i & 3) * 4;
+    return *(const uint32_t*)(base + lane_off(v, e));
 }
 DASH_HD void st_dw(const LView& v, uint32_t e, int i, uint32_t w) {
-    *(uint32_t*)(v.p + (int64_t)(i >> 2) * v.cs + (uint64_t)e * v.es + (i & 3) * 4) = w;
+    uint8_t* base = v.p + (int64_t)(i >> 2) * v.cs + (i & 3) * 4;
+    *(uint32_t*)(base + lane_off(v, e)) = w;
 }
 
 // PRG labels: one lane per (job, element)
@@ -31,26 +36,52 @@ DASH_HD void draw_body(const DrawLaunch& L, uint32_t bx, uint32_t by, uint32_t t
     });
 }
 
-// free gates: out = sum_t coef_t * term_t mod m
+// free gates: out = sum_t coef_t * term_t mod m.  One lane per (element, 16-digit chunk): a 16-byte load
+// per term.  Sums with unit coefficients (the mixed-radix additions of the sign gadget) accumulate two
+// digits per 32-bit word in 16-bit fields; general coefficients go digit by digit.
 DASH_HD void affine_body(const AffineLaunch& L, uint32_t bx, uint32_t by, uint32_t tx) {
     const AffineJob& J = L.jobs[by];
-    uint32_t e = bx * kThreads + tx;
-    if (e >= L.n_elem) return;
     const ModInfo M = L.mods[J.m];
-    for (int i = 0; i < (int)M.nchunk * 4; i++) {
-        uint32_t acc[4] = {0, 0, 0, 0};
+    const uint64_t idx = (uint64_t)bx * kThreads + tx;
+    if (idx >= (uint64_t)L.n_elem * M.nchunk) return;
+    const uint32_t ch = (uint32_t)(idx / L.n_elem), e = (uint32_t)(idx - (uint64_t)ch * L.n_elem);
+    const Term* T = L.terms + J.term_first;
+    uint32_t out[4];
+    if (J.unit) {
+        uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};      // digits 0,2 / 1,3 of each dword, 16 bits each
         for (uint32_t t = 0; t < J.term_count; t++) {
-            uint32_t w = ld_dw(L.terms[J.term_first + t].v, e, i), cf = L.terms[J.term_first + t].coef;
-            for (int b = 0; b < 4; b++) acc[b] += mul24(cf, byte_of(w, b));      // <= 16 * 254 * 254 < 2^24
+            const uint32_t* src = (const uint32_t*)(T[t].v.p + (int64_t)ch * T[t].v.cs + lane_off(T[t].v, e));
+            for (int q = 0; q < 4; q++) { uint32_t w = src[q]; ev[q] += w & 0x00ff00ffu; od[q] += (w >> 8) & 0x00ff00ffu; }
         }
-        st_dw(J.out, e, i, mod_m(acc[0], M) | (mod_m(acc[1], M) << 8) | (mod_m(acc[2], M) << 16) | (mod_m(acc[3], M) << 24));
+        for (int q = 0; q < 4; q++)
+            out[q] = mod_m(ev[q] & 0xffffu, M) | (mod_m(od[q] & 0xffffu, M) << 8) | (mod_m(ev[q] >> 16, M) << 16) | (mod_m(od[q] >> 16, M) << 24);
+    } else {
+        for (int q = 0; q < 4; q++) {
+            uint32_t acc[4] = {0, 0, 0, 0};
+            for (uint32_t t = 0; t < J.term_count; t++) {
+                const uint32_t* src = (const uint32_t*)(T[t].v.p + (int64_t)ch * T[t].v.cs + lane_off(T[t].v, e));
+                uint32_t w = src[q], cf = T[t].coef;
+                for (int b = 0; b < 4; b++) acc[b] += mul24(cf, byte_of(w, b));      // <= 16 * 254 * 254 < 2^24
+            }
+            out[q] = mod_m(acc[0], M) | (mod_m(acc[1], M) << 8) | (mod_m(acc[2], M) << 16) | (mod_m(acc[3], M) << 24);
+        }
     }
+    uint32_t* dst = (uint32_t*)(J.out.p + (int64_t)ch * J.out.cs + lane_off(J.out, e));
+    for (int q = 0; q < 4; q++) dst[q] = out[q];
 }
+
+// Where a finished ciphertext row goes.  DirectSink stores it dword by dword at its place in the table;
+// the kernel for long rows stages rows in LDS instead and writes them out cooperatively.
+struct DirectSink {
+    uint32_t* row;
+    DASH_HD void begin(uint8_t* table, uint64_t row_index, uint32_t pitch) { row = (uint32_t*)(table + row_index * pitch); }
+    DASH_HD void put(int i, uint32_t w) { row[i] = w; }
+};
 
 // garble: one lane per ciphertext row r = gate * p + a.  QD: description type of the output modulus
 // (every job of a launch has the same output modulus), fixed at compile time for the hot moduli.
-template <class QD, class Tab>
-DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+template <class QD, class Tab, class Sink>
+DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T, Sink& sink) {
     const GateJob& J = L.jobs[by];
     const ModInfo Mp = L.mods[J.p], Mq = L.mods[J.q];
     const QD Q = make_mod<QD>::from(Mq);
@@ -68,8 +99,8 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
     uint32_t colour = 0;
     U128 K = {{0, 0, 0, 0}};
     with_mod(Mp, [&](auto P) {
-        const uint32_t* da = P.dtab + (size_t)a * P.ndw;
-        K = compress(P, [&](int i) { return addmod4(ld_dw(J.in, g, i), da[i], P); }, &colour);
+        const uint32_t* da = P.dtab + a * P.ndw;
+        K = compress(P, [&](int i) { return addmod4(ld_dw(J.in, g, i), gload32(da + i), P); }, &colour);
     });
     U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
 
@@ -78,23 +109,31 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
         *(uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * 4) = v;
         return;
     }
-    uint32_t* row = (uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
+    sink.begin(J.table, (uint64_t)g * Mp.m + colour, Q.ndw * 4);
     if (J.mode == PAY_EHALF) {
         uint32_t cf = mod_m(a + J.r[g], Q);
         cf = cf ? Q.m - cf : 0;                          // minus (a + r) * x0
         decompress(Q, h, [&](int i, uint32_t hd) {
             uint32_t pay = axpymod4(ld_dw(J.out, g, i), cf, ld_dw(J.x0, g, i), Q);
-            row[i] = addmod4(pay, hd, Q);
+            sink.put(i, addmod4(pay, hd, Q));
         });
         return;
     }
     uint32_t f;
     if (J.mode == PAY_MULR) f = mod_m(a * J.r[g], Q);
     else f = J.phi[(size_t)g * J.phi_stride + a];
-    const uint32_t* df = Q.dtab + (size_t)f * Q.ndw;
-    decompress(Q, h, [&](int i, uint32_t hd) {
-        row[i] = addmod4(addmod4(ld_dw(J.out, g, i), df[i], Q), hd, Q);
-    });
+    const uint32_t* df = Q.dtab + f * Q.ndw;
+    if constexpr (cmod_m<QD>::value != 0) {
+        // payload first (its loads do not wait behind the row stores), then one pass over the hash digits
+        uint32_t pay[QD::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)QD::ndw; i++) pay[i] = addmod4(ld_dw(J.out, g, i), gload32(df + i), Q);
+        decompress(Q, h, [&](int i, uint32_t hd) { sink.put(i, addmod4(pay[i], hd, Q)); });
+    } else {
+        decompress(Q, h, [&](int i, uint32_t hd) {
+            sink.put(i, addmod4(addmod4(ld_dw(J.out, g, i), gload32(df + i), Q), hd, Q));
+        });
+    }
 }
 
 // eval: one lane per gate
@@ -110,7 +149,14 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
     with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(J.in, g, i); }, &colour); });
     U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
     const uint32_t* row = (const uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
-    decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(row[i], hd, Q)); });
+    if constexpr (cmod_m<QD>::value != 0) {
+        uint32_t rw[QD::ndw];           // the whole row first: wide loads, none of them behind a store
+#pragma unroll
+        for (int i = 0; i < (int)QD::ndw; i++) rw[i] = row[i];
+        decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(rw[i], hd, Q)); });
+    } else {
+        decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(row[i], hd, Q)); });
+    }
     for (int i = (int)Q.ndw; i < (int)Q.nchunk * 4; i++) st_dw(J.out, g, i, 0);
 }
 

@@ -33,11 +33,16 @@ struct ModInfo {
     uint32_t c4;      // (128 - m) replicated (m <= 128), else 0
     uint32_t gc;      // dwords (4 digits each) per 32-bit super-digit of compress: m^(4 gc) < 2^32
     uint32_t Qc;      // m^(4 gc)
-    uint32_t gd;      // digits per super-digit of decompress: m^gd <= 2^15
-    uint32_t Qd;      // m^gd
+    // decompress: m = 2^tw * mo (mo odd).  A super-digit of gd digits is h mod m^gd; dividing by
+    // m^gd = 2^(tw gd) * mo^gd is a shift by dsh = tw*gd bits and a long division by Qd = mo^gd <= 2^15.
+    uint32_t tw;      // number of factors 2 in m
+    uint32_t omagic;  // ceil(2^32 / mo): floor(n / mo) = mulhi(n, omagic) for n < 2^24; 0 when mo = 1
+    uint32_t gd;      // digits per super-digit
+    uint32_t dsh;     // tw * gd
+    uint32_t Qd;      // mo^gd
     uint32_t Qdmagic; // ceil(2^(31+L) / Qd), L = ceil(log2 Qd): floor(n / Qd) = mulhi(n, Qdmagic) >> (L-1), n < 2^31
     uint32_t Qdshift; // L - 1
-    uint32_t Qdbits;  // floor(log2 Qd): every division by Qd shortens the dividend by at least this many bits
+    uint32_t Qdbits;  // dsh + floor(log2 Qd): every super-digit shortens the dividend by at least this many bits
     const uint32_t* dtab;  // device: [a = 0..m-1][ndw] packed digits of a * R_m mod m
 };
 
@@ -47,7 +52,18 @@ constexpr uint32_t ceil_log2(uint64_t v) { uint32_t l = 0; while ((1ull << l) < 
 constexpr uint32_t floor_log2(uint64_t v) { uint32_t l = 0; while ((2ull << l) <= v) l++; return l; }
 constexpr uint64_t ipow(uint64_t b, uint32_t e) { uint64_t r = 1; for (uint32_t i = 0; i < e; i++) r *= b; return r; }
 constexpr uint32_t gc_of(uint32_t m) { uint32_t g = 0; while (g < 8 && ipow(m, 4 * (g + 1)) < (1ull << 32)) g++; return g; }
-constexpr uint32_t gd_of(uint32_t m) { uint32_t g = 0; while (ipow(m, g + 1) <= (1ull << 15)) g++; return g; }
+constexpr uint32_t twos_of(uint32_t m) { uint32_t t = 0; while (!(m & 1)) { m >>= 1; t++; } return t; }
+// largest g with mo^g <= 2^15, the super-digit (mo^g - 1) * 2^(tw g) + ... below 2^32 and, for the digit
+// extraction, (m^g >> tw) below 2^24 (powers of two: at most 24 bits per super-digit)
+constexpr bool gd_ok(uint32_t m, uint32_t g) {
+    const uint32_t tw = twos_of(m);
+    const uint64_t mo = m >> tw, qo = ipow(mo, g);
+    if (qo > (1ull << 15)) return false;
+    if (tw * g + ceil_log2(qo) > 32) return false;
+    if (mo == 1 && tw * g > 24) return false;
+    return (ipow(m, g) >> tw) < (1ull << 24);
+}
+constexpr uint32_t gd_of(uint32_t m) { uint32_t g = 1; while (gd_ok(m, g + 1)) g++; return g; }
 }  // namespace cm
 
 template <uint32_t MOD, uint32_t LAM>
@@ -56,10 +72,12 @@ struct CMod {
     static constexpr uint32_t mmagic = (uint32_t)(((1ull << 32) + MOD - 1) / MOD);
     static constexpr uint32_t m4 = MOD * 0x01010101u, c4 = MOD <= 128 ? (128 - MOD) * 0x01010101u : 0;
     static constexpr uint32_t gc = cm::gc_of(MOD), Qc = (uint32_t)cm::ipow(MOD, 4 * gc);
-    static constexpr uint32_t gd = cm::gd_of(MOD), Qd = (uint32_t)cm::ipow(MOD, gd);
-    static constexpr uint32_t Qdshift = cm::ceil_log2(Qd) - 1;
-    static constexpr uint32_t Qdmagic = (uint32_t)(((1ull << (32 + Qdshift)) + Qd - 1) / Qd);
-    static constexpr uint32_t Qdbits = cm::floor_log2(Qd);
+    static constexpr uint32_t tw = cm::twos_of(MOD), mo = MOD >> tw;
+    static constexpr uint32_t omagic = (uint32_t)(((1ull << 32) + mo - 1) / mo);
+    static constexpr uint32_t gd = cm::gd_of(MOD), dsh = tw * gd, Qd = (uint32_t)cm::ipow(mo, gd);
+    static constexpr uint32_t Qdshift = Qd > 1 ? cm::ceil_log2(Qd) - 1 : 0;
+    static constexpr uint32_t Qdmagic = Qd > 1 ? (uint32_t)(((1ull << (32 + Qdshift)) + Qd - 1) / Qd) : 0;
+    static constexpr uint32_t Qdbits = dsh + cm::floor_log2(Qd);
     const uint32_t* dtab;
 };
 
@@ -88,17 +106,31 @@ DASH_HD uint32_t dot4(uint32_t a, uint32_t b) {
     return s;
 #endif
 }
+// load through a pointer that is known to address device global memory (pointers that were themselves
+// loaded from memory would otherwise be dereferenced with flat instructions, which also occupy the LDS queue)
+DASH_HD uint32_t gload32(const uint32_t* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return *(const __attribute__((address_space(1))) uint32_t*)p;
+#else
+    return *p;
+#endif
+}
 template <class MI> DASH_HD uint32_t div_m(uint32_t n, const MI& M) { return mulhi(n, M.mmagic); }           // n < 2^24
 template <class MI> DASH_HD uint32_t mod_m(uint32_t n, const MI& M) { return n - mul24(div_m(n, M), M.m); }  // n < 2^24
 DASH_HD uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xffu; }
 
+// 0xff in every byte of x whose top bit is set, 0x00 elsewhere (shifts and subtractions only: a
+// multiplication by 255 would run at a quarter of the rate)
+DASH_HD uint32_t ge_mask(uint32_t x) {
+    uint32_t hi = x & 0x80808080u;
+    return (hi - (hi >> 7)) | hi;
+}
 // (a + b) mod m on 4 packed digits, a, b < m per byte.
 template <class MI>
 DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
     if (M.m <= 128) {
         uint32_t t = a + b;                                       // bytes <= 2m-2 <= 254
-        uint32_t ge = ((t + M.c4) & 0x80808080u) >> 7;            // 1 where byte >= m
-        return t - (((ge << 8) - ge) & M.m4);
+        return t - (ge_mask(t + M.c4) & M.m4);
     }
     uint32_t r = 0;
     for (int b8 = 0; b8 < 4; b8++) {
@@ -113,8 +145,7 @@ template <class MI>
 DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const MI& M) {
     if (M.m <= 128) {
         uint32_t t = a + (M.m4 - b);                              // bytes in [1, 2m-1] <= 255
-        uint32_t ge = ((t + M.c4) & 0x80808080u) >> 7;
-        return t - (((ge << 8) - ge) & M.m4);
+        return t - (ge_mask(t + M.c4) & M.m4);
     }
     uint32_t r = 0;
     for (int b8 = 0; b8 < 4; b8++) {
@@ -169,8 +200,8 @@ DASH_HD U128 compress(const MI& M, LoadDw dw, uint32_t* colour) {
     for (int i = (int)M.ndw - 1; i >= 0; i--) {
         uint32_t w = dw(i);
         if (i == 0) w0 = w;
-        uint32_t v = dot4(w, wlo) + m2 * dot4(w, whi);      // < m^4
-        S = S * m4 + v;
+        uint32_t v = dot4(w, wlo) + mul24(m2, dot4(w, whi));     // < m^4; both factors below 2^17
+        S = (M.Qc < (1u << 24) ? mul24(S, m4) : S * m4) + v;     // S < Qc / m^4
         if (--left == 0) { muladd128(acc, M.Qc, S); S = 0; left = M.gc; }
     }
     *colour = w0 & 0xffu;
@@ -221,32 +252,40 @@ DASH_HD U128 prg_block(uint64_t elem, uint32_t slot, uint32_t layer, uint32_t do
 
 // ---------------------------------------------------------------------------------------------
 // decompress: digits floor(h / m^j) mod m, j = 0..lam-1, delivered as packed dwords emit(i, w)
-// for i = 0..ndw-1.  Long division of eight 16-bit limbs by the super-digit base Qd = m^gd <= 2^15
-// (every partial dividend r * 2^16 + limb is below 2^31, where the magic division is exact), then
-// gd digits out of every remainder.  After t divisions the dividend is below 2^(128 - t*Qdbits), so
-// the upper limbs are known to be zero and are skipped.
+// for i = 0..ndw-1.  With m = 2^tw * mo, a super-digit of gd digits is taken off the 128-bit number by
+// a shift (its low dsh bits) and a long division by Qd = mo^gd <= 2^15 over 16-bit half-words (every
+// partial dividend r * 2^16 + half is below 2^31, where the magic division is exact):
+//     h mod m^gd = ((h >> dsh) mod Qd) << dsh | (h & (2^dsh - 1)),   h div m^gd = (h >> dsh) div Qd.
+// After each super-digit the number is shorter by Qdbits bits; half-words known to be zero are skipped.
 // ---------------------------------------------------------------------------------------------
-struct Limbs { uint32_t l[8]; };
-
-DASH_HD Limbs to_limbs(const U128& h) {
-    Limbs x;
-#pragma unroll
-    for (int i = 0; i < 4; i++) { x.l[2 * i] = h.w[i] & 0xffffu; x.l[2 * i + 1] = h.w[i] >> 16; }
-    return x;
-}
-// x = floor(x / Qd) over the nl low limbs, returns x mod Qd
 template <class MI>
-DASH_HD uint32_t divrem_Qd(Limbs& x, const MI& M, uint32_t nl) {
+DASH_HD uint32_t take_superdigit(U128& x, const MI& M, uint32_t bits) {
+    uint32_t low = 0;
+    if (M.dsh) {
+        low = x.w[0] & ((1u << M.dsh) - 1u);
+#pragma unroll
+        for (int i = 0; i < 3; i++) x.w[i] = (x.w[i] >> M.dsh) | (x.w[i + 1] << (32 - M.dsh));
+        x.w[3] >>= M.dsh;
+        bits = bits > M.dsh ? bits - M.dsh : 0;
+    }
+    if (M.Qd == 1) return low;                       // power of two: nothing left to divide
+    const uint32_t nh = (bits + 15) / 16;            // significant half-words
     uint32_t r = 0;
 #pragma unroll
-    for (int i = 7; i >= 0; i--) {
-        if ((uint32_t)i >= nl) continue;
-        uint32_t cur = (r << 16) | x.l[i];
-        uint32_t q = mulhi(cur, M.Qdmagic) >> M.Qdshift;
-        r = cur - mul24(q, M.Qd);
-        x.l[i] = q;
+    for (int i = 3; i >= 0; i--) {
+        if ((uint32_t)(2 * i) >= nh) continue;
+        uint32_t w = x.w[i], q1 = 0;
+        if ((uint32_t)(2 * i + 1) < nh) {
+            uint32_t cur = (r << 16) | (w >> 16);
+            q1 = mulhi(cur, M.Qdmagic) >> M.Qdshift;
+            r = cur - mul24(q1, M.Qd);
+        }
+        uint32_t cur = (r << 16) | (w & 0xffffu);
+        uint32_t q0 = mulhi(cur, M.Qdmagic) >> M.Qdshift;
+        r = cur - mul24(q0, M.Qd);
+        x.w[i] = (q1 << 16) | q0;
     }
-    return r;
+    return (r << M.dsh) | low;
 }
 
 template <class MI, class Emit>
@@ -259,24 +298,32 @@ DASH_HD void decompress(const MI& M, const U128& h, Emit emit) {
         }
         return;
     }
-    Limbs x = to_limbs(h);
+    U128 x = h;
     uint32_t S = 0, have = 0;     // digits left in the current super-digit
-    uint32_t bits = 128;          // the dividend is below 2^bits
+    uint32_t bits = 128;          // the number is below 2^bits
     uint32_t w = 0;
 #pragma unroll
     for (uint32_t j = 0; j < M.lam; j++) {
         if (have == 0) {
-            S = divrem_Qd(x, M, (bits + 15) / 16);
+            S = take_superdigit(x, M, bits);
             bits = bits > M.Qdbits ? bits - M.Qdbits : 0;
             have = M.gd;
         }
-        uint32_t q = mulhi(S, M.mmagic);
+        uint32_t q = M.omagic ? mulhi(S >> M.tw, M.omagic) : (S >> M.tw);   // S div m = (S >> tw) div mo; omagic = 0: mo = 1
         uint32_t d = S - mul24(q, M.m);
         S = q; have--;
         w |= d << (8 * (j & 3));
         if ((j & 3) == 3) { emit((int)(j >> 2), w); w = 0; }
     }
     if (M.lam & 3) emit((int)(M.lam >> 2), w);
+}
+
+struct Limbs { uint32_t l[8]; };
+DASH_HD Limbs to_limbs(const U128& h) {
+    Limbs x;
+#pragma unroll
+    for (int i = 0; i < 4; i++) { x.l[2 * i] = h.w[i] & 0xffffu; x.l[2 * i + 1] = h.w[i] >> 16; }
+    return x;
 }
 
 // digit 0 alone: h mod m

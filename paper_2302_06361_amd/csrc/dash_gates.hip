@@ -17,29 +17,46 @@
 
 namespace dash {
 
+// AES tables in LDS: T0..T3, 4 KB, shared by the block.  Measured on MI355X (AES only, 2M lanes): this
+// layout 3.7e10 blocks/s, limited by LDS bank collisions; one copy of T0 per bank (32 KB) with T1..T3
+// rotated in registers 6.3e10, but the rotations and the per-lane copy offset cost about 160 more vector
+// instructions per block, and inside the gate kernels, where the vector ALU is the limit and the
+// collisions hide behind other waves' arithmetic, the replicated layout was 5 % slower.
+constexpr int kTabWords = 1024;
+
 struct LdsTab {
     const uint32_t* t;
     __device__ __forceinline__ uint32_t operator()(int r, uint32_t x) const { return t[r * 256 + x]; }
 };
 
-__device__ __forceinline__ void load_ttab(uint32_t* lds, const uint32_t* g) {
-    for (int i = threadIdx.x; i < 1024; i += blockDim.x) lds[i] = g[i];
+__device__ __forceinline__ LdsTab load_ttab(uint32_t* lds, const uint32_t* g) {
+    for (int i = threadIdx.x; i < kTabWords; i += blockDim.x) lds[i] = g[i];
     __syncthreads();
+    return LdsTab{lds};
+}
+
+// Blocks walk over tiles of kThreads lanes with a grid stride, so that the table copy in LDS is paid
+// once per block and not once per tile.
+__host__ inline uint32_t grid_x_for(uint64_t tiles, int njobs) {
+    uint64_t cap = 2560 / (uint64_t)njobs;           // about two resident rounds of blocks on 256 CUs
+    if (cap < 1) cap = 1;
+    return (uint32_t)(tiles < cap ? tiles : cap);
 }
 
 // ------------------------------------------------------------------------------------------ draw
 __global__ __launch_bounds__(kThreads) void k_draw(const DrawLaunch L) {
-    __shared__ uint32_t tt[1024];
-    load_ttab(tt, L.ttab);
-    LdsTab T{tt};
-    draw_body(L, blockIdx.x, blockIdx.y, threadIdx.x, T);
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) draw_body(L, tile, blockIdx.y, threadIdx.x, T);
 }
 
 int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->seed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    dim3 grid((L.n_elem + kThreads - 1) / kThreads, njobs);
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
     hipLaunchKernelGGL(k_draw, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
@@ -53,8 +70,17 @@ __global__ __launch_bounds__(kThreads) void k_affine(const AffineLaunch L) {
 int launch_affine(const dash_ctx* c, AffineLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.mods = c->d_mods;
-    dim3 grid((L.n_elem + kThreads - 1) / kThreads, njobs);
+    uint32_t nchunk = 1;
+    for (int j = 0; j < njobs; j++) {
+        AffineJob& J = L.jobs[j];
+        if (J.m < 2 || J.m > 255 || J.term_count == 0 || J.term_first + J.term_count > (uint32_t)kMaxTerms) return DASH_EINVAL;
+        J.unit = 1;
+        for (uint32_t t = 0; t < J.term_count; t++) if (L.terms[J.term_first + t].coef != 1) J.unit = 0;
+        nchunk = c->mods[J.m].nchunk > nchunk ? c->mods[J.m].nchunk : nchunk;
+    }
+    dim3 grid((uint32_t)(((uint64_t)L.n_elem * nchunk + kThreads - 1) / kThreads), njobs);
     hipLaunchKernelGGL(k_affine, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
@@ -63,12 +89,56 @@ int launch_affine(const dash_ctx* c, AffineLaunch& L, int njobs, hipStream_t s) 
 // ---------------------------------------------------------------------------------------- garble
 // One instantiation per output-modulus description: QD = ModInfo (any modulus, run-time constants) or
 // CMod<m, lam> for the hot moduli.  The input modulus is dispatched inside (its code is small).
+// Rows of 64 bytes or more (pitch a multiple of 16): a lane that stored its own row dword by dword would
+// touch 64 different cache lines with every store instruction.  Such rows are staged in LDS (row stride
+// one word more than the pitch, so the column accesses spread over the banks) and written by the whole
+// block, each lane 16 consecutive bytes, consecutive lanes consecutive pieces of a row.
+template <class QD> struct stage_rows { static constexpr bool value = false; static constexpr int ndw = 1; };
+template <uint32_t MOD, uint32_t LAM> struct stage_rows<CMod<MOD, LAM>> {
+    static constexpr int ndw = (LAM + 3) / 4;
+    static constexpr bool value = ndw >= 16 && ndw % 4 == 0;
+};
+struct StagedSink {
+    uint32_t* st;        // this lane's row in LDS
+    uint32_t* slot;      // where the row index goes
+    __device__ __forceinline__ void begin(uint8_t*, uint64_t row_index, uint32_t) { *slot = (uint32_t)row_index; }
+    __device__ __forceinline__ void put(int i, uint32_t w) { st[i] = w; }
+};
+
 template <class QD>
 __global__ __launch_bounds__(kThreads) void k_proj_garble(const GateLaunch L) {
-    __shared__ uint32_t tt[1024];
-    load_ttab(tt, L.ttab);
-    LdsTab T{tt};
-    garble_body<QD>(L, blockIdx.x, blockIdx.y, threadIdx.x, T);
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint64_t rows = (uint64_t)L.n_elem * L.jobs[blockIdx.y].p;
+    const uint32_t tiles = (uint32_t)((rows + kThreads - 1) / kThreads);
+    if constexpr (stage_rows<QD>::value) {
+        constexpr int ndw = stage_rows<QD>::ndw, stride = ndw + 1, pieces = ndw / 4;
+        __shared__ uint32_t stage[kThreads * stride];
+        __shared__ uint32_t srow[kThreads];
+        uint8_t* table = L.jobs[blockIdx.y].table;
+        for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+            srow[threadIdx.x] = 0xffffffffu;
+            StagedSink sink{stage + threadIdx.x * stride, srow + threadIdx.x};
+            garble_body<QD>(L, tile, blockIdx.y, threadIdx.x, T, sink);
+            __syncthreads();
+            for (int id = threadIdx.x; id < kThreads * pieces; id += kThreads) {
+                const int k = id / pieces, part = id - k * pieces;
+                const uint32_t r = srow[k];
+                if (r != 0xffffffffu) {
+                    const uint32_t* src = stage + k * stride + part * 4;
+                    uint32_t* dst = (uint32_t*)(table + (uint64_t)r * (ndw * 4) + part * 16);
+                    uint32_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
+                    dst[0] = v0; dst[1] = v1; dst[2] = v2; dst[3] = v3;
+                }
+            }
+            __syncthreads();
+        }
+    } else {
+        for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+            DirectSink sink;
+            garble_body<QD>(L, tile, blockIdx.y, threadIdx.x, T, sink);
+        }
+    }
 }
 
 typedef void (*GateKernel)(const GateLaunch);
@@ -85,6 +155,7 @@ static uint32_t common_q(const GateLaunch& L, int njobs) {
 int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
     uint32_t pmax = 0;
     for (int j = 0; j < njobs; j++) {
@@ -96,7 +167,7 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     uint64_t rows = (uint64_t)L.n_elem * pmax;
     uint64_t blocks = (rows + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffull) return DASH_ESIZE;
-    dim3 grid((uint32_t)blocks, njobs);
+    dim3 grid(grid_x_for(blocks, njobs), njobs);
     double units = 0, bytes = 0;
     for (int j = 0; j < njobs; j++) {
         const GateJob& J = L.jobs[j];
@@ -106,6 +177,7 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     }
     const uint32_t q = common_q(L, njobs);
     if (!q) return DASH_EINVAL;
+    if (rows >= (1ull << 32)) return DASH_ESIZE;      // staged rows carry a 32-bit row index
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
     hipLaunchKernelGGL(kGarbleKernels[hot_mod_index(c->mods[q])], grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
@@ -115,10 +187,10 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
 // ------------------------------------------------------------------------------------------ eval
 template <class QD>
 __global__ __launch_bounds__(kThreads) void k_proj_eval(const GateLaunch L) {
-    __shared__ uint32_t tt[1024];
-    load_ttab(tt, L.ttab);
-    LdsTab T{tt};
-    eval_body<QD>(L, blockIdx.x, blockIdx.y, threadIdx.x, T);
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) eval_body<QD>(L, tile, blockIdx.y, threadIdx.x, T);
 }
 #define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>>,
 static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo>, DASH_HOT_MODS(DASH_EVAL_K)};
@@ -127,13 +199,14 @@ static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo>, DASH_HOT_MODS(DA
 int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
     for (int j = 0; j < njobs; j++) {
         const GateJob& J = L.jobs[j];
         if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
         if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
     }
-    dim3 grid((L.n_elem + kThreads - 1) / kThreads, njobs);
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
     double bytes = 0;
     for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
     const uint32_t q = common_q(L, njobs);
@@ -146,17 +219,18 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
 
 // ----------------------------------------------------------------------------- half gate, evaluator
 __global__ __launch_bounds__(kThreads) void k_hg_finish(const HgLaunch L) {
-    __shared__ uint32_t tt[1024];
-    load_ttab(tt, L.ttab);
-    LdsTab T{tt};
-    hg_finish_body(L, blockIdx.x, blockIdx.y, threadIdx.x, T);
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) hg_finish_body(L, tile, blockIdx.y, threadIdx.x, T);
 }
 
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    dim3 grid((L.n_elem + kThreads - 1) / kThreads, njobs);
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
     hipLaunchKernelGGL(k_hg_finish, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;

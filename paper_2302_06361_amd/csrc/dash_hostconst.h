@@ -85,11 +85,16 @@ inline void fill_modinfo(ModInfo& M, int m, int rule) {
     M.c4 = m <= 128 ? (uint32_t)(128 - m) * 0x01010101u : 0;
     // the compile-time descriptions (CMod) use the same formulas
     M.gc = cm::gc_of(m); M.Qc = (uint32_t)cm::ipow(m, 4 * M.gc);
-    M.gd = cm::gd_of(m); M.Qd = (uint32_t)cm::ipow(m, M.gd);
-    uint32_t L = ceil_log2(M.Qd);
-    M.Qdmagic = (uint32_t)((((u128)1 << (31 + L)) + M.Qd - 1) / M.Qd);
-    M.Qdshift = L - 1;
-    M.Qdbits = cm::floor_log2(M.Qd);
+    M.tw = cm::twos_of(m);
+    const uint32_t mo = (uint32_t)m >> M.tw;
+    M.omagic = (uint32_t)(((1ull << 32) + mo - 1) / mo);
+    M.gd = cm::gd_of(m); M.dsh = M.tw * M.gd; M.Qd = (uint32_t)cm::ipow(mo, M.gd);
+    if (M.Qd > 1) {
+        uint32_t L = ceil_log2(M.Qd);
+        M.Qdmagic = (uint32_t)((((u128)1 << (31 + L)) + M.Qd - 1) / M.Qd);
+        M.Qdshift = L - 1;
+    }
+    M.Qdbits = M.dsh + cm::floor_log2(M.Qd);
 }
 
 }  // namespace hostconst

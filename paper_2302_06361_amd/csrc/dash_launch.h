@@ -72,7 +72,8 @@ struct DrawLaunch {
 };
 
 struct AffineJob {
-    uint32_t m, term_first, term_count, pad_;
+    uint32_t m, term_first, term_count;
+    uint32_t unit;       // 1 if every coefficient is 1
     LView out;
 };
 struct AffineLaunch {

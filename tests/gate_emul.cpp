@@ -91,7 +91,7 @@ int main(int argc, char** argv) {
     const uint64_t rows = (uint64_t)n * p;
     for (uint32_t bx = 0; bx < (rows + kThreads - 1) / kThreads; bx++)
         for (uint32_t tx = 0; tx < kThreads; tx++)
-            with_mod(Mq, [&](auto Qd) { garble_body<decltype(Qd)>(G, bx, 0, tx, HostTab()); });
+            with_mod(Mq, [&](auto Qd) { DirectSink sink; garble_body<decltype(Qd)>(G, bx, 0, tx, HostTab(), sink); });
 
     J.in = LView{cact.data(), (int64_t)16 * n, 16u};
     J.out = LView{cout.data(), (int64_t)16 * n, 16u};
