@@ -214,15 +214,24 @@ DASH_HD U128 compress(const MI& M, LoadDw dw, uint32_t* colour) {
 // integer.  T[r][x] = column r of MixColumns times S[x]; T[r] = T[0] rotated left by 8r bits.
 // rk: 44 round-key words in the same byte order.
 // ---------------------------------------------------------------------------------------------
+// three-input exclusive or (one v_bitop3_b32 on gfx950)
+DASH_HD uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+#if defined(__HIP_DEVICE_COMPILE__) && __has_builtin(__builtin_amdgcn_bitop3_b32)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+#else
+    return a ^ b ^ c;
+#endif
+}
+
 template <class Tab>
 DASH_HD void aes128_encrypt(uint32_t s[4], const uint32_t* rk, const Tab& T) {
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
 #pragma unroll
     for (int r = 1; r < 10; r++) {
-        uint32_t b0 = T(0, a0 & 0xff) ^ T(1, (a1 >> 8) & 0xff) ^ T(2, (a2 >> 16) & 0xff) ^ T(3, a3 >> 24) ^ rk[4 * r + 0];
-        uint32_t b1 = T(0, a1 & 0xff) ^ T(1, (a2 >> 8) & 0xff) ^ T(2, (a3 >> 16) & 0xff) ^ T(3, a0 >> 24) ^ rk[4 * r + 1];
-        uint32_t b2 = T(0, a2 & 0xff) ^ T(1, (a3 >> 8) & 0xff) ^ T(2, (a0 >> 16) & 0xff) ^ T(3, a1 >> 24) ^ rk[4 * r + 2];
-        uint32_t b3 = T(0, a3 & 0xff) ^ T(1, (a0 >> 8) & 0xff) ^ T(2, (a1 >> 16) & 0xff) ^ T(3, a2 >> 24) ^ rk[4 * r + 3];
+        uint32_t b0 = xor3(xor3(T(0, a0 & 0xff), T(1, (a1 >> 8) & 0xff), T(2, (a2 >> 16) & 0xff)), T(3, a3 >> 24), rk[4 * r + 0]);
+        uint32_t b1 = xor3(xor3(T(0, a1 & 0xff), T(1, (a2 >> 8) & 0xff), T(2, (a3 >> 16) & 0xff)), T(3, a0 >> 24), rk[4 * r + 1]);
+        uint32_t b2 = xor3(xor3(T(0, a2 & 0xff), T(1, (a3 >> 8) & 0xff), T(2, (a0 >> 16) & 0xff)), T(3, a1 >> 24), rk[4 * r + 2]);
+        uint32_t b3 = xor3(xor3(T(0, a3 & 0xff), T(1, (a0 >> 8) & 0xff), T(2, (a1 >> 16) & 0xff)), T(3, a2 >> 24), rk[4 * r + 3]);
         a0 = b0; a1 = b1; a2 = b2; a3 = b3;
     }
     // last round: SubBytes + ShiftRows only.  S[x] sits in byte 0 of T2, byte 1 of T3, byte 2 of T0, byte 3 of T1.
