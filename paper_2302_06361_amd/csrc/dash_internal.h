@@ -82,6 +82,9 @@ int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
 
 // linear layers (dash_linear.hip)
 int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s);
+// dense layers on the matrix cores (dash_gemm.hip)
+bool dense_mfma_wanted(const dash_layer* L, int64_t batch);
+int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s);
 
 inline LView view_of(const dash_labels* t, int i) { return LView{(uint8_t*)t->data[i], t->chunk_stride[i], 16u}; }
 

@@ -7,6 +7,7 @@
 //
 //   k_weights_prepare : int32 weights -> per-prime int8 residues in [0, p), rows padded to 64
 //   k_linear_direct   : any shape; one lane per (output value, 16-digit chunk)
+//   (dense layers that fill MFMA tiles go to k_dense_mfma in dash_gemm.hip)
 //   k_sumpool         : 2x2 sum, stride 2
 #include <string.h>
 
@@ -165,6 +166,7 @@ int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_label
         uint64_t p1 = (uint64_t)(c->prime[i] - 1);
         if (p1 * p1 * (uint64_t)K >= (1ull << 31)) return DASH_ESIZE;      // int32 accumulators must not overflow
     }
+    if (dense_mfma_wanted(L, batch)) return dense_mfma(c, L, garble, in, out, s);
     const int out_h = (in_h + 2 * pad - kh) / stride + 1, out_w = (in_w + 2 * pad - kw) / stride + 1;
     for (int i = 0; i < c->k; i++) {
         LinArgs A;

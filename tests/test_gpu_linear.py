@@ -72,3 +72,16 @@ def test_conv_vgg_block_shape():
 def test_sumpool():
     run_linear(8, 3, 10, 10, 16, 16, 1, 1, 0, 0, 0, False, 10, pool=True)
     run_linear(12, 2, 6, 4, 5, 5, 1, 1, 0, 0, 0, False, 11, pool=True)
+
+
+def test_dense_mfma_ragged_tiles_and_bias():
+    """dense layers large enough for the MFMA kernel: several K stages, ragged M, K and group tails"""
+    run_linear(12, 5, 1, 1, 500, 300, 1, 1, 0, -64, 63, True, 21)
+    run_linear(8, 7, 1, 1, 128, 257, 1, 1, 0, -8, 7, False, 22, garble=False)
+    run_linear(12, 3, 1, 1, 1030, 70, 1, 1, 0, -64, 63, True, 23, garble=False)
+
+
+def test_dense_mfma_config4_sample():
+    """config 4 shape on a slice: K = 4096 inputs (one-step reduction no longer applies for the larger
+    primes), 96 output rows, batch 2, all 12 primes, weights in [-64, 63]"""
+    run_linear(12, 2, 1, 1, 4096, 96, 1, 1, 0, -64, 63, False, 24)
