@@ -17,6 +17,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
+# 32-bit integer vector issue rate: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+# Figures taken from the rocprofv3 --pmc runs of this same command (profiles/k_proj_garble_lenet_b16_pmc.txt):
+# vector instructions per ciphertext row of k_proj_garble / per gate of k_proj_eval, averaged over the
+# launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per launch
+# (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up).
+PMC = dict(garble_valu_per_row=None, eval_valu_per_gate=None,
+           garble_fetch_bytes_per_launch=None, garble_write_bytes_per_launch=None)
 
 
 def gate_counts(net, k, n_digits):
@@ -80,13 +89,117 @@ def cpu_baseline(net, seconds_target=12.0):
                        % (repeat, done, count, dt))
 
 
+def kernel_line(pr, steps, bytes_per_unit_note=None):
+    """per-kernel figures from the library's own HIP-event instrumentation (events recorded around every
+    launch on the stream the kernel runs on)"""
+    if not pr["ms"]:
+        return None
+    sec = pr["ms"] * 1e-3
+    return dict(ms_per_step=pr["ms"] / steps, launches_per_step=pr["launches"] // steps,
+                avg_launch_ms=pr["ms"] / max(pr["launches"], 1), units_per_s=pr["units"] / sec,
+                gbytes_per_s=pr["bytes"] / sec / 1e9, units_per_launch=pr["units"] / max(pr["launches"], 1),
+                bytes_per_launch=pr["bytes"] / max(pr["launches"], 1))
+
+
+def read_profiles(ctx):
+    return {name: ctx.profile_read(kind) for name, kind in (("garble", 0), ("eval", 1), ("linear", 2))}
+
+
+def micro_projection(torch, workloads, reps=2):
+    """Config 3: 2^24 independent gates Z_p -> Z_q over the 12-prime base, grouped by (p, q)."""
+    from paper_2302_06361_amd import Context, ProjectionBatch
+    mb = workloads.proj_microbench(seed=3)
+    ctx = Context(mb["primes"], mb["seed"], workloads.DIGITS[12])
+    pb = ProjectionBatch(ctx, mb["pi"], mb["qi"])
+    a_all = torch.as_tensor(mb["a"][pb.order].astype("int16")).to(ctx.device)
+    gen = torch.Generator(device=ctx.device)
+    gen.manual_seed(3)
+    for G in pb.groups:
+        i, p, n = G["pi"], ctx.primes[G["pi"]], G["count"]
+        t = G["in0"].tensors[i]
+        t.copy_(torch.randint(0, p, t.shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+        R = torch.zeros(t.shape[0] * 16, dtype=torch.int16)
+        R[:ctx.lam(p)] = torch.as_tensor(ctx.offset(p).astype("int16"))
+        a = a_all[G["start"]:G["start"] + n].view(1, n, 1)
+        G["act"].tensors[i].copy_(((t.to(torch.int16) + a * R.to(ctx.device).view(-1, 1, 16)) % p).to(torch.uint8))
+        G["phi"].copy_(torch.randint(0, ctx.primes[G["qi"]], G["phi"].shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+    pb.garble(); pb.evaluate()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ctx.profile_enable(True)
+    read_profiles(ctx)
+    ev[0].record()
+    for _ in range(reps):
+        pb.garble()
+    ev[1].record()
+    for _ in range(reps):
+        pb.evaluate()
+    ev[2].record()
+    torch.cuda.synchronize()
+    ctx.profile_enable(False)
+    pr = read_profiles(ctx)
+    gms, ems = ev[0].elapsed_time(ev[1]) / reps, ev[1].elapsed_time(ev[2]) / reps
+    out = dict(workload="config 3: 2^24 gates Z_p->Z_q, (p,q) uniform over the 12-prime base, 144 grouped launches",
+               gates=pb.n, rows=pb.rows, table_bytes=pb.table_bytes,
+               garble_ms=gms, eval_ms=ems, garble_gates_per_s=pb.n / (gms * 1e-3), eval_gates_per_s=pb.n / (ems * 1e-3),
+               garble_rows_per_s=pb.rows / (gms * 1e-3), garble_table_GBps=pb.table_bytes / (gms * 1e-3) / 1e9,
+               garble_frac_of_hbm=pb.table_bytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_proj_eval=kernel_line(pr["eval"], reps)))
+    del pb
+    ctx.close()
+    torch.cuda.empty_cache()
+    return out
+
+
+def micro_contraction(torch, workloads, reps=5):
+    """Config 4: dense 4096 x 4096 on label tensors at batch 128, every prime of the 12-prime base."""
+    from paper_2302_06361_amd import DENSE, Context, Labels, Layer
+    mb = workloads.gemm_microbench(seed=4)
+    ctx = Context(mb["primes"], mb["seed"], workloads.DIGITS[12])
+    M, K, Bn = mb["M"], mb["K"], mb["batch"]
+    wp = ctx.weights_prepare(mb["W"])
+    x, y = Labels(ctx, Bn * K), Labels(ctx, Bn * M)
+    gen = torch.Generator(device=ctx.device)
+    gen.manual_seed(4)
+    for i, p in enumerate(ctx.primes):
+        t = x.tensors[i]
+        t.copy_(torch.randint(0, p, t.shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+    lay = Layer(DENSE, 1, Bn, in_c=K, out_c=M, weights=wp)
+    lam = sum(ctx.lam(p) for p in ctx.primes)
+    macs = M * K * Bn * lam
+    for _ in range(2):
+        ctx.eval_layer(lay, x, None, y)
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    read_profiles(ctx)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        ctx.eval_layer(lay, x, None, y)
+    e1.record()
+    torch.cuda.synchronize()
+    ctx.profile_enable(False)
+    pr = read_profiles(ctx)["linear"]
+    ms = e0.elapsed_time(e1) / reps
+    kms = pr["ms"] / max(pr["launches"], 1)
+    out = dict(workload="config 4: dense 4096x4096, weights in [-64,63], batch 128, 12 primes (%d label digits per value)" % lam,
+               ms=ms, label_mac_per_s=macs / (ms * 1e-3),
+               roofline=dict(bound="mfma", kernel="k_dense_mfma", unit="TOP/s", peak=INT8_MFMA_PEAK_TOPS,
+                             achieved=2 * macs / (kms * 1e-3) / 1e12, frac=2 * macs / (kms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+                             avg_launch_ms=kms, ops_per_launch=2 * macs, traffic=None))
+    ctx.close()
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--batch", type=int, default=16, help="batch elements of config 2 (16 = the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-micro", action="store_true", help="skip the config-3 and config-4 microbenchmarks")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures ONE GPU (every box has one); --gpus %d is not supported" % a.gpus, file=sys.stderr)
@@ -95,7 +208,7 @@ def main():
     import torch
 
     import workloads
-    from paper_2302_06361_amd import Context, GarbledNetwork, binding
+    from paper_2302_06361_amd import Context, GarbledNetwork
 
     net = workloads.lenet(seed=2, batch=a.batch)
     ctx = Context(net["primes"], net["seed"], net["digits"])
@@ -105,6 +218,12 @@ def main():
     lam_sum = sum(ctx.lam(p) for p in ctx.primes)
     gates = gate_counts(net, k, n)
     macs = mac_counts(net, lam_sum)
+
+    # a plain copy of known size, for scaling the HBM counters of a rocprofv3 --pmc run of this command
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=ctx.device)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    del src, dst
 
     def step(ev=None):
         if ev:
@@ -125,7 +244,6 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(True)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(a.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -133,32 +251,39 @@ def main():
         step(evs[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ctx.profile_enable(False)
     phase = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / a.steps for i in range(4)]   # ms: garble, encode, eval, decode
-    prof = {name: ctx.profile_read(kind) for name, kind in (("garble", 0), ("eval", 1), ("linear", 2))}
     ok = bool(g.valid.all().item())
-
     ms_step = wall * 1e3 / a.steps
-    pg = prof["garble"]
-    garble_kernel = dict(
-        bound="hbm", unit="GB/s", peak=HBM_PEAK_GBS,
-        achieved=pg["bytes"] / (pg["ms"] * 1e-3) / 1e9 if pg["ms"] else None,
-        kernel="k_proj_garble", launches_per_step=pg["launches"] // a.steps,
-        avg_launch_ms=pg["ms"] / max(pg["launches"], 1),
-        rows_per_s=pg["units"] / (pg["ms"] * 1e-3) if pg["ms"] else None,
-        traffic=None)
-    garble_kernel["frac"] = garble_kernel["achieved"] / HBM_PEAK_GBS if garble_kernel["achieved"] else None
-    pe = prof["eval"]
-    eval_kernel = dict(bound="hbm", unit="GB/s", peak=HBM_PEAK_GBS, kernel="k_proj_eval",
-                       achieved=pe["bytes"] / (pe["ms"] * 1e-3) / 1e9 if pe["ms"] else None,
-                       gates_per_s=pe["units"] / (pe["ms"] * 1e-3) if pe["ms"] else None)
-    eval_kernel["frac"] = eval_kernel["achieved"] / HBM_PEAK_GBS if eval_kernel["achieved"] else None
-    pl = prof["linear"]
-    linear_kernel = dict(bound="mfma", unit="TOP/s", peak=INT8_MFMA_PEAK_TOPS,
-                         achieved=2 * pl["units"] / (pl["ms"] * 1e-3) / 1e12 if pl["ms"] else None,
-                         label_mac_per_s=pl["units"] / (pl["ms"] * 1e-3) if pl["ms"] else None,
-                         note="config-2 layers are tiny (launch-bound); see the config-4 line in DESIGN.md")
-    linear_kernel["frac"] = linear_kernel["achieved"] / INT8_MFMA_PEAK_TOPS if linear_kernel["achieved"] else None
+
+    # the same steps again with an event pair around every kernel launch (the library's instrumentation,
+    # on the launch stream): per-kernel durations for the roofline.  Not part of the timed region above.
+    ctx.profile_enable(True)
+    read_profiles(ctx)
+    for s in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(False)
+    prof = read_profiles(ctx)
+
+    kg, ke, kl = (kernel_line(prof[n_], a.steps) for n_ in ("garble", "eval", "linear"))
+    valu = PMC["garble_valu_per_row"]
+    roofline = dict(
+        kernel="k_proj_garble", bound="alu", unit="Tlane-op/s (32-bit integer vector operations)", peak=ALU_PEAK_TOPS,
+        achieved=kg["units_per_s"] * valu / 1e12 if valu else None,
+        avg_launch_ms=kg["avg_launch_ms"], launches_per_step=kg["launches_per_step"],
+        rows_per_launch=kg["units_per_launch"], rows_per_s=kg["units_per_s"], lane_ops_per_row=valu,
+        hbm_algorithmic_GBps=kg["gbytes_per_s"], hbm_frac=kg["gbytes_per_s"] / HBM_PEAK_GBS,
+        algorithmic_bytes_per_launch=kg["bytes_per_launch"],
+        traffic=(PMC["garble_fetch_bytes_per_launch"] + PMC["garble_write_bytes_per_launch"])
+        if PMC["garble_fetch_bytes_per_launch"] is not None else None)
+    roofline["frac"] = roofline["achieved"] / ALU_PEAK_TOPS if roofline["achieved"] else None
+    ev_valu = PMC["eval_valu_per_gate"]
+    roofline_eval = dict(kernel="k_proj_eval", bound="alu", unit=roofline["unit"], peak=ALU_PEAK_TOPS,
+                         achieved=ke["units_per_s"] * ev_valu / 1e12 if ev_valu else None,
+                         avg_launch_ms=ke["avg_launch_ms"], launches_per_step=ke["launches_per_step"],
+                         gates_per_s=ke["units_per_s"], hbm_algorithmic_GBps=ke["gbytes_per_s"],
+                         hbm_frac=ke["gbytes_per_s"] / HBM_PEAK_GBS)
+    roofline_eval["frac"] = roofline_eval["achieved"] / ALU_PEAK_TOPS if roofline_eval["achieved"] else None
 
     out = dict(
         metric="label-MAC/s + projection gates/s (garble & eval); ms/inference, 1 GPU",
@@ -172,13 +297,21 @@ def main():
         outputs_valid=ok,
         garble_gates_per_s=gates / (phase[0] * 1e-3),
         eval_gates_per_s=gates / (phase[2] * 1e-3),
-        label_mac_per_s_eval_linear=prof["linear"]["units"] / (prof["linear"]["ms"] * 1e-3) if prof["linear"]["ms"] else None,
+        ms_per_inference=ms_step / a.batch,
         ms_per_inference_eval=phase[2] / a.batch,
         ms_per_inference_garble=phase[0] / a.batch,
         phase_ms=dict(garble=phase[0], encode=phase[1], eval=phase[2], decode=phase[3]),
         gates_per_step=gates, label_macs_per_step=2 * macs,
-        roofline=garble_kernel, roofline_eval_kernel=eval_kernel, roofline_linear_kernel=linear_kernel,
+        roofline=roofline, roofline_eval_kernel=roofline_eval,
+        linear_kernels_config2=dict(ms_per_step=kl["ms_per_step"], label_mac_per_s=kl["units_per_s"],
+                                    note="config-2 linear layers are tiny (launch-bound); config 4 below is the contraction figure"),
     )
+    del g
+    ctx.close()
+    torch.cuda.empty_cache()
+    if not a.no_micro:
+        out["config3_projection_gates"] = micro_projection(torch, workloads)
+        out["config4_contraction"] = micro_contraction(torch, workloads)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(net)
     print(json.dumps(out))

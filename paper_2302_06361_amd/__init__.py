@@ -6,4 +6,5 @@ step of the path runs in the kernels of libdash.so; there is no CPU fallback.
 """
 from .binding import (Context, Labels, Layer, DashError, lib_path,  # noqa: F401
                       DENSE, CONV2D, SUMPOOL, RELU, SCALE, SIGN, PROJ, LAMBDA_CEIL, LAMBDA_FLOOR)
-from .network import GarbledNetwork  # noqa: F401
+from .network import GarbledNetwork, StreamedNetwork  # noqa: F401
+from .grouped import ProjectionBatch  # noqa: F401

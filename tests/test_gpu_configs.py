@@ -1,0 +1,192 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times.  Where the oracle cannot run the whole size in seconds it runs a sample from the seeds alone (one
+batch element, runs of consecutive gates) and the rest is covered by properties that hold at any size:
+decoded outputs equal the plain integer evaluation, and active = zero + value * R_p on every boundary
+(Sec. Arithmetic Garbled Circuits, label invariant)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import both
+from oracle import capi, plain
+from oracle import net as onet
+
+pytestmark = pytest.mark.gpu
+
+
+def check_invariant(ctx, zero, act, ring_values, what):
+    """act == zero + (value mod p) * R_p, digit by digit, for every residue (device-side comparison of
+    buffers; the values come from the plain evaluation)."""
+    v = torch.as_tensor(np.asarray(ring_values, dtype=np.int64)).to(ctx.device)
+    for i, p in enumerate(ctx.primes):
+        if zero.tensors[i] is None:
+            continue
+        nch = zero.tensors[i].shape[0]
+        R = np.zeros(nch * 16, np.int16)
+        R[:ctx.lam(p)] = ctx.offset(p)
+        Rt = torch.as_tensor(R).to(ctx.device).view(nch, 1, 16)
+        n = zero.n_elem
+        z = zero.tensors[i][:, :n, :].to(torch.int16)
+        want = (z + (v % p).to(torch.int16).view(1, n, 1) * Rt) % p
+        bad = (want != act.tensors[i][:, :n, :].to(torch.int16)).any(dim=2).any(dim=0)
+        assert not bool(bad.any().item()), "%s residue %d: invariant broken at element %d" % (
+            what, i, int(torch.nonzero(bad)[0].item()))
+
+
+def segment_sizes(orc, kind, repeat=1):
+    """bytes per element of every table segment of an activation layer, in slot order (the table format:
+    segment = [gate][row][pitch], rows = input modulus, pitch = 4 * ceil(lambda_out / 4))"""
+    k, n = orc.k, len(orc.digits)
+    m = [orc.mj(j) for j in range(1, n + 1)]
+    pitch = lambda q: 4 * ((orc.lam(q) + 3) // 4)
+
+    def sign(first):
+        out = [orc.primes[i] * pitch(m[j]) for i in range(first, k) for j in range(n)]
+        out += [m[j] * pitch(m[j - 1]) for j in range(1, n)]
+        out.append(m[0] * pitch(2))
+        return out
+    if kind == "relu":
+        out = sign(0)
+        for i in range(k):
+            p = orc.primes[i]
+            out += [p * pitch(p), 2 * pitch(p), 2 * 4]
+        assert sum(out) == orc.relu_bytes_per_elem()
+        return out
+    out = []
+    for _ in range(repeat):
+        out += [2 * pitch(orc.primes[i]) for i in range(1, k)] + sign(1)
+    assert sum(out) == repeat * orc.scale_bytes_per_elem()
+    return out
+
+
+def test_config2_lenet_batch16_full():
+    """Config 2 at full size.  Batch element 11 of 16 is recomputed by the oracle from the seeds: its
+    labels on every boundary and its slice of every table segment must agree byte for byte.  All 16
+    decoded outputs against the plain evaluation; the label invariant on every boundary."""
+    from paper_2302_06361_amd import Context, GarbledNetwork
+    net = workloads.lenet(seed=2, batch=16)
+    b = 11
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    g = GarbledNetwork(ctx, net)
+    g.garble()
+    g.encode(torch.as_tensor(net["x"]).to(ctx.device))
+    g.evaluate()
+    values, valid = g.decode()
+    torch.cuda.synchronize()
+    P = int(np.prod(net["primes"]))
+    pv = plain.run_network(net["layers"], net["x"], P, 16)
+    assert valid.cpu().numpy().all()
+    assert (values.cpu().numpy() == plain.to_signed(pv[-1], P)).all()
+    for i in range(len(g.zero)):
+        check_invariant(ctx, g.zero[i], g.act[i], pv[i], "boundary %d" % i)
+
+    print("oracle: batch element %d" % b, flush=True)
+    ref = onet.run(net, 1, b, 0, keep=True)
+    orc = onet.make_oracle(net)
+    for i in range(len(g.zero)):
+        n = g.sizes[i] // 16
+        for r in range(ctx.k):
+            assert (g.zero[i].slice(b * n, (b + 1) * n).to_numpy(r) == ref["gb"]["zero"][i][r]).all(), ("zero", i, r)
+            assert (g.act[i].slice(b * n, (b + 1) * n).to_numpy(r) == ref["acts"][i][r]).all(), ("act", i, r)
+    for li, L in enumerate(net["layers"]):
+        if L["id"] not in ref["gb"]["tables"]:
+            continue
+        want = ref["gb"]["tables"][L["id"]]
+        n = L["n"]
+        E = 16 * n
+        before = 0
+        for sz in segment_sizes(orc, L["kind"], L.get("repeat", 1)):
+            got = g.tables[li][E * before + b * n * sz:E * before + (b + 1) * n * sz].cpu().numpy()
+            assert (got == want[n * before:n * (before + sz)]).all(), "layer %d segment at %d" % (L["id"], before)
+            before += sz
+        assert n * before == want.size
+    assert (values.cpu().numpy()[b * 10:(b + 1) * 10] == ref["values"]).all()
+
+
+def test_config3_projection_microbenchmark_full():
+    """Config 3 at full size: 2^24 gates, (p, q) uniform over the 12-prime base, grouped by pair.  Runs of
+    consecutive gates in every sixth group are recomputed by the oracle (zero labels, table rows,
+    evaluated labels); every gate must evaluate to out0 + phi(a) * R_q."""
+    from paper_2302_06361_amd import ProjectionBatch
+    mb = workloads.proj_microbench(seed=3)
+    ctx, orc = both(12, seed=mb["seed"])
+    pb = ProjectionBatch(ctx, mb["pi"], mb["qi"], layer_id=1)
+    assert pb.n == 1 << 24 and len(pb.groups) == 144
+    a_all = mb["a"][pb.order]
+    keep = {}
+    for gi, G in enumerate(pb.groups):
+        p, q, n = ctx.primes[G["pi"]], ctx.primes[G["qi"]], G["count"]
+        gen = workloads.rng(3, 1000 + gi)
+        in0 = workloads.uniform_labels(gen, n, ctx.lam(p), p)
+        phi = workloads.proj_phi(gen, n, p, q)
+        a = a_all[G["start"]:G["start"] + n].astype(np.int64)
+        act = ((in0.astype(np.int16) + a[:, None].astype(np.int16) * orc.delta(p).astype(np.int16)[None, :]) % p).astype(np.uint8)
+        G["in0"].from_numpy(G["pi"], in0)
+        G["act"].from_numpy(G["pi"], act)
+        G["phi"].copy_(torch.as_tensor(phi))
+        if gi % 6 == 0:
+            off = int(gen.integers(0, n - 40))
+            keep[gi] = (off, in0[off:off + 40].copy(), act[off:off + 40].copy(), phi[off:off + 40].copy())
+        G["f"] = torch.as_tensor(phi[np.arange(n), a].astype(np.int16)).to(ctx.device)
+    print("inputs uploaded", flush=True)
+    pb.garble()
+    pb.evaluate()
+    torch.cuda.synchronize()
+    for gi, G in enumerate(pb.groups):
+        q, j, n = ctx.primes[G["qi"]], G["qi"], G["count"]
+        nch = G["out"].tensors[j].shape[0]
+        R = np.zeros(nch * 16, np.int16)
+        R[:ctx.lam(q)] = orc.delta(q)
+        Rt = torch.as_tensor(R).to(ctx.device).view(nch, 1, 16)
+        want = (G["out0"].tensors[j].to(torch.int16) + G["f"].view(1, n, 1) * Rt) % q
+        assert bool((want == G["out"].tensors[j].to(torch.int16)).all().item()), "group %d: out != out0 + phi(a) R_q" % gi
+    for gi, (off, in0, act, phi) in keep.items():
+        G = pb.groups[gi]
+        p, q = ctx.primes[G["pi"]], ctx.primes[G["qi"]]
+        rout0, rtable = orc.proj_garble(p, q, in0, phi, 1, 0, G["start"] + off)
+        rout = orc.proj_eval(p, q, act, rtable, 1, 0, G["start"] + off)
+        assert (G["out0"].slice(off, off + 40).to_numpy(G["qi"]) == rout0).all(), gi
+        assert (G["out"].slice(off, off + 40).to_numpy(G["qi"]) == rout).all(), gi
+        rb = p * ctx.pitch(q)
+        assert (G["table"][off * rb:(off + 40) * rb].cpu().numpy() == rtable.reshape(-1)).all(), gi
+
+
+def vgg_check(net, batch, exact):
+    from paper_2302_06361_amd import Context, StreamedNetwork
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    g = StreamedNetwork(ctx, net, batch=batch)
+    P = int(np.prod(net["primes"]))
+    x = net["x"][:batch * net["n_in"]]
+    pv = plain.run_network(net["layers"], x, P, batch)
+    ref = onet.run(net, batch, 0, 0, keep=True) if exact else None
+
+    def boundary(i, zero, act):
+        check_invariant(ctx, zero, act, pv[i], "boundary %d" % i)
+        if exact:
+            for r in range(ctx.k):
+                assert (zero.to_numpy(r) == ref["gb"]["zero"][i][r]).all(), ("zero", i, r)
+                assert (act.to_numpy(r) == ref["acts"][i][r]).all(), ("act", i, r)
+            if i and net["layers"][i - 1]["id"] in ref["gb"]["tables"]:
+                want = ref["gb"]["tables"][net["layers"][i - 1]["id"]]
+                assert (g.table[:want.size].cpu().numpy() == want).all(), ("tables", i)
+    values, valid = g.run(torch.as_tensor(x).to(ctx.device), boundary)
+    torch.cuda.synchronize()
+    assert valid.cpu().numpy().all()
+    assert (values.cpu().numpy() == plain.to_signed(pv[-1], P)).all()
+    return g
+
+
+def test_config5_vgg_shape_reduced_exact():
+    """The VGG-shaped network of config 5 (12 primes, 3x3 convolutions with padding, three pooled blocks,
+    scale 2^5) at reduced width and image size, every byte against the oracle, layer by layer in the
+    streamed mode config 5 needs."""
+    vgg_check(workloads.vgg(seed=5, batch=2, width=(3, 4, 5), hw=8), 2, exact=True)
+
+
+def test_config5_vgg_full_width_one_image():
+    """Config 5 at its real layer shapes: one image of the batch of 64 (the tables of one image already
+    take tens of GB, so the batch is streamed image by image and layer by layer).  Decoded outputs against
+    the plain evaluation and the label invariant on every boundary."""
+    g = vgg_check(workloads.vgg(seed=5, batch=64), 1, exact=False)
+    print("config 5: %.1f GB of tables per image" % (g.table_bytes / 1e9))
