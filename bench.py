@@ -24,8 +24,9 @@ ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # vector instructions per ciphertext row of k_proj_garble / per gate of k_proj_eval, averaged over the
 # launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per launch
 # (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up).
-PMC = dict(garble_valu_per_row=None, eval_valu_per_gate=None,
-           garble_fetch_bytes_per_launch=None, garble_write_bytes_per_launch=None)
+PMC = dict(garble_valu_per_row=739.2, eval_valu_per_gate=659.0,
+           garble_fetch_bytes_per_launch=7169701 * 1024 * 2.0 / 1188,     # FETCH_SIZE reads 0.5 KiB per KiB copied
+           garble_write_bytes_per_launch=60526835 * 1024 * 1.0 / 1188)    # WRITE_SIZE reads 1.0 KiB per KiB copied
 
 
 def gate_counts(net, k, n_digits):
@@ -200,6 +201,7 @@ def main():
     ap.add_argument("--batch", type=int, default=16, help="batch elements of config 2 (16 = the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true", help="skip the config-3 and config-4 microbenchmarks")
+    ap.add_argument("--only", choices=["config3", "config4"], help="run one microbenchmark alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures ONE GPU (every box has one); --gpus %d is not supported" % a.gpus, file=sys.stderr)
@@ -209,6 +211,10 @@ def main():
 
     import workloads
     from paper_2302_06361_amd import Context, GarbledNetwork
+
+    if a.only:
+        print(json.dumps(micro_projection(torch, workloads) if a.only == "config3" else micro_contraction(torch, workloads)))
+        return
 
     net = workloads.lenet(seed=2, batch=a.batch)
     ctx = Context(net["primes"], net["seed"], net["digits"])

@@ -223,22 +223,24 @@ DASH_HD uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
 #endif
 }
 
+// Tab: the T-tables.  T.template at<R, B>(w) is entry (byte B of w) of table R; the accessor gets the whole
+// word so that a table layout can build its address from the byte in place.
 template <class Tab>
 DASH_HD void aes128_encrypt(uint32_t s[4], const uint32_t* rk, const Tab& T) {
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
 #pragma unroll
     for (int r = 1; r < 10; r++) {
-        uint32_t b0 = xor3(xor3(T(0, a0 & 0xff), T(1, (a1 >> 8) & 0xff), T(2, (a2 >> 16) & 0xff)), T(3, a3 >> 24), rk[4 * r + 0]);
-        uint32_t b1 = xor3(xor3(T(0, a1 & 0xff), T(1, (a2 >> 8) & 0xff), T(2, (a3 >> 16) & 0xff)), T(3, a0 >> 24), rk[4 * r + 1]);
-        uint32_t b2 = xor3(xor3(T(0, a2 & 0xff), T(1, (a3 >> 8) & 0xff), T(2, (a0 >> 16) & 0xff)), T(3, a1 >> 24), rk[4 * r + 2]);
-        uint32_t b3 = xor3(xor3(T(0, a3 & 0xff), T(1, (a0 >> 8) & 0xff), T(2, (a1 >> 16) & 0xff)), T(3, a2 >> 24), rk[4 * r + 3]);
+        uint32_t b0 = xor3(xor3(T.template at<0, 0>(a0), T.template at<1, 1>(a1), T.template at<2, 2>(a2)), T.template at<3, 3>(a3), rk[4 * r + 0]);
+        uint32_t b1 = xor3(xor3(T.template at<0, 0>(a1), T.template at<1, 1>(a2), T.template at<2, 2>(a3)), T.template at<3, 3>(a0), rk[4 * r + 1]);
+        uint32_t b2 = xor3(xor3(T.template at<0, 0>(a2), T.template at<1, 1>(a3), T.template at<2, 2>(a0)), T.template at<3, 3>(a1), rk[4 * r + 2]);
+        uint32_t b3 = xor3(xor3(T.template at<0, 0>(a3), T.template at<1, 1>(a0), T.template at<2, 2>(a1)), T.template at<3, 3>(a2), rk[4 * r + 3]);
         a0 = b0; a1 = b1; a2 = b2; a3 = b3;
     }
     // last round: SubBytes + ShiftRows only.  S[x] sits in byte 0 of T2, byte 1 of T3, byte 2 of T0, byte 3 of T1.
-    s[0] = ((T(2, a0 & 0xff) & 0xffu) | (T(3, (a1 >> 8) & 0xff) & 0xff00u) | (T(0, (a2 >> 16) & 0xff) & 0xff0000u) | (T(1, a3 >> 24) & 0xff000000u)) ^ rk[40];
-    s[1] = ((T(2, a1 & 0xff) & 0xffu) | (T(3, (a2 >> 8) & 0xff) & 0xff00u) | (T(0, (a3 >> 16) & 0xff) & 0xff0000u) | (T(1, a0 >> 24) & 0xff000000u)) ^ rk[41];
-    s[2] = ((T(2, a2 & 0xff) & 0xffu) | (T(3, (a3 >> 8) & 0xff) & 0xff00u) | (T(0, (a0 >> 16) & 0xff) & 0xff0000u) | (T(1, a1 >> 24) & 0xff000000u)) ^ rk[42];
-    s[3] = ((T(2, a3 & 0xff) & 0xffu) | (T(3, (a0 >> 8) & 0xff) & 0xff00u) | (T(0, (a1 >> 16) & 0xff) & 0xff0000u) | (T(1, a2 >> 24) & 0xff000000u)) ^ rk[43];
+    s[0] = ((T.template at<2, 0>(a0) & 0xffu) | (T.template at<3, 1>(a1) & 0xff00u) | (T.template at<0, 2>(a2) & 0xff0000u) | (T.template at<1, 3>(a3) & 0xff000000u)) ^ rk[40];
+    s[1] = ((T.template at<2, 0>(a1) & 0xffu) | (T.template at<3, 1>(a2) & 0xff00u) | (T.template at<0, 2>(a3) & 0xff0000u) | (T.template at<1, 3>(a0) & 0xff000000u)) ^ rk[41];
+    s[2] = ((T.template at<2, 0>(a2) & 0xffu) | (T.template at<3, 1>(a3) & 0xff00u) | (T.template at<0, 2>(a0) & 0xff0000u) | (T.template at<1, 3>(a1) & 0xff000000u)) ^ rk[42];
+    s[3] = ((T.template at<2, 0>(a3) & 0xffu) | (T.template at<3, 1>(a0) & 0xff00u) | (T.template at<0, 2>(a1) & 0xff0000u) | (T.template at<1, 3>(a2) & 0xff000000u)) ^ rk[43];
 }
 
 // h = AES(X) xor X with X = K xor tweak; tweak = elem:u64 | slot:u32 | layer:u16 | 0:u16.

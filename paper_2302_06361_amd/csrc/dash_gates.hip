@@ -17,16 +17,34 @@
 
 namespace dash {
 
-// AES tables in LDS: T0..T3, 4 KB, shared by the block.  Measured on MI355X (AES only, 2M lanes): this
-// layout 3.7e10 blocks/s, limited by LDS bank collisions; one copy of T0 per bank (32 KB) with T1..T3
-// rotated in registers 6.3e10, but the rotations and the per-lane copy offset cost about 160 more vector
-// instructions per block, and inside the gate kernels, where the vector ALU is the limit and the
-// collisions hide behind other waves' arithmetic, the replicated layout was 5 % slower.
+// AES tables in LDS, two layouts.
+//
+// LdsTab: T0..T3 once, 4 KB, shared by the block.  A wave's 64 look-ups fall on the 32 banks at random
+// (bank = index mod 32): in the gate kernels two thirds of the LDS cycles are bank collisions
+// (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE = 0.68).
+//
+// BankTab: every table entry once per bank, 128 KB, for blocks of 1024 lanes (one block per CU, four waves
+// per SIMD).  Byte address of entry x of table R for a lane that owns bank b:
+//     (R >> 1) * 65536 + x * 256 + (R & 1) * 128 + b * 4
+// so a look-up never collides, and the address still costs ONE instruction, a byte permute: byte 0 <- 4b
+// (from the lane's constant), byte 1 <- the state byte, byte 2 <- R >> 1; (R & 1) * 128 goes into the
+// instruction's offset.
+//
+// Measured on the LeNet batch-16 step: with BankTab the collisions are gone (counter reads 0) and the LDS
+// is active a third as long, but the gate kernels take the same time (garble 2.64e10 rows/s against
+// 2.76e10) and small launches get slower (128 KB to fill per block, one block per CU): the vector ALU is
+// the limit (about 80 % busy in either layout) and the collisions were hidden behind other waves'
+// arithmetic.  kBankedTables chooses the layout at compile time; the shared tables are the default.
+constexpr bool kBankedTables = false;
 constexpr int kTabWords = 1024;
+constexpr int kBankTabWords = 32768;
+constexpr int kGateThreads = kBankedTables ? 1024 : kThreads;   // lanes per block of the draw / garble / eval kernels
+constexpr int kGateTiles = kGateThreads / kThreads;             // tiles of kThreads lanes a block works on at a time
+constexpr int kGateTabWords = kBankedTables ? kBankTabWords : kTabWords;
 
 struct LdsTab {
     const uint32_t* t;
-    __device__ __forceinline__ uint32_t operator()(int r, uint32_t x) const { return t[r * 256 + x]; }
+    template <int R, int B> __device__ __forceinline__ uint32_t at(uint32_t w) const { return t[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
 };
 
 __device__ __forceinline__ LdsTab load_ttab(uint32_t* lds, const uint32_t* g) {
@@ -35,6 +53,31 @@ __device__ __forceinline__ LdsTab load_ttab(uint32_t* lds, const uint32_t* g) {
     return LdsTab{lds};
 }
 
+struct BankTab {
+    const uint8_t* t;
+    uint32_t lane;       // byte 0: 4 * bank, byte 1: 1
+    template <int R, int B> __device__ __forceinline__ uint32_t at(uint32_t w) const {
+        // v_perm_b32(hi = w, lo = lane): selector 0..3 bytes of lane, 4..7 bytes of w, 0x0c zero
+        constexpr uint32_t sel = 0x0c000000u | ((R >> 1) ? 0x00010000u : 0x000c0000u) | ((4u + B) << 8);
+        const uint32_t a = __builtin_amdgcn_perm(w, lane, sel);
+        return *(const uint32_t*)(t + a + (R & 1) * 128);
+    }
+};
+
+__device__ __forceinline__ BankTab load_banktab(uint32_t* lds, const uint32_t* g) {
+    for (int i = threadIdx.x; i < kBankTabWords; i += blockDim.x) {
+        const int region = i >> 14, x = (i >> 6) & 255, half = (i >> 5) & 1;
+        lds[i] = g[(region * 2 + half) * 256 + x];
+    }
+    __syncthreads();
+    return BankTab{(const uint8_t*)lds, ((threadIdx.x & 31u) << 2) | 0x100u};
+}
+
+template <bool Banked> struct gate_tab { typedef LdsTab type; static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_ttab(lds, g); } };
+template <> struct gate_tab<true> { typedef BankTab type; static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_banktab(lds, g); } };
+typedef gate_tab<kBankedTables>::type GateTab;
+__device__ __forceinline__ GateTab load_gate_tab(uint32_t* lds, const uint32_t* g) { return gate_tab<kBankedTables>::load(lds, g); }
+
 // Blocks walk over tiles of kThreads lanes with a grid stride, so that the table copy in LDS is paid
 // once per block and not once per tile.
 __host__ inline uint32_t grid_x_for(uint64_t tiles, int njobs) {
@@ -42,13 +85,22 @@ __host__ inline uint32_t grid_x_for(uint64_t tiles, int njobs) {
     if (cap < 1) cap = 1;
     return (uint32_t)(tiles < cap ? tiles : cap);
 }
+// the same for blocks of kGateThreads lanes (kGateTiles tiles at a time)
+__host__ inline uint32_t gate_grid_x_for(uint64_t tiles, int njobs) {
+    if (kGateTiles == 1) return grid_x_for(tiles, njobs);
+    uint64_t blocks = (tiles + kGateTiles - 1) / kGateTiles;
+    uint64_t cap = 512 / (uint64_t)njobs;            // one block per CU
+    if (cap < 1) cap = 1;
+    return (uint32_t)(blocks < cap ? blocks : cap);
+}
 
 // ------------------------------------------------------------------------------------------ draw
-__global__ __launch_bounds__(kThreads) void k_draw(const DrawLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
+__global__ __launch_bounds__(kGateThreads) void k_draw(const DrawLaunch L) {
+    __shared__ uint32_t tt[kGateTabWords];
+    const GateTab T = load_gate_tab(tt, L.ttab);
     const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) draw_body(L, tile, blockIdx.y, threadIdx.x, T);
+    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) draw_body(L, tile, blockIdx.y, tx, T);
 }
 
 int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
@@ -56,8 +108,8 @@ int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
     if (L.n_elem == 0) return DASH_OK;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->seed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
-    hipLaunchKernelGGL(k_draw, grid, dim3(kThreads), 0, s, L);
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
+    hipLaunchKernelGGL(k_draw, grid, dim3(kGateThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
@@ -106,12 +158,12 @@ struct StagedSink {
 };
 
 template <class QD>
-__global__ __launch_bounds__(kThreads) void k_proj_garble(const GateLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
+__global__ __launch_bounds__(stage_rows<QD>::value ? kThreads : kGateThreads) void k_proj_garble(const GateLaunch L) {
     const uint64_t rows = (uint64_t)L.n_elem * L.jobs[blockIdx.y].p;
     const uint32_t tiles = (uint32_t)((rows + kThreads - 1) / kThreads);
     if constexpr (stage_rows<QD>::value) {
+        __shared__ uint32_t tt[kTabWords];
+        const LdsTab T = load_ttab(tt, L.ttab);
         constexpr int ndw = stage_rows<QD>::ndw, stride = ndw + 1, pieces = ndw / 4;
         __shared__ uint32_t stage[kThreads * stride];
         __shared__ uint32_t srow[kThreads];
@@ -134,9 +186,12 @@ __global__ __launch_bounds__(kThreads) void k_proj_garble(const GateLaunch L) {
             __syncthreads();
         }
     } else {
-        for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        __shared__ uint32_t tt[kGateTabWords];
+        const GateTab T = load_gate_tab(tt, L.ttab);
+        const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+        for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) {
             DirectSink sink;
-            garble_body<QD>(L, tile, blockIdx.y, threadIdx.x, T, sink);
+            garble_body<QD>(L, tile, blockIdx.y, tx, T, sink);
         }
     }
 }
@@ -145,6 +200,9 @@ typedef void (*GateKernel)(const GateLaunch);
 #define DASH_GARBLE_K(MOD, LAM) k_proj_garble<CMod<MOD, LAM>>,
 static const GateKernel kGarbleKernels[] = {k_proj_garble<ModInfo>, DASH_HOT_MODS(DASH_GARBLE_K)};
 #undef DASH_GARBLE_K
+#define DASH_GARBLE_S(MOD, LAM) stage_rows<CMod<MOD, LAM>>::value,
+static const bool kGarbleStaged[] = {false, DASH_HOT_MODS(DASH_GARBLE_S)};
+#undef DASH_GARBLE_S
 
 // every job of a gate launch must have the same output modulus; returns it (0 if they differ)
 static uint32_t common_q(const GateLaunch& L, int njobs) {
@@ -167,7 +225,6 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     uint64_t rows = (uint64_t)L.n_elem * pmax;
     uint64_t blocks = (rows + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffull) return DASH_ESIZE;
-    dim3 grid(grid_x_for(blocks, njobs), njobs);
     double units = 0, bytes = 0;
     for (int j = 0; j < njobs; j++) {
         const GateJob& J = L.jobs[j];
@@ -178,19 +235,23 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     const uint32_t q = common_q(L, njobs);
     if (!q) return DASH_EINVAL;
     if (rows >= (1ull << 32)) return DASH_ESIZE;      // staged rows carry a 32-bit row index
+    const int ki = hot_mod_index(c->mods[q]);
+    const bool staged = kGarbleStaged[ki];
+    dim3 grid(staged ? grid_x_for(blocks, njobs) : gate_grid_x_for(blocks, njobs), njobs);
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
-    hipLaunchKernelGGL(kGarbleKernels[hot_mod_index(c->mods[q])], grid, dim3(kThreads), 0, s, L);
+    hipLaunchKernelGGL(kGarbleKernels[ki], grid, dim3(staged ? kThreads : kGateThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
 
 // ------------------------------------------------------------------------------------------ eval
 template <class QD>
-__global__ __launch_bounds__(kThreads) void k_proj_eval(const GateLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
+__global__ __launch_bounds__(kGateThreads) void k_proj_eval(const GateLaunch L) {
+    __shared__ uint32_t tt[kGateTabWords];
+    const GateTab T = load_gate_tab(tt, L.ttab);
     const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) eval_body<QD>(L, tile, blockIdx.y, threadIdx.x, T);
+    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) eval_body<QD>(L, tile, blockIdx.y, tx, T);
 }
 #define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>>,
 static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo>, DASH_HOT_MODS(DASH_EVAL_K)};
@@ -206,13 +267,13 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
         if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
         if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
     }
-    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
     double bytes = 0;
     for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
     const uint32_t q = common_q(L, njobs);
     if (!q) return DASH_EINVAL;
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
-    hipLaunchKernelGGL(kEvalKernels[hot_mod_index(c->mods[q])], grid, dim3(kThreads), 0, s, L);
+    hipLaunchKernelGGL(kEvalKernels[hot_mod_index(c->mods[q])], grid, dim3(kGateThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

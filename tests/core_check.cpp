@@ -12,7 +12,9 @@ namespace {
 uint32_t TT[1024];
 bool ready = false;
 uint8_t SB[256];
-struct HostTab { uint32_t operator()(int r, uint32_t x) const { return TT[r * 256 + x]; } };
+struct HostTab {
+    template <int R, int B> uint32_t at(uint32_t w) const { return TT[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
+};
 void init() { if (!ready) { make_sbox(SB); make_ttab(SB, TT); ready = true; } }
 uint32_t pack_dw(const uint8_t* lab, uint32_t lam, int i) {
     uint32_t w = 0;

@@ -20,7 +20,9 @@ using namespace dash;
 using namespace dash::hostconst;
 
 static uint32_t TT[1024];
-struct HostTab { uint32_t operator()(int r, uint32_t x) const { return TT[r * 256 + x]; } };
+struct HostTab {
+    template <int R, int B> uint32_t at(uint32_t w) const { return TT[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
+};
 
 // chunk-major LabelTensor from compact labels, exactly nchunk*n*16 bytes
 static std::vector<uint8_t> to_chunked(const uint8_t* compact, uint32_t n, const ModInfo& M) {
