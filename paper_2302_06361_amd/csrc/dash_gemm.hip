@@ -20,6 +20,8 @@
 // lane holds, for its pair, the four digits of one output dword for 64 output features.
 #include <string.h>
 
+#include <type_traits>
+
 #include "dash_internal.h"
 
 namespace dash {
@@ -45,29 +47,45 @@ struct GemmArgs {
     int64_t kpad, mpad;
     const int32_t* bias;
     uint32_t small_acc;         // 1 if (p-1)^2 K < 2^24 for every prime: one-step reduction
+    int sty;                    // block rows per super-tile: 4, 2 or 1 (kStBlocks / sty block columns)
+    int gy4;                    // super-tile rows: ceil(ceil(M / kBM) / sty)
+    int st_total;               // super-tiles of all primes
+    int st_first[DASH_MAX_PRIMES + 1];   // first super-tile of every prime
     GemmPrime pr[DASH_MAX_PRIMES];
 };
 
-// bytes (a.bS, b.bS, c.bS, d.bS) for S = 0..3: transposes a 4x4 byte block held in 4 dwords
-__device__ __forceinline__ void transpose4x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d, uint32_t out[4]) {
-    // v_perm_b32(hi, lo, sel): byte k of the result = byte sel.k of the 8 bytes {hi:lo} (lo = bytes 0..3)
-    uint32_t ab02 = __builtin_amdgcn_perm(b, a, 0x06020400u);   // a0 b0 a2 b2
-    uint32_t ab13 = __builtin_amdgcn_perm(b, a, 0x07030501u);   // a1 b1 a3 b3
-    uint32_t cd02 = __builtin_amdgcn_perm(d, c, 0x06020400u);
-    uint32_t cd13 = __builtin_amdgcn_perm(d, c, 0x07030501u);
-    out[0] = __builtin_amdgcn_perm(cd02, ab02, 0x05040100u);    // a0 b0 c0 d0
-    out[2] = __builtin_amdgcn_perm(cd02, ab02, 0x07060302u);    // a2 b2 c2 d2
-    out[1] = __builtin_amdgcn_perm(cd13, ab13, 0x05040100u);
-    out[3] = __builtin_amdgcn_perm(cd13, ab13, 0x07060302u);
-}
+// Block -> tile.  Work-groups go to the 8 XCDs round-robin by their linear id, and each XCD has its own
+// L2.  The 32 blocks that are resident on one XCD at a time are therefore ids xcd + 8 * (32 s .. 32 s + 31):
+// they are given one "super-tile" of 4 (M) x 8 (groups) block tiles, so that together they read 4 row
+// panels of the weights and 8 column panels of the labels (12 panel streams for 32 blocks) instead of
+// 1 + 32 with a row-major order.  Super-tiles are numbered over all primes; tiles past the edge of a
+// prime's grid exit.
+// (Layers with fewer than 4 row blocks use 2 x 16 or 1 x 32.)
+constexpr int kStBlocks = 32, kXcds = 8;
 
 __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
-    const GemmPrime& P = A.pr[blockIdx.z];
+    const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+    const int st = (seq / kStBlocks) * kXcds + xcd, within = seq % kStBlocks;
+    if (st >= A.st_total) return;
+    int pi = 0;
+    while (st >= A.st_first[pi + 1]) pi++;
+    const GemmPrime& P = A.pr[pi];
     const int ngroups = (int)P.nchunk * A.batch;
     const int gblocks = (ngroups + kBG - 1) / kBG;
-    if ((int)blockIdx.x >= gblocks) return;
+    const int stl = st - A.st_first[pi];                    // super-tile inside the prime: row-major over (x super, y super)
+    const int sty = A.sty, stx = kStBlocks / sty;
+    const int by = (stl % A.gy4) * sty + within % sty, bx = (stl / A.gy4) * stx + within / sty;
+    const int M = A.M, K = A.K;
+    if (bx >= gblocks || by * kBM >= M) return;
+    // everything the loops need, in registers: fields read through the argument block inside a loop are
+    // fetched again (a scalar load and a wait) every time they are used
+    const int8_t* const wbase = P.w;
+    const int64_t kpad = A.kpad, mpad = A.mpad;
+    const uint32_t prime = P.p, mmagic = P.mmagic, pow12 = P.pow12;
+    const bool small_acc = A.small_acc != 0;
+    const int32_t* const bias = A.bias;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-    const int row0 = blockIdx.y * kBM, grp0 = blockIdx.x * kBG;
+    const int row0 = by * kBM, grp0 = bx * kBG;
 
     __shared__ __attribute__((aligned(16))) uint8_t As[2][kBM * kRow];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][4 * kBG * 4 * kRow];
@@ -78,37 +96,45 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     const int bG = tid >> 4, bkq = tid & 15;
     const int gglob = grp0 + bG;
     const bool gvalid = gglob < ngroups;
+    // a group past the end reads group 0 (its results are never stored): loads need no predicate
     const int gch = gvalid ? gglob / A.batch : 0, gb = gvalid ? gglob - gch * A.batch : 0;
-    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + ((int64_t)gb * A.K) * 16;
+    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + ((int64_t)gb * K) * 16;
 
-    uint4 ra[4], rb[4];
-    auto load_stage = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int id = tid + 256 * i, row = row0 + (id >> 2), part = id & 3;
-            ra[i] = row < A.mpad ? *(const uint4*)(P.w + (int64_t)row * A.kpad + k0 + part * 16) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int kk = 0; kk < 4; kk++) {
-            const int k = k0 + 4 * bkq + kk;
-            rb[kk] = (gvalid && k < A.K) ? *(const uint4*)(xg + (int64_t)k * 16) : make_uint4(0, 0, 0, 0);
-        }
+    // Global data is fetched two stages ahead into one of two register sets (a stage of MFMAs is shorter
+    // than a miss in the L2), transposed and written to LDS one stage ahead.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // (a plain vector: HIP's uint4 is a struct and was left in scratch memory)
+    struct Regs { u32x4 a0, a1, a2, a3, b0, b1, b2, b3; };
+    Regs Rx, Ry;
+    const int arow = tid >> 2, apart = tid & 3;         // A piece i of this thread: row arow + 64 i, 16-byte part apart
+    auto a_src = [&](int i, int k0) __attribute__((always_inline)) {
+        const int row = row0 + arow + 64 * i;
+        return (const u32x4*)(wbase + (int64_t)(row < mpad ? row : mpad - 1) * kpad + k0 + apart * 16);   // rows past M are never stored
     };
-    auto store_stage = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int id = tid + 256 * i;
-            *(uint4*)(As[buf] + (id >> 2) * kRow + (id & 3) * 16) = ra[i];
-        }
-        const uint32_t r[4][4] = {{rb[0].x, rb[0].y, rb[0].z, rb[0].w}, {rb[1].x, rb[1].y, rb[1].z, rb[1].w},
-                                  {rb[2].x, rb[2].y, rb[2].z, rb[2].w}, {rb[3].x, rb[3].y, rb[3].z, rb[3].w}};
-#pragma unroll
-        for (int g = 0; g < 4; g++) {
-            uint32_t t[4];
-            transpose4x4(r[0][g], r[1][g], r[2][g], r[3][g], t);     // t[s] = digit 4g+s at k = 4kq..4kq+3
-#pragma unroll
-            for (int s = 0; s < 4; s++) *(uint32_t*)(Bs[buf] + (((s * kBG + bG) * 4 + g) * kRow) + 4 * bkq) = t[s];
-        }
+    auto b_src = [&](int kk, int k0) __attribute__((always_inline)) {
+        const int k = k0 + 4 * bkq + kk;
+        return (const u32x4*)(xg + (int64_t)(k < K ? k : K - 1) * 16);                                   // the weights are zero for k >= K
+    };
+    auto load_stage = [&](int k0, Regs& R) __attribute__((always_inline)) {
+        R.a0 = *a_src(0, k0); R.a1 = *a_src(1, k0); R.a2 = *a_src(2, k0); R.a3 = *a_src(3, k0);
+        R.b0 = *b_src(0, k0); R.b1 = *b_src(1, k0); R.b2 = *b_src(2, k0); R.b3 = *b_src(3, k0);
+    };
+    auto store_stage = [&](int buf, const Regs& R) __attribute__((always_inline)) {
+        uint8_t* ad = As[buf] + arow * kRow + apart * 16;
+        *(u32x4*)(ad) = R.a0; *(u32x4*)(ad + 64 * kRow) = R.a1; *(u32x4*)(ad + 128 * kRow) = R.a2; *(u32x4*)(ad + 192 * kRow) = R.a3;
+        auto put = [&](int g, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) __attribute__((always_inline)) {      // dword g of rows k..k+3
+            // v_perm_b32(hi, lo, sel): byte k of the result = byte sel.k of the 8 bytes {hi:lo} (lo = bytes 0..3)
+            const uint32_t ab02 = __builtin_amdgcn_perm(w1, w0, 0x06020400u), ab13 = __builtin_amdgcn_perm(w1, w0, 0x07030501u);
+            const uint32_t cd02 = __builtin_amdgcn_perm(w3, w2, 0x06020400u), cd13 = __builtin_amdgcn_perm(w3, w2, 0x07030501u);
+            uint8_t* dst = Bs[buf] + ((bG * 4 + g) * kRow) + 4 * bkq;                    // + s * kBG * 4 * kRow: digit 4g+s
+            *(uint32_t*)(dst + 0 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd02, ab02, 0x05040100u);
+            *(uint32_t*)(dst + 1 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd13, ab13, 0x05040100u);
+            *(uint32_t*)(dst + 2 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd02, ab02, 0x07060302u);
+            *(uint32_t*)(dst + 3 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd13, ab13, 0x07060302u);
+        };
+        put(0, R.b0.x, R.b1.x, R.b2.x, R.b3.x);
+        put(1, R.b0.y, R.b1.y, R.b2.y, R.b3.y);
+        put(2, R.b0.z, R.b1.z, R.b2.z, R.b3.z);
+        put(3, R.b0.w, R.b1.w, R.b2.w, R.b3.w);
     };
 
     v16i acc[4][4];
@@ -117,64 +143,100 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
 #pragma unroll
         for (int s = 0; s < 4; s++) acc[i][s] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-    const int nk = (int)(A.kpad / kKT);
-    load_stage(0);
-    store_stage(0);
+    const int nk = (int)(kpad / kKT);
+    load_stage(0, Rx);
+    store_stage(0, Rx);
     __syncthreads();
+    if (nk > 1) load_stage(kKT, Ry);
     const int n = lane & 31, kh = lane >> 5;
     const int fa = (wm * 128 + n) * kRow + kh * 16;                              // + rb*32*kRow + ks*32
     const int fb = (((wn * 8 + (n >> 2)) * 4) + (n & 3)) * kRow + kh * 16;       // + s*kBG*4*kRow + ks*32
-    for (int kt = 0; kt < nk; kt++) {
+    // Software pipeline inside the wave (one wave per SIMD: nothing else hides latency).  Per stage:
+    //   global loads of the stage after next
+    //   16 MFMAs of the first K half   | LDS reads of the fragments of the second half
+    //   16 MFMAs of the second K half  | the next stage's data: byte transposes and LDS writes
+    // then the barrier and the fragment reads of the first half of the next stage.
+    // sched_group_barrier(mask, n, id): 0x8 MFMA, 0x100 LDS read, 0x200 LDS write, 0x2 vector ALU.
+    v4i a0[4], b0[4], a1[4], b1[4];
+    auto read_frags = [&](int buf, int ks, v4i (&a)[4], v4i (&b)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) a[i] = *(const v4i*)(As[buf] + fa + i * 32 * kRow + ks * 32);
+#pragma unroll
+        for (int q = 0; q < 4; q++) b[q] = *(const v4i*)(Bs[buf] + fb + q * kBG * 4 * kRow + ks * 32);
+    };
+    auto mfma16 = [&](const v4i (&a)[4], const v4i (&b)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int q = 0; q < 4; q++) acc[i][q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[q], acc[i][q], 0, 0, 0);
+    };
+    // one stage that has a successor: Rl receives stage kt + 2, Rs holds stage kt + 1
+    auto stage = [&](int kt, Regs& Rl, const Regs& Rs) __attribute__((always_inline)) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) load_stage((kt + 1) * kKT);
+        load_stage((kt + 2 < nk ? kt + 2 : nk - 1) * kKT, Rl);      // past the end: the last stage again, unused (no branch, so the
+                                                                    // wait before the LDS writes can leave these loads in flight)
+        read_frags(cur, 1, a1, b1);
+        mfma16(a0, b0);
 #pragma unroll
-        for (int ks = 0; ks < 2; ks++) {
-            v4i a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) a[i] = *(const v4i*)(As[cur] + fa + i * 32 * kRow + ks * 32);
-#pragma unroll
-            for (int s = 0; s < 4; s++) b[s] = *(const v4i*)(Bs[cur] + fb + s * kBG * 4 * kRow + ks * 32);
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-#pragma unroll
-                for (int s = 0; s < 4; s++) acc[i][s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[s], acc[i][s], 0, 0, 0);
+        for (int t = 0; t < 8; t++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        if (kt + 1 < nk) store_stage(cur ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        store_stage(cur ^ 1, Rs);
+        mfma16(a1, b1);
+#pragma unroll
+        for (int t = 0; t < 16; t++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        read_frags(cur ^ 1, 0, a0, b0);
+    };
+    read_frags(0, 0, a0, b0);
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) { stage(kt, Rx, Ry); stage(kt + 1, Ry, Rx); }
+    if (kt + 1 < nk) { stage(kt, Rx, Ry); kt++; }
+    {   // last stage: nothing left to fetch
+        read_frags(kt & 1, 1, a1, b1);
+        mfma16(a0, b0);
+        mfma16(a1, b1);
     }
 
     // ---- epilogue: reduce mod p, pack the four digits of a dword, store ----
     const int G = grp0 + wn * 8 + (n >> 2), g = n & 3;
     if (G >= ngroups) return;
     const int och = G / A.batch, ob = G - och * A.batch;
-    uint8_t* og = P.out.p + (int64_t)och * P.out.cs + ((int64_t)ob * A.M) * 16 + 4 * g;
+    uint8_t* og = P.out.p + (int64_t)och * P.out.cs + ((int64_t)ob * M) * 16 + 4 * g;
     uint32_t one4 = 0;
-    if (A.bias) one4 = *(const uint32_t*)(P.one + och * 16 + 4 * g);
-    auto red = [&](uint32_t v) -> uint32_t {
-        if (!A.small_acc) {                                   // v = hi * 4096 + lo
-            uint32_t hi = v >> 12;
-            hi -= mul24(mulhi(hi, P.mmagic), P.p);
-            v = mul24(hi, P.pow12) + (v & 4095u);
-        }
-        return v - mul24(mulhi(v, P.mmagic), P.p);
-    };
+    if (bias) one4 = *(const uint32_t*)(P.one + och * 16 + 4 * g);
+    auto red1 = [&](uint32_t v) -> uint32_t { return v - mul24(mulhi(v, mmagic), prime); };      // v < 2^24
+    auto emit = [&](auto small) {
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int j = row0 + wm * 128 + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-            if (j >= A.M) continue;
-            uint32_t d[4];
+            for (int r = 0; r < 16; r++) {
+                const int j = row0 + wm * 128 + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                if (j >= M) continue;
+                uint32_t d[4];
 #pragma unroll
-            for (int s = 0; s < 4; s++) d[s] = red((uint32_t)acc[i][s][r]);
-            if (A.bias) {
-                int32_t bj = A.bias[j] % (int32_t)P.p;
-                uint32_t bm = (uint32_t)(bj < 0 ? bj + (int32_t)P.p : bj);
+                for (int s = 0; s < 4; s++) {
+                    uint32_t v = (uint32_t)acc[i][s][r];
+                    if (!decltype(small)::value) v = mul24(red1(v >> 12), pow12) + (v & 4095u);    // v = hi * 4096 + lo
+                    d[s] = red1(v);
+                }
+                if (bias) {
+                    int32_t bj = bias[j] % (int32_t)prime;
+                    uint32_t bm = (uint32_t)(bj < 0 ? bj + (int32_t)prime : bj);
 #pragma unroll
-                for (int s = 0; s < 4; s++) d[s] = red(d[s] + mul24(bm, (one4 >> (8 * s)) & 0xffu));
+                    for (int s = 0; s < 4; s++) d[s] = red1(d[s] + mul24(bm, (one4 >> (8 * s)) & 0xffu));
+                }
+                *(uint32_t*)(og + (int64_t)j * 16) = d[0] | (d[1] << 8) | (d[2] << 16) | (d[3] << 24);
             }
-            *(uint32_t*)(og + (int64_t)j * 16) = d[0] | (d[1] << 8) | (d[2] << 16) | (d[3] << 24);
-        }
+    };
+    if (small_acc) emit(std::true_type{}); else emit(std::false_type{});
 }
 
 // true if the MFMA path should take this dense layer (large enough to fill tiles)
@@ -205,9 +267,21 @@ int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         macs += (double)batch * M * K * Mi.lam;
         bytes += (double)batch * (M + K) * Mi.lam + (double)M * K;
     }
-    const int64_t gblocks = ((int64_t)max_nchunk * batch + kBG - 1) / kBG;
-    if (gblocks > 0x7fffffff) return DASH_ESIZE;
-    dim3 grid((uint32_t)gblocks, (uint32_t)((M + kBM - 1) / kBM), c->k);
+    (void)max_nchunk;
+    const int gy = (M + kBM - 1) / kBM;
+    A.sty = gy >= 4 ? 4 : gy >= 2 ? 2 : 1;
+    const int kStX = kStBlocks / A.sty;
+    A.gy4 = (gy + A.sty - 1) / A.sty;
+    int64_t st_total = 0;
+    for (int i = 0; i < c->k; i++) {
+        A.st_first[i] = (int)st_total;
+        const int64_t gb = ((int64_t)A.pr[i].nchunk * batch + kBG - 1) / kBG;
+        st_total += (gb + kStX - 1) / kStX * A.gy4;
+        if (st_total > (1 << 24)) return DASH_ESIZE;
+    }
+    A.st_first[c->k] = (int)st_total;
+    A.st_total = (int)st_total;
+    dim3 grid((uint32_t)((st_total + kXcds - 1) / kXcds * kXcds * kStBlocks));
     ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
     hipLaunchKernelGGL(k_dense_mfma, grid, dim3(256), 0, s, A);
     DASH_HIP(hipGetLastError());
