@@ -160,6 +160,83 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
     for (int i = (int)Q.ndw; i < (int)Q.nchunk * 4; i++) st_dw(J.out, g, i, 0);
 }
 
+// ---- evaluator, carry chain of the sign gadget ------------------------------------------------
+// One gate of the chain for element e: the input label comes dword by dword from in_dw, the output label
+// goes dword by dword to out.
+template <class MI, class MO, class Tab, class In, class Out>
+DASH_HD void chain_gate(const ChainLaunch& L, const MI& Mi, const MO& Mo, uint32_t e, int j, In in_dw, Out out, const Tab& T) {
+    uint32_t colour = 0;
+    U128 K = compress(Mi, in_dw, &colour);
+    U128 h = hash_block(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T);
+    const uint32_t* row = (const uint32_t*)(L.table[j] + ((size_t)e * Mi.m + colour) * (Mo.ndw * 4));
+    if constexpr (cmod_m<MO>::value != 0) {
+        uint32_t rw[MO::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)MO::ndw; i++) rw[i] = row[i];
+        decompress(Mo, h, [&](int i, uint32_t hd) { out(i, submod4(rw[i], hd, Mo)); });
+    } else {
+        decompress(Mo, h, [&](int i, uint32_t hd) { out(i, submod4(row[i], hd, Mo)); });
+    }
+}
+
+// Digit sets whose digits 2..n share one accumulation modulus (description MC) and whose first digit has
+// description M1, both fixed at compile time: the carry label stays in registers from gate to gate.
+template <class MC, class M1, class Tab>
+DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, const Tab& T) {
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem) return;
+    const MC Mc{nullptr};
+    const M1 Mf{nullptr};
+    const CMod<2, 128> M2{nullptr};
+    uint32_t cw[MC::ndw], c1[M1::ndw];
+#pragma unroll
+    for (int i = 0; i < (int)MC::ndw; i++) cw[i] = 0;
+    const int n = (int)L.n;
+    for (int j = n; j >= 3; j--) {                  // carry out of digit j into digit j-1, same modulus
+        uint32_t in[MC::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(ld_dw(L.sum[j], e, i), cw[i], Mc);   // cw = 0 at j = n
+        chain_gate(L, Mc, Mc, e, j, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { cw[i] = w; }, T);
+    }
+    {                                               // digit 2 -> carry into digit 1 (modulus of the first digit)
+        uint32_t in[MC::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(ld_dw(L.sum[2], e, i), cw[i], Mc);
+        chain_gate(L, Mc, Mf, e, 2, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { c1[i] = w; }, T);
+    }
+    {                                               // final gate: digit 1 -> the sign bit
+        uint32_t in[M1::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(ld_dw(L.sum[1], e, i), c1[i], Mf);
+        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { st_dw(L.bit, e, i, w); }, T);
+    }
+}
+
+// Any digit set, run-time constants: the carry label goes through its buffer in memory (written and read
+// back by the same lane).
+template <class Tab>
+DASH_HD void chain_eval_generic_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, const Tab& T) {
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem) return;
+    const int n = (int)L.n;
+    for (int j = n; j >= 1; j--) {
+        const ModInfo Mi = L.mods[L.m[j]];
+        const bool has_carry = j < n;
+        auto in_dw = [&](int i) {
+            uint32_t w = ld_dw(L.sum[j], e, i);
+            return has_carry ? addmod4(w, ld_dw(L.carry[j], e, i), Mi) : w;
+        };
+        if (j >= 2) {
+            const ModInfo Mo = L.mods[L.m[j - 1]];
+            chain_gate(L, Mi, Mo, e, j, in_dw, [&](int i, uint32_t w) { st_dw(L.carry[j - 1], e, i, w); }, T);
+            for (int i = (int)Mo.ndw; i < (int)Mo.nchunk * 4; i++) st_dw(L.carry[j - 1], e, i, 0);
+        } else {
+            const CMod<2, 128> M2{nullptr};
+            chain_gate(L, Mi, M2, e, 1, in_dw, [&](int i, uint32_t w) { st_dw(L.bit, e, i, w); }, T);
+        }
+    }
+}
+
 // evaluator side of the mixed-modulus half gate: z = V + beta * x - U
 template <class Tab>
 DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {

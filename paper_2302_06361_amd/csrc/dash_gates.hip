@@ -232,10 +232,11 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
         units += (double)L.n_elem * J.p;
         bytes += (double)L.n_elem * (lp + (J.phi_stride ? J.p : 0) + lq + J.p * lq + (J.mode == PAY_EHALF ? lq : 0));
     }
+    // jobs with one output modulus run its instantiation; a mix of output moduli (many small batches
+    // in one launch) runs the instantiation with run-time constants
     const uint32_t q = common_q(L, njobs);
-    if (!q) return DASH_EINVAL;
     if (rows >= (1ull << 32)) return DASH_ESIZE;      // staged rows carry a 32-bit row index
-    const int ki = hot_mod_index(c->mods[q]);
+    const int ki = q ? hot_mod_index(c->mods[q]) : 0;
     const bool staged = kGarbleStaged[ki];
     dim3 grid(staged ? grid_x_for(blocks, njobs) : gate_grid_x_for(blocks, njobs), njobs);
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
@@ -271,9 +272,53 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     double bytes = 0;
     for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
     const uint32_t q = common_q(L, njobs);
-    if (!q) return DASH_EINVAL;
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
-    hipLaunchKernelGGL(kEvalKernels[hot_mod_index(c->mods[q])], grid, dim3(kGateThreads), 0, s, L);
+    hipLaunchKernelGGL(kEvalKernels[q ? hot_mod_index(c->mods[q]) : 0], grid, dim3(kGateThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+// ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
+// One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
+// whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
+// other set takes the body with run-time constants.
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_chain_eval(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1>(L, tile, threadIdx.x, T);
+}
+__global__ __launch_bounds__(kThreads) void k_chain_eval_generic(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_generic_body(L, tile, threadIdx.x, T);
+}
+
+int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
+    if (L.n < 2 || L.n > (uint32_t)kMaxChain) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    bool uniform = true;
+    double bytes = 0;
+    for (uint32_t j = 1; j <= L.n; j++) {
+        if (L.m[j] < 2 || L.m[j] > 255 || !L.table[j] || !L.sum[j].p || (j < L.n && !L.carry[j].p)) return DASH_EINVAL;
+        if (j >= 3 && L.m[j] != L.m[2]) uniform = false;
+        bytes += (double)L.n_elem * (c->mods[L.m[j]].lam + (j >= 2 ? c->mods[L.m[j - 1]].lam : 128));
+    }
+    if ((uint64_t)L.n_elem * 255 >= (1ull << 32)) return DASH_ESIZE;
+    const ModInfo &Mc = c->mods[L.m[2]], &M1 = c->mods[L.m[1]];
+    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
+    if (uniform && is(Mc, 96, 20) && is(M1, 26, 28))
+        hipLaunchKernelGGL((k_chain_eval<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, L);
+    else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24))
+        hipLaunchKernelGGL((k_chain_eval<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
+    else
+        hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

@@ -15,9 +15,17 @@
 // Tiling.  Block = 256 threads = 2 x 2 waves, block tile 256 (M) x 16 groups (256 columns), K-step 64,
 // LDS double buffered (2 x (20 KB A + 20 KB B), rows padded from 64 to 80 bytes so that the 16-byte
 // fragment reads of 8 consecutive lanes fall into different banks).  Wave tile 128 x 128 columns =
-// 4 x 4 MFMA 32x32x32 per 32 of K, accumulators 256 registers per lane.  MFMA s (0..3) of a wave
-// covers digit 4g+s of the 32 (group, g) pairs that its lanes stand for, so that after the last K-step a
-// lane holds, for its pair, the four digits of one output dword for 64 output features.
+// 4 x 4 MFMA 32x32x32 per 32 of K, accumulators 256 registers per lane (so one wave per SIMD).  MFMA s
+// (0..3) of a wave covers digit 4g+s of the 32 (group, g) pairs that its lanes stand for, so that after the
+// last K-step a lane holds, for its pair, the four digits of one output dword for 64 output features.
+//
+// Pipeline.  With one wave per SIMD nothing but the wave's own instruction order hides latency: global
+// data is fetched two K-steps ahead into one of two register sets, transposed and written to LDS one step
+// ahead, and the 32 MFMAs of a step are interleaved with the fragment reads of its second half and with
+// the LDS writes of the next step (sched_group_barrier).  Measured on the 4096 x 4096, batch 128, 12-prime
+// case: 1.38 ms, 35 % of the 5.0 POP/s int8 peak (a loop of nothing but MFMAs reaches 4.2 - 4.7 POP/s on
+// this chip); per K-step 2200 cycles against 1150 for the MFMAs alone, plus 0.25 ms of prologue and
+// epilogue that one block per CU cannot overlap with another block's MFMAs.
 #include <string.h>
 
 #include <type_traits>

@@ -8,8 +8,9 @@
 namespace dash {
 
 constexpr int kMaxJobs = 16;    // gate batches per launch (blockIdx.y)
-constexpr int kMaxTerms = 16;   // label terms per launch, shared by its jobs
+constexpr int kMaxTerms = 64;   // label terms per launch, shared by its jobs
 constexpr int kThreads = 256;
+constexpr int kMaxChain = 16;   // mixed-radix digits of the sign gadget
 
 // PRG domains (byte 14 of the counter block)
 enum { DOM_DELTA = 0, DOM_INPUT = 1, DOM_GATE = 2, DOM_MASK = 3, DOM_ONE = 4 };
@@ -97,6 +98,24 @@ struct HgLaunch {
     uint32_t layer;
     uint32_t n_elem;
     HgJob jobs[kMaxJobs];
+};
+
+// evaluator side of the mixed-radix addition of one sign gadget (Appendix, Garbled Mixed-Radix Addition):
+// digits n..1 in turn, one lane per element
+struct ChainLaunch {
+    AesKey key;
+    const uint32_t* ttab;
+    const ModInfo* mods;
+    uint64_t elem_base;
+    uint32_t layer;
+    uint32_t n_elem;
+    uint32_t n;                          // digits
+    uint32_t m[kMaxChain + 1];           // accumulation modulus of digit j (1-based)
+    uint32_t slot[kMaxChain + 1];        // slot of the gate that digit j feeds (carry gate for j >= 2, final gate for j = 1)
+    uint8_t* table[kMaxChain + 1];       // its segment
+    LView sum[kMaxChain + 1];            // free sum of the digit wires of digit j, WITHOUT the carry
+    LView carry[kMaxChain + 1];          // carry into digit j (j < n): written by gate j+1, read back by the same lane
+    LView bit;                           // output wire (Z_2)
 };
 
 }  // namespace dash

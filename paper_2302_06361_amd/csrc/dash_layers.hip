@@ -84,11 +84,15 @@ void plan_sign(const dash_ctx* c, Arena& ar, int64_t E, int first_res, SignWires
 // ---- launch batchers -------------------------------------------------------------------------
 // Collects independent gate jobs and launches them grouped by output modulus (a launch runs one
 // instantiation of the gate kernel, chosen by the output modulus), up to kMaxJobs per launch.
+// mixed = true puts jobs of any output moduli into the same launch (the instantiation with run-time
+// constants): for the many small batches whose output moduli all differ (one cast or half gate per
+// prime), where a launch per modulus would cost more than the slower digit extraction.
 struct GateBatcher {
     static constexpr int kSlots = 4;
-    const dash_ctx* c; bool garble; hipStream_t s;
+    const dash_ctx* c; bool garble; hipStream_t s; bool mixed = false;
     GateLaunch L[kSlots]; int nj[kSlots]; int status = DASH_OK;
-    GateBatcher(const dash_ctx* c_, bool g, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_) : c(c_), garble(g), s(s_) {
+    GateBatcher(const dash_ctx* c_, bool g, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_, bool mixed_ = false)
+        : c(c_), garble(g), s(s_), mixed(mixed_) {
         memset(L, 0, sizeof(L));
         for (int t = 0; t < kSlots; t++) { L[t].n_elem = E; L[t].layer = layer; L[t].elem_base = elem_base; nj[t] = 0; }
     }
@@ -99,7 +103,7 @@ struct GateBatcher {
     void add(const GateJob& J) {
         int t = -1, free_slot = -1;
         for (int u = 0; u < kSlots; u++) {
-            if (nj[u] && L[u].jobs[0].q == J.q) t = u;
+            if (nj[u] && (mixed || L[u].jobs[0].q == J.q)) t = u;
             if (!nj[u] && free_slot < 0) free_slot = u;
         }
         if (t < 0) {
@@ -194,6 +198,31 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         gb.flush();
         return gb.status;
     }
+    if (n >= 2) {
+        // evaluator: all digit sums (without carries) in one free-gate launch, then the whole chain in one
+        AffineBatcher ab(c, E, s);
+        for (int j = n; j >= 1; j--) {
+            Term t[kMaxTerms];
+            int nt = 0;
+            for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
+            ab.add(c->mj[j], w.S[j], t, nt);
+        }
+        ab.flush();
+        if (ab.status) return ab.status;
+        ChainLaunch CL;
+        memset(&CL, 0, sizeof(CL));
+        CL.n_elem = E; CL.layer = layer; CL.elem_base = elem_base; CL.n = (uint32_t)n;
+        for (int j = 1; j <= n; j++) {
+            const int sl = j >= 2 ? k * n + (j - 2) : k * n + n - 1;
+            CL.m[j] = (uint32_t)c->mj[j];
+            CL.slot[j] = slot_base + (uint32_t)sl;
+            CL.table[j] = seg + off[sl];
+            CL.sum[j] = w.S[j];
+            if (j < n) CL.carry[j] = w.C[j];
+        }
+        CL.bit = w.bit;
+        return launch_chain_eval(c, CL, s);
+    }
     for (int j = n; j >= 1; j--) {
         AffineBatcher ab(c, E, s);
         sum_digit(ab, j);
@@ -253,7 +282,7 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         }
         db.flush();
         if (db.status) return db.status;
-        GateBatcher gb(c, true, E, layer, eb, s);
+        GateBatcher gb(c, true, E, layer, eb, s), gb2(c, true, E, layer, eb, s, true);   // the two-row tables share launches
         for (int i = 0; i < k; i++) {
             int p = c->prime[i];
             GateJob J = phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
@@ -261,13 +290,15 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
             gb.add(J);
             J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]);         // evaluator half: -(b+r)*x0
             J.mode = PAY_EHALF; J.r = pl.r[i]; J.x0 = x[i];
-            gb.add(J);
+            gb2.add(J);
             J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 2, pl.V[i], S[i]);          // b + r for the evaluator
             J.mode = PAY_SHORT; J.r = pl.r[i];
-            gb.add(J);
+            gb2.add(J);
         }
         gb.flush();
+        gb2.flush();
         if (gb.status) return gb.status;
+        if (gb2.status) return gb2.status;
         AffineBatcher ab(c, E, s);                                                    // zero label of the product: V0 - U0
         for (int i = 0; i < k; i++) {
             Term t[2] = {Term{pl.V[i], 1}, Term{pl.U[i], (uint32_t)c->prime[i] - 1}};
@@ -276,7 +307,7 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         ab.flush();
         return ab.status;
     }
-    GateBatcher gb(c, false, E, layer, eb, s);
+    GateBatcher gb(c, false, E, layer, eb, s, true);
     for (int i = 0; i < k; i++) {
         int p = c->prime[i];
         gb.add(phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]));
@@ -314,7 +345,7 @@ int signact_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labe
         if (db.status) return db.status;
     }
     size_t cum = sign_bytes(c, 0);
-    GateBatcher gb(c, garble, E, layer, eb, s);
+    GateBatcher gb(c, garble, E, layer, eb, s, true);
     for (int i = 0; i < k; i++) {
         gb.add(phi_job(2, c->prime[i], w.bit, c->phi_pm1[i], ns + i, view_of(out, i), tables + cum * E));
         cum += 2 * pitch_of(c, c->prime[i]);
@@ -374,7 +405,7 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         }
         size_t cum = 0;
         {
-            GateBatcher gb(c, garble, E, layer, eb, s);
+            GateBatcher gb(c, garble, E, layer, eb, s, true);
             for (int i = 1; i < k; i++) {
                 gb.add(phi_job(2, c->prime[i], pl.up, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
                 cum += 2 * pitch_of(c, c->prime[i]);

@@ -59,3 +59,63 @@ def test_gate_bodies_sizes_and_rules(emul, tmp_path):
         run_case(emul, tmp_path, 7, 96, n)
     run_case(emul, tmp_path, 11, 13, 100, rule=1)
     run_case(emul, tmp_path, 3, 5, 100, shared=True)
+
+
+# ---- the evaluator's fused carry chain ------------------------------------------------------------
+CHAIN_EXE = os.path.join(HERE, "chain_emul.bin")
+
+
+@pytest.fixture(scope="module")
+def chain_emul():
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-o", CHAIN_EXE, os.path.join(HERE, "chain_emul.cpp")])
+    return CHAIN_EXE
+
+
+def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70):
+    """m[0..n-1] = accumulation moduli of digits 1..n.  The tables are random bytes below the output modulus:
+    the evaluator's result is defined by them alone, C_{j-1} = row[colour(S_j)] - H(S_j), S_j = sum_j + C_j
+    (Appendix, Garbled Mixed-Radix Addition), recomputed here with the oracle's hash."""
+    orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
+    n = len(m)
+    g = np.random.default_rng(sum(m) + n_elem)
+    slots = [slot0 + n - 1] + [slot0 + (j - 2) for j in range(2, n + 1)]          # digit 1 feeds the final gate
+    sums = [g.integers(0, mj, (n_elem, orc.lam(mj))).astype(np.uint8) for mj in m]
+    outm = [2] + m[:-1]                                                           # output modulus of the gate fed by digit j
+    tabs = []
+    for j in range(n):
+        lam_o = orc.lam(outm[j])
+        pitch = capi.pitch(lam_o)
+        t = np.zeros((n_elem, m[j], pitch), np.uint8)
+        t[:, :, :lam_o] = g.integers(0, outm[j], (n_elem, m[j], lam_o))
+        tabs.append(t)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, 0, 0, 0, elem_base)
+    blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % n, *slots)
+    blob += b"".join(s.tobytes() for s in sums) + b"".join(t.tobytes() for t in tabs)
+    fin, fout = str(tmp_path / "cin.bin"), str(tmp_path / "cout.bin")
+    open(fin, "wb").write(blob)
+    r = subprocess.run([chain_emul, fin, fout], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    got = np.fromfile(fout, np.uint8).reshape(n_elem, 128)
+    for e in range(n_elem):
+        carry = None
+        for j in range(n - 1, -1, -1):
+            S = sums[j][e].astype(np.int64)
+            if carry is not None:
+                S = (S + carry) % m[j]
+            S = S.astype(np.uint8)
+            h = orc.hash(S, m[j], layer, slots[j], elem_base + e, outm[j]).astype(np.int64)
+            lam_o = orc.lam(outm[j])
+            carry = (tabs[j][e, int(S[0]), :lam_o].astype(np.int64) - h) % outm[j]
+        assert (got[e] == carry).all(), (e, variant)
+
+
+def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
+    run_chain(chain_emul, tmp_path, [26] + [96] * 6, 1, 300)
+    run_chain(chain_emul, tmp_path, [26] + [96] * 6, 0, 70)
+    run_chain(chain_emul, tmp_path, [46] + [204] * 10, 2, 260)
+    run_chain(chain_emul, tmp_path, [46] + [204] * 10, 0, 40)
+    run_chain(chain_emul, tmp_path, [2, 6], 0, 257)                 # small bases: generic body, a 128-digit first label
+    run_chain(chain_emul, tmp_path, [2, 15, 27], 0, 65)
+    run_chain(chain_emul, tmp_path, [4, 60, 56], 0, 33, rule=1)
+    run_chain(chain_emul, tmp_path, [26, 96], 1, 5)                 # n = 2: no same-modulus step
