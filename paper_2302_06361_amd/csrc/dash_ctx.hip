@@ -227,6 +227,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
         off_dtab[m] = take((size_t)m * c->mods[m].ndw * 4);
     }
     for (int i = 0; i < k; i++) { off_one0[i] = take(c->mods[c->prime[i]].nchunk * 16); off_one[i] = take(c->mods[c->prime[i]].nchunk * 16); }
+    const size_t off_zero = take(256);
     c->pool_bytes = bytes;
 
     int status = DASH_EHIP;
@@ -253,6 +254,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
         c->phi_final[0] = c->d_pool + off_final[0];
         c->phi_final[1] = c->d_pool + off_final[1];
         c->phi_ident = c->d_pool + off_ident;
+        c->d_zero = c->d_pool + off_zero;
 
         // offset labels R_m and their multiples
         bool fail = false;

@@ -5,6 +5,12 @@
 // Residues and reduced weights are below p <= 127, so both operands are int8; the int32 accumulators are
 // exact because (p-1)^2 * K < 2^31 (checked by the caller) and a single reduction mod p follows.
 //
+// Convolutions run through the same kernel as an implicit GEMM (Sec. LabelTensors, the Conv2D figure): the
+// "batch element" of a group is then an output pixel and row k = (ky, kx, ci) of its K x 16 matrix is the
+// 16-byte word of input pixel (oy * stride - pad + ky, ox * stride - pad + kx), channel ci, or zeros
+// outside the image; with the channel count a multiple of 4, the four rows a loader thread fetches are
+// consecutive channels of one tap, i.e. 64 contiguous bytes.
+//
 // Shape.  A "group" is the 16 digits of one chunk of one batch element: in memory a K x 16 byte matrix
 // X_G (rows = input features, consecutive rows 16 bytes apart).  The layer is  Out_G (M x 16) = W (M x K)
 // * X_G  for every group, i.e. one GEMM  M x K x (16 * groups)  per prime whose B operand is
@@ -55,6 +61,10 @@ struct GemmArgs {
     int64_t kpad, mpad;
     const int32_t* bias;
     uint32_t small_acc;         // 1 if (p-1)^2 K < 2^24 for every prime: one-step reduction
+    // convolution geometry (conv = 0: dense, batch elements are the groups' columns)
+    int conv, in_h, in_w, in_c, kw, stride, pad, out_h, out_w;
+    uint32_t c_magic, kw_magic; // ceil(2^32 / in_c), ceil(2^32 / kw)
+    const uint8_t* zero;        // 64 zero bytes on the device
     int sty;                    // block rows per super-tile: 4, 2 or 1 (kStBlocks / sty block columns)
     int gy4;                    // super-tile rows: ceil(ceil(M / kBM) / sty)
     int st_total;               // super-tiles of all primes
@@ -106,7 +116,18 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     const bool gvalid = gglob < ngroups;
     // a group past the end reads group 0 (its results are never stored): loads need no predicate
     const int gch = gvalid ? gglob / A.batch : 0, gb = gvalid ? gglob - gch * A.batch : 0;
-    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + ((int64_t)gb * K) * 16;
+    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + (A.conv ? (int64_t)0 : ((int64_t)gb * K) * 16);
+    // convolution: gb = (image, oy, ox)
+    const int conv = A.conv, in_h = A.in_h, in_w = A.in_w, in_c = A.in_c, kw = A.kw;
+    const uint32_t c_magic = A.c_magic, kw_magic = A.kw_magic;
+    const uint8_t* const zero = A.zero;
+    int img = 0, iy0 = 0, ix0 = 0;
+    if (conv) {
+        const int per = A.out_h * A.out_w;
+        img = gb / per;
+        const int r = gb - img * per, oy = r / A.out_w, ox = r - oy * A.out_w;
+        iy0 = oy * A.stride - A.pad; ix0 = ox * A.stride - A.pad;
+    }
 
     // Global data is fetched two stages ahead into one of two register sets (a stage of MFMAs is shorter
     // than a miss in the L2), transposed and written to LDS one stage ahead.
@@ -122,9 +143,24 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
         const int k = k0 + 4 * bkq + kk;
         return (const u32x4*)(xg + (int64_t)(k < K ? k : K - 1) * 16);                                   // the weights are zero for k >= K
     };
+    // convolution: rows k..k+3 (k a multiple of 4, in_c a multiple of 4) are channels ci..ci+3 of one tap
+    auto conv_src = [&](int k0) __attribute__((always_inline)) {
+        const uint32_t k = (uint32_t)(k0 + 4 * bkq);
+        const uint32_t tap = mulhi(k, c_magic), ci = k - tap * (uint32_t)in_c;          // k < 2^24
+        const uint32_t ky = kw > 1 ? mulhi(tap, kw_magic) : tap, kx = tap - ky * (uint32_t)kw;
+        const int iy = iy0 + (int)ky, ix = ix0 + (int)kx;
+        const bool ok = (int)k < K && iy >= 0 && iy < in_h && ix >= 0 && ix < in_w;
+        const uint8_t* src = xg + ((((int64_t)img * in_h + iy) * in_w + ix) * in_c + ci) * 16;
+        return (const u32x4*)(ok ? src : zero);
+    };
     auto load_stage = [&](int k0, Regs& R) __attribute__((always_inline)) {
         R.a0 = *a_src(0, k0); R.a1 = *a_src(1, k0); R.a2 = *a_src(2, k0); R.a3 = *a_src(3, k0);
-        R.b0 = *b_src(0, k0); R.b1 = *b_src(1, k0); R.b2 = *b_src(2, k0); R.b3 = *b_src(3, k0);
+        if (conv) {
+            const u32x4* src = conv_src(k0);
+            R.b0 = src[0]; R.b1 = src[1]; R.b2 = src[2]; R.b3 = src[3];
+        } else {
+            R.b0 = *b_src(0, k0); R.b1 = *b_src(1, k0); R.b2 = *b_src(2, k0); R.b3 = *b_src(3, k0);
+        }
     };
     auto store_stage = [&](int buf, const Regs& R) __attribute__((always_inline)) {
         uint8_t* ad = As[buf] + arow * kRow + apart * 16;
@@ -247,17 +283,32 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     if (small_acc) emit(std::true_type{}); else emit(std::false_type{});
 }
 
-// true if the MFMA path should take this dense layer (large enough to fill tiles)
+// true if the MFMA path should take this dense or convolution layer (large enough to fill tiles; for a
+// convolution the channel count must be a multiple of 4, see above)
 bool dense_mfma_wanted(const dash_layer* L, int64_t batch) {
-    return L->kind == DASH_DENSE && (int64_t)L->in_c * L->out_c >= 64 * 64 && (int64_t)L->out_c * batch >= 64;
+    if (L->kind == DASH_DENSE) return (int64_t)L->in_c * L->out_c >= 64 * 64 && (int64_t)L->out_c * batch >= 64;
+    if (L->kind != DASH_CONV2D || L->in_c % 4 != 0 || L->stride < 1) return false;
+    const int64_t K = (int64_t)L->kh * L->kw * L->in_c;
+    const int64_t oh = (L->in_h + 2 * L->pad - L->kh) / L->stride + 1, ow = (L->in_w + 2 * L->pad - L->kw) / L->stride + 1;
+    // (K * in_c < 2^31: the multiply-high divisions by in_c and kw are exact)
+    return K * L->out_c >= 64 * 64 && K * L->in_c < (1ll << 31) && batch * oh * ow >= 16 && batch * oh * ow < (1ll << 31);
 }
 
 int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s) {
-    const int M = L->out_c, K = L->in_c;
-    const int64_t batch = L->n_elem;
+    const bool conv = L->kind == DASH_CONV2D;
+    const int out_h = conv ? (L->in_h + 2 * L->pad - L->kh) / L->stride + 1 : 1, out_w = conv ? (L->in_w + 2 * L->pad - L->kw) / L->stride + 1 : 1;
+    const int M = L->out_c, K = conv ? L->kh * L->kw * L->in_c : L->in_c;
+    const int64_t batch = conv ? L->n_elem * out_h * out_w : L->n_elem;      // columns: batch elements, or output pixels
     GemmArgs A;
     memset(&A, 0, sizeof(A));
     A.M = M; A.K = K; A.batch = (int)batch; A.nprimes = c->k;
+    if (conv) {
+        A.conv = 1; A.in_h = L->in_h; A.in_w = L->in_w; A.in_c = L->in_c; A.kw = L->kw; A.stride = L->stride; A.pad = L->pad;
+        A.out_h = out_h; A.out_w = out_w;
+        A.c_magic = (uint32_t)(((1ull << 32) + L->in_c - 1) / L->in_c);
+        A.kw_magic = L->kw > 1 ? (uint32_t)(((1ull << 32) + L->kw - 1) / L->kw) : 0;
+        A.zero = c->d_zero;
+    }
     A.kpad = ((int64_t)K + 63) / 64 * 64; A.mpad = ((int64_t)M + 31) / 32 * 32;
     A.bias = L->bias;
     A.small_acc = 1;

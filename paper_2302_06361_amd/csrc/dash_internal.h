@@ -59,6 +59,7 @@ struct dash_ctx {
     const uint8_t* phi_carry[DASH_MAX_DIGITS + 1];                   // [j] -> [m_j], j = 2..n
     const uint8_t* phi_final[2];                                     // [negate] -> [m_1]
     const uint8_t* phi_ident;                                        // {0, 1}
+    const uint8_t* d_zero;                                           // 256 zero bytes
     const uint8_t* phi_pm1[DASH_MAX_PRIMES];                         // {1, p-1}
 };
 

@@ -85,3 +85,13 @@ def test_dense_mfma_config4_sample():
     """config 4 shape on a slice: K = 4096 inputs (one-step reduction no longer applies for the larger
     primes), 96 output rows, batch 2, all 12 primes, weights in [-64, 63]"""
     run_linear(12, 2, 1, 1, 4096, 96, 1, 1, 0, -64, 63, False, 24)
+
+
+def test_conv_mfma_shapes():
+    """convolutions that take the MFMA kernel as an implicit GEMM (channels a multiple of 4): stride, padding,
+    bias, batches, a 1x1 kernel, pixel counts that leave ragged group tiles, K not a multiple of 64"""
+    run_linear(12, 2, 9, 7, 8, 40, 3, 2, 1, -16, 15, True, 31)
+    run_linear(8, 3, 6, 6, 4, 70, 5, 1, 2, -8, 7, False, 32)
+    run_linear(8, 1, 5, 5, 64, 64, 1, 1, 0, -8, 7, True, 33, garble=False)
+    run_linear(12, 1, 16, 16, 12, 48, 3, 1, 1, -16, 15, False, 34)
+    run_linear(5, 2, 7, 7, 20, 33, 3, 1, 0, -3, 3, True, 35)
