@@ -193,6 +193,42 @@ def micro_contraction(torch, workloads, reps=5):
     return out
 
 
+def micro_vgg(torch, workloads, images=1, reps=2):
+    """Config 5, streamed: garble + evaluate layer by layer, `images` images of the batch of 64 at a time."""
+    from paper_2302_06361_amd import Context, StreamedNetwork
+    net = workloads.vgg(seed=5, batch=64)
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    g = StreamedNetwork(ctx, net, batch=images)
+    x = torch.as_tensor(net["x"][:images * net["n_in"]]).to(ctx.device)
+    k, n = ctx.k, len(ctx.digits)
+    lam_sum = sum(ctx.lam(p) for p in ctx.primes)
+    sub = dict(net, batch=images)
+    gates, macs = gate_counts(sub, k, n), mac_counts(sub, lam_sum)
+    g.run(x)
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    read_profiles(ctx)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.run(x)
+    e1.record()
+    torch.cuda.synchronize()
+    ctx.profile_enable(False)
+    pr = read_profiles(ctx)
+    ms = e0.elapsed_time(e1) / reps
+    out = dict(workload="config 5: VGG shape (12 primes, scale 2^5), %d image(s) of the batch of 64 streamed layer by layer, "
+                        "garble + evaluate + decode" % images,
+               images=images, ms=ms, ms_per_image=ms / images, outputs_valid=bool(g.valid.all().item()),
+               table_bytes_per_image=g.table_bytes // images, gates_per_image=gates // images,
+               gates_per_s=2 * gates / (ms * 1e-3), label_macs_per_image=2 * macs // images,
+               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_proj_eval=kernel_line(pr["eval"], reps),
+                            linear=kernel_line(pr["linear"], reps)))
+    ctx.close()
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,7 +237,7 @@ def main():
     ap.add_argument("--batch", type=int, default=16, help="batch elements of config 2 (16 = the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true", help="skip the config-3 and config-4 microbenchmarks")
-    ap.add_argument("--only", choices=["config3", "config4"], help="run one microbenchmark alone (for profiling); prints its JSON object")
+    ap.add_argument("--only", choices=["config3", "config4", "config5"], help="run one microbenchmark alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures ONE GPU (every box has one); --gpus %d is not supported" % a.gpus, file=sys.stderr)
@@ -213,7 +249,8 @@ def main():
     from paper_2302_06361_amd import Context, GarbledNetwork
 
     if a.only:
-        print(json.dumps(micro_projection(torch, workloads) if a.only == "config3" else micro_contraction(torch, workloads)))
+        fn = dict(config3=micro_projection, config4=micro_contraction, config5=micro_vgg)[a.only]
+        print(json.dumps(fn(torch, workloads)))
         return
 
     net = workloads.lenet(seed=2, batch=a.batch)

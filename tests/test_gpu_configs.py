@@ -190,3 +190,10 @@ def test_config5_vgg_full_width_one_image():
     the plain evaluation and the label invariant on every boundary."""
     g = vgg_check(workloads.vgg(seed=5, batch=64), 1, exact=False)
     print("config 5: %.1f GB of tables per image" % (g.table_bytes / 1e9))
+
+
+@pytest.mark.parametrize("name", ["f", "F"])
+def test_paper_cifar_model_shapes(name):
+    """the CIFAR-sized models f and F of the paper's table (7-prime base, rescaling by 2^5 after every ReLU): one
+    image, decoded outputs against the plain evaluation and the label invariant on every boundary"""
+    vgg_check(workloads.paper_model(name, seed=6), 1, exact=False)

@@ -11,9 +11,9 @@ from oracle import plain
 pytestmark = pytest.mark.gpu
 
 
-def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500):
+def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500, digits=None, exact=True):
     from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN
-    ctx, orc = both(k, rule)
+    ctx, orc = both(k, rule, digits=digits)
     n = len(X)
     zero = [orc.input_labels(first_wire, n, i) for i in range(k)]
     act = [orc.encode(i, np.asarray(X), zero[i]) for i in range(k)]
@@ -46,7 +46,7 @@ def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wir
     assert_tables_equal(tables, rt, kind + " tables")
     assert_bundle_equal(oa, r, kind + " active labels")
     vals, valid = orc.decode(r, r0)
-    assert valid.all() and (vals == plain.to_signed(want, orc.P)).all()
+    assert valid.all() and (not exact or (vals == plain.to_signed(want, orc.P)).all())
 
 
 @pytest.mark.parametrize("k", [2, 3, 4])
@@ -82,3 +82,15 @@ def test_activation_floor_rule():
 def test_activation_single_element():
     run_activation(8, "relu", np.array([12345]))
     run_activation(8, "scale", np.array([9699689]), repeat=3)
+
+
+def test_reduced_accuracy_digit_sets():
+    """fewer mixed-radix digits (M < k P, Appendix, Approximated Garbled Sign): the approximated gadgets, bit for
+    bit against the oracle, for the 3-digit set of the 8-prime base and a 2-digit set of a small base"""
+    P8 = int(np.prod(workloads.PRIMES[:8]))
+    g = np.random.default_rng(77)
+    X = np.concatenate([g.integers(0, P8, 300), [0, 1, P8 // 2 - 1, P8 // 2, P8 - 1], P8 // 2 - 1 - g.integers(0, 20000, 100)])
+    for kind, rep in (("relu", 1), ("scale", 2), ("sign", 1)):
+        run_activation(8, kind, X, repeat=rep, digits=workloads.DIGITS_REDUCED[8], exact=False)
+    P4 = int(np.prod(workloads.PRIMES[:4]))
+    run_activation(4, "relu", np.arange(P4), digits=(4, 15), exact=False)

@@ -67,3 +67,10 @@ def test_batch_chunk_matches_full_batch_labels():
 @pytest.mark.parametrize("centered", [False, True])
 def test_mlp_config1(centered):
     run_net(workloads.mlp(seed=1, centered=centered))
+
+
+@pytest.mark.parametrize("name", ["A", "B", "C", "D"])
+def test_paper_model_shapes(name):
+    """the MNIST-sized models of the paper's table of architectures (strided convolutions, biases, 8- and 9-prime
+    bases, no rescaling) with random weights: every label, table byte and output against the oracle"""
+    run_net(workloads.paper_model(name, seed=6))

@@ -315,3 +315,38 @@ def test_decode_flags_forged_labels():
     act[1][2, 5] = (act[1][2, 5] + 1) % 3           # one digit of one residue of element 2
     vals, valid = orc.decode(act, zero)
     assert valid.tolist() == [1, 1, 0, 1, 1] and vals[2] == 0
+
+
+# ---- reduced-accuracy sign (Appendix, Approximated Garbled Sign: fewer digits, M < k P) -------------
+@pytest.mark.parametrize("k,digits", [(4, (4, 15)), (5, (2, 12, 25)), (5, (6, 20))])
+def test_reduced_accuracy_sign_errs_only_next_to_the_boundaries(k, digits):
+    """With M < k P the k rounded-up terms overestimate the fraction X/P by less than k/M: the approximated sign
+    can differ from [X >= P/2] only for fractions within k/M below 1/2 or below 1, and never elsewhere."""
+    orc = capi.Oracle(workloads.PRIMES[:k], digits, SEED)
+    P, M = orc.P, orc.M
+    assert M < k * P
+    wrong = 0
+    for X in range(P):
+        got = orc.sign_plain(residues(X, orc.primes), 0, 0)
+        exact = int(2 * X >= P)
+        if got != exact:
+            wrong += 1
+            f = X / P
+            assert (0.5 - k / M <= f < 0.5) or (1 - k / M <= f < 1), X
+    assert 0 < wrong <= 2 * k * P / M + 2
+
+
+def test_reduced_accuracy_relu_garbled_equals_its_plain_approximation():
+    """the garbled gadget computes exactly the approximated function, wrong values included"""
+    k, digits = 4, (4, 15)
+    orc = capi.Oracle(workloads.PRIMES[:k], digits, SEED)
+    P = orc.P
+    X = np.arange(P)
+    zero, act = bundle_for(orc, X)
+    out0, tables = orc.relu_garble(5, zero)
+    out = orc.relu_eval(5, act, tables)
+    vals, valid = orc.decode(out, out0)
+    assert valid.all()
+    pos = np.array([orc.sign_plain(residues(int(x), orc.primes), 0, 1) for x in X])
+    assert (vals == plain.to_signed(np.where(pos == 1, X, 0), P)).all()
+    assert (pos != (2 * X < P)).any()

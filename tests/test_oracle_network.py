@@ -77,3 +77,9 @@ def test_mlp_config1(centered):
     sizes = r["gb"]["tables"]
     assert sizes[2].size == 128 * r["orc"].relu_bytes_per_elem()
     assert sizes[3].size == 128 * 6 * r["orc"].scale_bytes_per_elem()
+
+
+def test_paper_model_c_shape():
+    """Model C of the paper's table of architectures (strided convolution without padding, biases, 9 primes,
+    no rescaling), random weights"""
+    check_network(workloads.paper_model("C", seed=6))

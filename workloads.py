@@ -28,8 +28,18 @@ DIGITS = {
     3: (2, 5, 9),
     4: (4, 15, 14),
     5: (2, 12, 25, 20),
+    7: (10,) + (13,) * 5,
     8: (26, 12, 12, 12, 12, 12, 12),
+    9: (22,) + (10,) * 8,
     12: (46,) + (17,) * 10,
+}
+# (7 and 9: the sets (d_1; d, .., d) with the fewest table bytes per sign gadget, found by exhaustive search)
+
+# Reduced-accuracy sign (Appendix, Approximated Garbled Sign): fewer digits, prod(d) < k * P_k.  The k-term sum
+# of fractions rounded up to 1/M overestimates by less than k/M, so the sign is wrong only for values whose
+# fraction X/P lies within k/M below 1/2 or below 1: at most a share 2k/M of all values.
+DIGITS_REDUCED = {
+    8: (26, 12, 12),          # M = 3744: wrong for at most 0.43 % of the values, 27 gates per sign instead of 63
 }
 
 
@@ -160,6 +170,45 @@ def tiny_cnn(seed=8, k=4, batch=2, repeat=1):
     if repeat:
         b.scale(repeat)
     b.dense(3)
+    return b.net
+
+
+# Sec. Model architectures, the table of models: (in, out, filter, stride) convolutions without padding, R = ReLU,
+# (a) = dense layer.  CRT bases per model as in the text; models f and F rescale by 2^5 after every ReLU.
+PAPER_MODELS = {
+    "A": dict(k=8, hw=28, c=1, scale=0, layers=[("d", 128), "R", ("d", 128), "R", ("d", 10)]),
+    "B": dict(k=9, hw=28, c=1, scale=0, layers=[("c", 5, 5, 1), "R", ("c", 5, 3, 3), "R", ("c", 10, 3, 1), "R", ("c", 10, 3, 3), "R",
+                                                  ("d", 100), "R", ("d", 10)]),
+    "C": dict(k=9, hw=28, c=1, scale=0, layers=[("c", 5, 4, 2), "R", ("d", 100), "R", ("d", 10)]),
+    "D": dict(k=8, hw=28, c=1, scale=0, layers=[("c", 16, 6, 2), "R", ("c", 16, 6, 2), "R", ("d", 100), "R", ("d", 10)]),
+    "f": dict(k=7, hw=32, c=3, scale=5, layers=[("c", 32, 3, 1), "R", ("c", 32, 3, 1), "R", ("c", 32, 2, 2), ("c", 64, 3, 1), "R",
+                                                  ("c", 64, 3, 1), "R", ("c", 64, 2, 2), ("c", 128, 3, 1), "R", ("c", 128, 3, 1), "R", ("d", 10)]),
+    "F": dict(k=7, hw=32, c=3, scale=5, layers=[("c", 64, 3, 1), "R", ("c", 64, 3, 1), "R", ("c", 64, 2, 2), ("c", 64, 3, 1), "R",
+                                                  ("c", 64, 3, 1), "R", ("c", 64, 2, 2), ("c", 64, 3, 1), "R", ("c", 64, 1, 1), "R",
+                                                  ("c", 16, 1, 1), "R", ("d", 10)]),
+}
+
+
+def paper_model(name, seed=6, batch=1, centered=True):
+    """The SHAPE of one of the paper's models A, B, C, D, f, F with random integer weights and biases (the trained
+    weights are not available; run time does not depend on them)."""
+    spec = PAPER_MODELS[name]
+    hw, ch = spec["hw"], spec["c"]
+    b = _Builder(seed, spec["k"], batch, hw * hw * ch, -7 if centered else -8, 7)
+    h = w = hw
+    for L in spec["layers"]:
+        if L == "R":
+            b.relu()
+            if spec["scale"]:
+                b.scale(spec["scale"])
+        elif L[0] == "c":
+            _, out_c, ks, stride = L
+            b.conv(h, w, ch, out_c, ks, stride=stride, pad=0, bias=True)
+            h, w, ch = (h - ks) // stride + 1, (w - ks) // stride + 1, out_c
+        else:
+            b.dense(L[1], bias=True)
+            h = w = 1
+            ch = L[1]
     return b.net
 
 
