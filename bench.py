@@ -21,12 +21,11 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # Figures taken from the rocprofv3 --pmc runs of this same command (profiles/k_proj_garble_lenet_b16_pmc.txt):
-# vector instructions per ciphertext row of k_proj_garble / per gate of k_proj_eval, averaged over the
-# launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per launch
-# (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up).
-PMC = dict(garble_valu_per_row=739.2, eval_valu_per_gate=659.0,
-           garble_fetch_bytes_per_launch=7169701 * 1024 * 2.0 / 1188,     # FETCH_SIZE reads 0.5 KiB per KiB copied
-           garble_write_bytes_per_launch=60526835 * 1024 * 1.0 / 1188)    # WRITE_SIZE reads 1.0 KiB per KiB copied
+# vector instructions per ciphertext row of k_proj_garble / per gate of the evaluator's gate kernels, averaged over
+# the launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per row (FETCH_SIZE,
+# WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up: 2.0 and 1.0).
+PMC = dict(garble_valu_per_row=746.7, eval_valu_per_gate=728.7,
+           garble_fetch_bytes_per_row=5.42, garble_write_bytes_per_row=26.70)
 
 
 def gate_counts(net, k, n_digits):
@@ -229,6 +228,40 @@ def micro_vgg(torch, workloads, images=1, reps=2):
     return out
 
 
+def micro_paper_models(torch, workloads, reps=5):
+    """The shapes of the paper's models A-F (Sec. Model architectures), batch 1, random weights: garbling time
+    (offline in the paper) and evaluation time (its online figure, there including a modelled network cost)."""
+    from paper_2302_06361_amd import Context, GarbledNetwork
+    out = {}
+    for name in "ABCDfF":
+        net = workloads.paper_model(name, seed=6)
+        ctx = Context(net["primes"], net["seed"], net["digits"])
+        g = GarbledNetwork(ctx, net)
+        x = torch.as_tensor(net["x"]).to(ctx.device)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for r in range(reps + 1):
+            if r == 1:
+                torch.cuda.synchronize()
+                ev[0].record()
+            g.garble()
+        ev[1].record()
+        g.encode(x)
+        for _ in range(reps):
+            g.evaluate()
+            g.decode()
+        ev[2].record()
+        torch.cuda.synchronize()
+        out[name] = dict(primes=len(net["primes"]), relu_values=sum(L["n"] for L in net["layers"] if L["kind"] == "relu"),
+                         table_bytes=g.table_bytes, garble_ms=ev[0].elapsed_time(ev[1]) / reps,
+                         eval_ms=ev[1].elapsed_time(ev[2]) / reps, outputs_valid=bool(g.valid.all().item()))
+        del g
+        ctx.close()
+        torch.cuda.empty_cache()
+    return dict(workload="paper model shapes A-F, batch 1, random integer weights and biases", models=out,
+                paper_online_ms_gpu=dict(A=10, B=32, C=16, D=42, f=1332, F=1443),
+                note="the paper's figures (its Table of online runtimes, other hardware) include a modelled 1 Gbit/s transfer; context only")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -237,7 +270,7 @@ def main():
     ap.add_argument("--batch", type=int, default=16, help="batch elements of config 2 (16 = the config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true", help="skip the config-3 and config-4 microbenchmarks")
-    ap.add_argument("--only", choices=["config3", "config4", "config5"], help="run one microbenchmark alone (for profiling); prints its JSON object")
+    ap.add_argument("--only", choices=["config3", "config4", "config5", "paper_models"], help="run one microbenchmark alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures ONE GPU (every box has one); --gpus %d is not supported" % a.gpus, file=sys.stderr)
@@ -249,7 +282,7 @@ def main():
     from paper_2302_06361_amd import Context, GarbledNetwork
 
     if a.only:
-        fn = dict(config3=micro_projection, config4=micro_contraction, config5=micro_vgg)[a.only]
+        fn = dict(config3=micro_projection, config4=micro_contraction, config5=micro_vgg, paper_models=micro_paper_models)[a.only]
         print(json.dumps(fn(torch, workloads)))
         return
 
@@ -317,8 +350,7 @@ def main():
         rows_per_launch=kg["units_per_launch"], rows_per_s=kg["units_per_s"], lane_ops_per_row=valu,
         hbm_algorithmic_GBps=kg["gbytes_per_s"], hbm_frac=kg["gbytes_per_s"] / HBM_PEAK_GBS,
         algorithmic_bytes_per_launch=kg["bytes_per_launch"],
-        traffic=(PMC["garble_fetch_bytes_per_launch"] + PMC["garble_write_bytes_per_launch"])
-        if PMC["garble_fetch_bytes_per_launch"] is not None else None)
+        traffic=(PMC["garble_fetch_bytes_per_row"] + PMC["garble_write_bytes_per_row"]) * kg["units_per_launch"])
     roofline["frac"] = roofline["achieved"] / ALU_PEAK_TOPS if roofline["achieved"] else None
     ev_valu = PMC["eval_valu_per_gate"]
     roofline_eval = dict(kernel="k_proj_eval", bound="alu", unit=roofline["unit"], peak=ALU_PEAK_TOPS,

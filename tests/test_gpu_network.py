@@ -74,3 +74,48 @@ def test_paper_model_shapes(name):
     """the MNIST-sized models of the paper's table of architectures (strided convolutions, biases, 8- and 9-prime
     bases, no rescaling) with random weights: every label, table byte and output against the oracle"""
     run_net(workloads.paper_model(name, seed=6))
+
+
+def test_layer_calls_can_be_captured_in_a_graph():
+    """garble and evaluate only enqueue kernels on the caller's stream: captured in HIP graphs and replayed
+    several times, with eager work and synchronisations in between, every replay reproduces the eager tables
+    and outputs"""
+    from paper_2302_06361_amd import Context, GarbledNetwork
+    net = workloads.paper_model("C", seed=6)
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    g = GarbledNetwork(ctx, net)
+    x = torch.as_tensor(net["x"]).to(ctx.device)
+    g.garble(); g.encode(x); g.evaluate(); g.decode()
+    torch.cuda.synchronize()
+    ref_values = g.values.clone()
+    ref_tables = [None if t is None else t.clone() for t in g.tables]
+    ref_act = [t.clone() for t in g.act[-1].tensors]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on a side stream, as capture requires
+        g.garble(); g.evaluate(); g.decode()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gg, ge = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gg):
+        g.garble()
+    with torch.cuda.graph(ge):
+        g.evaluate(); g.decode()
+    for rep in range(3):
+        for t in g.tables:
+            if t is not None:
+                t.fill_(rep)
+        g.values.zero_()
+        for t in g.act[-1].tensors:
+            t.fill_(0xEE)
+        torch.cuda.synchronize()
+        gg.replay()
+        g.encode(x)                        # eager work between the replays
+        torch.cuda.synchronize()
+        ge.replay()
+        torch.cuda.synchronize()
+        for t, r in zip(g.tables, ref_tables):
+            assert t is None or bool((t == r).all().item()), rep
+        assert bool((g.values == ref_values).all().item()) and bool(g.valid.all().item()), rep
+        for t, r in zip(g.act[-1].tensors, ref_act):
+            assert bool((t == r).all().item()), rep
