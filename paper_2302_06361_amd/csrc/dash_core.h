@@ -53,6 +53,7 @@ constexpr uint32_t floor_log2(uint64_t v) { uint32_t l = 0; while ((2ull << l) <
 constexpr uint64_t ipow(uint64_t b, uint32_t e) { uint64_t r = 1; for (uint32_t i = 0; i < e; i++) r *= b; return r; }
 constexpr uint32_t gc_of(uint32_t m) { uint32_t g = 0; while (g < 8 && ipow(m, 4 * (g + 1)) < (1ull << 32)) g++; return g; }
 constexpr uint32_t twos_of(uint32_t m) { uint32_t t = 0; while (!(m & 1)) { m >>= 1; t++; } return t; }
+constexpr uint32_t bits_of(uint64_t v) { uint32_t b = 0; while (v) { b++; v >>= 1; } return b; }   // v < 2^bits_of(v)
 // largest g with mo^g <= 2^15, the super-digit (mo^g - 1) * 2^(tw g) + ... below 2^32 and, for the digit
 // extraction, (m^g >> tw) below 2^24 (powers of two: at most 24 bits per super-digit)
 constexpr bool gd_ok(uint32_t m, uint32_t g) {
@@ -172,6 +173,41 @@ DASH_HD void muladd128(U128& a, uint32_t mul, uint32_t add) {
     t += (uint64_t)a.w[3] * mul; a.w[3] = (uint32_t)t;
 }
 
+// acc = acc * mul + add (mod 2^128) for an accumulator known to fit W words: W multiplications
+template <int W>
+DASH_HD void muladd128_w(U128& a, uint32_t mul, uint32_t add) {
+    uint64_t t = add;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        if (i < W) { t += (uint64_t)a.w[i] * mul; a.w[i] = (uint32_t)t; t >>= 32; }
+        else if (i == W) a.w[i] = (uint32_t)t;
+    }
+}
+// compile-time descriptions: super-digit T (counted from the top) and all below it.  Before it is folded in, the
+// accumulator is below Qc^T, so only the words that can be non-zero are multiplied.
+template <class MI, int T, class LoadDw>
+DASH_HD void compress_from(U128& acc, LoadDw& dw, uint32_t& w0) {
+    constexpr int NS = ((int)MI::ndw + (int)MI::gc - 1) / (int)MI::gc;
+    if constexpr (T < NS) {
+        constexpr int top = (int)MI::ndw - (NS - 1) * (int)MI::gc;        // dwords of the top super-digit (may be short)
+        constexpr int cnt = T == 0 ? top : (int)MI::gc;
+        constexpr int hi = T == 0 ? (int)MI::ndw - 1 : (int)MI::ndw - 1 - top - (T - 1) * (int)MI::gc;
+        constexpr uint32_t wlo = 1u | (MI::m << 8), whi = (1u << 16) | (MI::m << 24), m2 = MI::m * MI::m, m4 = m2 * m2;
+        uint32_t S = 0;
+#pragma unroll
+        for (int c = 0; c < cnt; c++) {
+            const uint32_t w = dw(hi - c);
+            if (hi - c == 0) w0 = w;
+            const uint32_t v = dot4(w, wlo) + mul24(m2, dot4(w, whi));     // < m^4; both factors below 2^17
+            S = c == 0 ? v : (MI::Qc < (1u << 24) ? mul24(S, m4) : S * m4) + v;
+        }
+        constexpr int wbits = T * (int)cm::bits_of((uint64_t)MI::Qc - 1);
+        constexpr int W = T == 0 ? 0 : (wbits + 31) / 32 > 4 ? 4 : (wbits + 31) / 32;
+        muladd128_w<W>(acc, MI::Qc, S);
+        compress_from<MI, T + 1>(acc, dw, w0);
+    }
+}
+
 // compress(l) = sum_j l[j] m^j mod 2^128 (Horner from the top digit).  dw(i) returns packed digits
 // 4i..4i+3 of the label, digits past lam zero.  *colour receives digit 0.
 // Four digits at a time: v = d0 + m d1 + m^2 d2 + m^3 d3 by two byte dot products; gc such values
@@ -189,6 +225,12 @@ DASH_HD U128 compress(const MI& M, LoadDw dw, uint32_t* colour) {
             if (i == 0) w0 = w;
             acc.w[i >> 3] |= dot4(w, 0x08040201u) << (4 * (i & 7));
         }
+        *colour = w0 & 0xffu;
+        return acc;
+    }
+    if constexpr (cmod_m<MI>::value > 2) {
+        uint32_t w0 = 0;
+        compress_from<MI, 0>(acc, dw, w0);
         *colour = w0 & 0xffu;
         return acc;
     }
@@ -299,13 +341,74 @@ DASH_HD uint32_t take_superdigit(U128& x, const MI& M, uint32_t bits) {
     return (r << M.dsh) | low;
 }
 
+// Compile-time descriptions: the gd digits of a super-digit S < m^G are split by halving, S = hi * m^G1 + lo,
+// so that all but the first division work on numbers below 2^15, where floor(n / D) = (n * M) >> s with a
+// 24-bit multiplication (M = ceil(2^s / D), s = bits(n) + ceil(log2 D): n * (M D - 2^s) < 2^s, so the result is
+// exact, and n * M < 2^32).  A 32-bit multiply-high runs at a quarter of that rate.
+template <class MI, int G>
+DASH_HD void split_digits(uint32_t S, uint32_t* d) {
+    if constexpr (G == 1) {
+        d[0] = S;
+    } else {
+        constexpr int G1 = G / 2, G2 = G - G1;
+        constexpr uint64_t mG = cm::ipow(MI::m, G), mG1 = cm::ipow(MI::m, G1), D = cm::ipow(MI::mo, G1);
+        constexpr uint32_t sh = MI::tw * G1;
+        constexpr uint64_t nmax = (mG - 1) >> sh;                 // S >> sh <= nmax
+        constexpr uint32_t a = cm::bits_of(nmax);
+        const uint32_t n = S >> sh;                               // floor(S / m^G1) = floor(n / D)
+        uint32_t hi;
+        if constexpr (D == 1) {
+            hi = n;
+        } else if constexpr (a <= 15) {
+            constexpr uint32_t sft = a + cm::ceil_log2(D);
+            constexpr uint32_t Mg = (uint32_t)(((1ull << sft) + D - 1) / D);
+            static_assert(nmax * Mg < (1ull << 32) && Mg < (1u << 24), "24-bit magic division out of range");
+            hi = mul24(n, Mg) >> sft;
+        } else {
+            static_assert(a + cm::ceil_log2(D) <= 32 && D < (1ull << 32), "multiply-high division out of range");
+            hi = mulhi(n, (uint32_t)(((1ull << 32) + D - 1) / D));
+        }
+        static_assert(mG1 < (1ull << 24) && (mG - 1) / mG1 < (1ull << 24), "24-bit multiply out of range");
+        const uint32_t lo = S - mul24(hi, (uint32_t)mG1);
+        split_digits<MI, G1>(lo, d);
+        split_digits<MI, G2>(hi, d + G1);
+    }
+}
+// super-digit SD and all after it (compile-time descriptions under the ceil rule: m^lam >= 2^128, so the last
+// super-digit holds exactly the digits that are left)
+template <class MI, int SD, class Emit>
+DASH_HD void decompress_from(const MI& M, U128& x, uint32_t& w, Emit& emit) {
+    constexpr int first = SD * (int)MI::gd;
+    if constexpr (first < (int)MI::lam) {
+        constexpr int G = (int)MI::lam - first < (int)MI::gd ? (int)MI::lam - first : (int)MI::gd;
+        constexpr uint32_t bits = 128u > SD * MI::Qdbits ? 128u - SD * MI::Qdbits : 0u;
+        const uint32_t S = take_superdigit(x, M, bits);
+        uint32_t d[G];
+        split_digits<MI, G>(S, d);
+#pragma unroll
+        for (int t = 0; t < G; t++) {
+            const int j = first + t;
+            w |= d[t] << (8 * (j & 3));
+            if ((j & 3) == 3) { emit(j >> 2, w); w = 0; }
+        }
+        decompress_from<MI, SD + 1>(M, x, w, emit);
+    }
+}
+
 template <class MI, class Emit>
 DASH_HD void decompress(const MI& M, const U128& h, Emit emit) {
+    if constexpr (cmod_m<MI>::value > 2) {
+        U128 x = h;
+        uint32_t w = 0;
+        decompress_from<MI, 0>(M, x, w, emit);
+        if (MI::lam & 3) emit((int)(MI::lam >> 2), w);
+        return;
+    }
     if constexpr (cmod_m<MI>::value == 2) {   // digits are bits: spread 4 bits into 4 bytes
 #pragma unroll
         for (int i = 0; i < (int)M.ndw; i++) {
             uint32_t nib = (h.w[i >> 3] >> (4 * (i & 7))) & 0xfu;
-            emit(i, (nib * 0x00204081u) & 0x01010101u);
+            emit(i, mul24(nib, 0x00204081u) & 0x01010101u);
         }
         return;
     }
