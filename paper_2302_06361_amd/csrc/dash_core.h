@@ -13,6 +13,8 @@
 #pragma once
 #include <stdint.h>
 
+#include <type_traits>
+
 #if defined(__HIPCC__)
 #include <hip/hip_runtime.h>
 #define DASH_HD __host__ __device__ __forceinline__
@@ -266,10 +268,30 @@ DASH_HD uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
 }
 
 // Tab: the T-tables.  T.template at<R, B>(w) is entry (byte B of w) of table R; the accessor gets the whole
-// word so that a table layout can build its address from the byte in place.
+// word so that a table layout can build its address from the byte in place.  A layout with
+// Tab::two_tables holds T0 and T1 only: T2 = rot16(T0), T3 = rot16(T1), and one rotation serves both.
+template <class Tab, class = void> struct tab_two : std::false_type {};
+template <class Tab> struct tab_two<Tab, std::enable_if_t<Tab::two_tables>> : std::true_type {};
+DASH_HD uint32_t rot16(uint32_t v) { return (v << 16) | (v >> 16); }
+
 template <class Tab>
 DASH_HD void aes128_encrypt(uint32_t s[4], const uint32_t* rk, const Tab& T) {
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
+    if constexpr (tab_two<Tab>::value) {
+#pragma unroll
+        for (int r = 1; r < 10; r++) {
+            uint32_t b0 = xor3(T.template at<0, 0>(a0), T.template at<1, 1>(a1), rk[4 * r + 0]) ^ rot16(T.template at<0, 2>(a2) ^ T.template at<1, 3>(a3));
+            uint32_t b1 = xor3(T.template at<0, 0>(a1), T.template at<1, 1>(a2), rk[4 * r + 1]) ^ rot16(T.template at<0, 2>(a3) ^ T.template at<1, 3>(a0));
+            uint32_t b2 = xor3(T.template at<0, 0>(a2), T.template at<1, 1>(a3), rk[4 * r + 2]) ^ rot16(T.template at<0, 2>(a0) ^ T.template at<1, 3>(a1));
+            uint32_t b3 = xor3(T.template at<0, 0>(a3), T.template at<1, 1>(a0), rk[4 * r + 3]) ^ rot16(T.template at<0, 2>(a1) ^ T.template at<1, 3>(a2));
+            a0 = b0; a1 = b1; a2 = b2; a3 = b3;
+        }
+        // last round: S[x] sits in bytes 1 and 2 of T0 and in bytes 2 and 3 of T1
+        s[0] = (((T.template at<0, 0>(a0) >> 8) & 0xffu) | (T.template at<0, 1>(a1) & 0xff00u) | (T.template at<0, 2>(a2) & 0xff0000u) | (T.template at<1, 3>(a3) & 0xff000000u)) ^ rk[40];
+        s[1] = (((T.template at<0, 0>(a1) >> 8) & 0xffu) | (T.template at<0, 1>(a2) & 0xff00u) | (T.template at<0, 2>(a3) & 0xff0000u) | (T.template at<1, 3>(a0) & 0xff000000u)) ^ rk[41];
+        s[2] = (((T.template at<0, 0>(a2) >> 8) & 0xffu) | (T.template at<0, 1>(a3) & 0xff00u) | (T.template at<0, 2>(a0) & 0xff0000u) | (T.template at<1, 3>(a1) & 0xff000000u)) ^ rk[42];
+        s[3] = (((T.template at<0, 0>(a3) >> 8) & 0xffu) | (T.template at<0, 1>(a0) & 0xff00u) | (T.template at<0, 2>(a1) & 0xff0000u) | (T.template at<1, 3>(a2) & 0xff000000u)) ^ rk[43];
+    } else {
 #pragma unroll
     for (int r = 1; r < 10; r++) {
         uint32_t b0 = xor3(xor3(T.template at<0, 0>(a0), T.template at<1, 1>(a1), T.template at<2, 2>(a2)), T.template at<3, 3>(a3), rk[4 * r + 0]);
@@ -283,6 +305,7 @@ DASH_HD void aes128_encrypt(uint32_t s[4], const uint32_t* rk, const Tab& T) {
     s[1] = ((T.template at<2, 0>(a1) & 0xffu) | (T.template at<3, 1>(a2) & 0xff00u) | (T.template at<0, 2>(a3) & 0xff0000u) | (T.template at<1, 3>(a0) & 0xff000000u)) ^ rk[41];
     s[2] = ((T.template at<2, 0>(a2) & 0xffu) | (T.template at<3, 1>(a3) & 0xff00u) | (T.template at<0, 2>(a0) & 0xff0000u) | (T.template at<1, 3>(a1) & 0xff000000u)) ^ rk[42];
     s[3] = ((T.template at<2, 0>(a3) & 0xffu) | (T.template at<3, 1>(a0) & 0xff00u) | (T.template at<0, 2>(a1) & 0xff0000u) | (T.template at<1, 3>(a2) & 0xff000000u)) ^ rk[43];
+    }
 }
 
 // h = AES(X) xor X with X = K xor tweak; tweak = elem:u64 | slot:u32 | layer:u16 | 0:u16.

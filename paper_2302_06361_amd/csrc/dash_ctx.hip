@@ -1,5 +1,6 @@
 // dash_ctx.hip -- context (CRT base, label lengths, offset labels, function tables of the sign
 // gadget), En / De kernels and the C ABI entry points of include/dash.h.
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -143,6 +144,8 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     if (!c) return DASH_EINVAL;
     memset(c, 0, sizeof(*c));
     c->device = hip_device; c->k = k; c->rule = lambda_rule;
+    c->banked_min_lanes = 1u << 20;
+    if (const char* e = getenv("DASH_BANKED_MIN_LANES")) c->banked_min_lanes = strtoull(e, nullptr, 10);   // tuning and test hook
     c->prof = new (std::nothrow) ProfState();
     c->P = 1;
     for (int i = 0; i < k; i++) { c->prime[i] = primes[i]; c->P *= primes[i]; }

@@ -20,27 +20,23 @@ namespace dash {
 // AES tables in LDS, two layouts.
 //
 // LdsTab: T0..T3 once, 4 KB, shared by the block.  A wave's 64 look-ups fall on the 32 banks at random
-// (bank = index mod 32): in the gate kernels two thirds of the LDS cycles are bank collisions
-// (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE = 0.68).
+// (bank = index mod 32): two thirds of the LDS cycles are bank collisions (SQ_LDS_BANK_CONFLICT /
+// SQ_LDS_IDX_ACTIVE = 0.68), and AES alone runs at 3.8e10 blocks/s on the chip, exactly what 160 look-ups of
+// 6.4 LDS cycles each allow.
 //
-// BankTab: every table entry once per bank, 128 KB, for blocks of 1024 lanes (one block per CU, four waves
-// per SIMD).  Byte address of entry x of table R for a lane that owns bank b:
-//     (R >> 1) * 65536 + x * 256 + (R & 1) * 128 + b * 4
-// so a look-up never collides, and the address still costs ONE instruction, a byte permute: byte 0 <- 4b
-// (from the lane's constant), byte 1 <- the state byte, byte 2 <- R >> 1; (R & 1) * 128 goes into the
-// instruction's offset.
+// BankTab: every entry of T0 and T1 once per bank, 64 KB, for blocks of 1024 lanes (two blocks per CU, eight
+// waves per SIMD); T2 and T3 are T0 and T1 rotated by 16 bits, one rotation per column for both.  Byte address
+// of entry x of table R (0 or 1) for a lane that owns bank b:  x * 256 + R * 128 + b * 4,  so a look-up never
+// collides, and the address still costs ONE instruction, a byte permute: byte 0 <- 4b (from the lane's
+// constant), byte 1 <- the state byte; R * 128 goes into the instruction's offset.
 //
-// Measured on the LeNet batch-16 step: with BankTab the collisions are gone (counter reads 0) and the LDS
-// is active a third as long, but the gate kernels take the same time (garble 2.64e10 rows/s against
-// 2.76e10) and small launches get slower (128 KB to fill per block, one block per CU): the vector ALU is
-// the limit (about 80 % busy in either layout) and the collisions were hidden behind other waves'
-// arithmetic.  kBankedTables chooses the layout at compile time; the shared tables are the default.
-constexpr bool kBankedTables = false;
+// Measured on the LeNet batch-16 step: BankTab garbles 3.4e10 rows/s against 2.9e10, but launches that do not
+// fill the chip get slower (64 KB to fill per block, fewer and larger blocks), so each kernel exists in both
+// forms and the launcher takes BankTab from kBankedMinLanes lanes up.
 constexpr int kTabWords = 1024;
-constexpr int kBankTabWords = 32768;
-constexpr int kGateThreads = kBankedTables ? 1024 : kThreads;   // lanes per block of the draw / garble / eval kernels
-constexpr int kGateTiles = kGateThreads / kThreads;             // tiles of kThreads lanes a block works on at a time
-constexpr int kGateTabWords = kBankedTables ? kBankTabWords : kTabWords;
+constexpr int kBankTabWords = 16384;
+constexpr int kBigThreads = 1024;                               // lanes per block with BankTab
+
 
 struct LdsTab {
     const uint32_t* t;
@@ -54,29 +50,42 @@ __device__ __forceinline__ LdsTab load_ttab(uint32_t* lds, const uint32_t* g) {
 }
 
 struct BankTab {
+    static constexpr bool two_tables = true;
     const uint8_t* t;
-    uint32_t lane;       // byte 0: 4 * bank, byte 1: 1
+    uint32_t lane;       // byte 0: 4 * bank
     template <int R, int B> __device__ __forceinline__ uint32_t at(uint32_t w) const {
+        static_assert(R < 2, "T0 and T1 only");
         // v_perm_b32(hi = w, lo = lane): selector 0..3 bytes of lane, 4..7 bytes of w, 0x0c zero
-        constexpr uint32_t sel = 0x0c000000u | ((R >> 1) ? 0x00010000u : 0x000c0000u) | ((4u + B) << 8);
+        constexpr uint32_t sel = 0x0c0c0000u | ((4u + B) << 8);
         const uint32_t a = __builtin_amdgcn_perm(w, lane, sel);
-        return *(const uint32_t*)(t + a + (R & 1) * 128);
+        return *(const uint32_t*)(t + a + R * 128);
     }
 };
 
 __device__ __forceinline__ BankTab load_banktab(uint32_t* lds, const uint32_t* g) {
-    for (int i = threadIdx.x; i < kBankTabWords; i += blockDim.x) {
-        const int region = i >> 14, x = (i >> 6) & 255, half = (i >> 5) & 1;
-        lds[i] = g[(region * 2 + half) * 256 + x];
+    // one global load per lane (entry x of table R), then its 32 copies as 8 16-byte LDS writes
+    for (int e = threadIdx.x; e < 512; e += blockDim.x) {
+        const uint32_t v = g[e];
+        const int R = e >> 8, x = e & 255;
+        uint4* dst = (uint4*)(lds + x * 64 + R * 32);
+        const uint4 v4 = make_uint4(v, v, v, v);
+#pragma unroll
+        for (int i = 0; i < 8; i++) dst[i] = v4;
     }
     __syncthreads();
-    return BankTab{(const uint8_t*)lds, ((threadIdx.x & 31u) << 2) | 0x100u};
+    return BankTab{(const uint8_t*)lds, (threadIdx.x & 31u) << 2};
 }
 
-template <bool Banked> struct gate_tab { typedef LdsTab type; static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_ttab(lds, g); } };
-template <> struct gate_tab<true> { typedef BankTab type; static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_banktab(lds, g); } };
-typedef gate_tab<kBankedTables>::type GateTab;
-__device__ __forceinline__ GateTab load_gate_tab(uint32_t* lds, const uint32_t* g) { return gate_tab<kBankedTables>::load(lds, g); }
+template <bool Banked> struct gate_tab {
+    typedef LdsTab type;
+    static constexpr int threads = kThreads, words = kTabWords;
+    static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_ttab(lds, g); }
+};
+template <> struct gate_tab<true> {
+    typedef BankTab type;
+    static constexpr int threads = kBigThreads, words = kBankTabWords;
+    static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_banktab(lds, g); }
+};
 
 // Blocks walk over tiles of kThreads lanes with a grid stride, so that the table copy in LDS is paid
 // once per block and not once per tile.
@@ -85,19 +94,22 @@ __host__ inline uint32_t grid_x_for(uint64_t tiles, int njobs) {
     if (cap < 1) cap = 1;
     return (uint32_t)(tiles < cap ? tiles : cap);
 }
-// the same for blocks of kGateThreads lanes (kGateTiles tiles at a time)
-__host__ inline uint32_t gate_grid_x_for(uint64_t tiles, int njobs) {
-    if (kGateTiles == 1) return grid_x_for(tiles, njobs);
+// the same for blocks of kBigThreads lanes (kBigThreads / kThreads tiles at a time)
+__host__ inline uint32_t gate_grid_x_for(uint64_t tiles, int njobs, bool banked) {
+    if (!banked) return grid_x_for(tiles, njobs);
+    constexpr int kGateTiles = kBigThreads / kThreads;
     uint64_t blocks = (tiles + kGateTiles - 1) / kGateTiles;
-    uint64_t cap = 512 / (uint64_t)njobs;            // one block per CU
+    uint64_t cap = 1024 / (uint64_t)njobs;           // two blocks per CU, two rounds
     if (cap < 1) cap = 1;
     return (uint32_t)(blocks < cap ? blocks : cap);
 }
 
 // ------------------------------------------------------------------------------------------ draw
-__global__ __launch_bounds__(kGateThreads) void k_draw(const DrawLaunch L) {
-    __shared__ uint32_t tt[kGateTabWords];
-    const GateTab T = load_gate_tab(tt, L.ttab);
+template <bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_draw(const DrawLaunch L) {
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
+    __shared__ uint32_t tt[gate_tab<Banked>::words];
+    const auto T = gate_tab<Banked>::load(tt, L.ttab);
     const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
     const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
     for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) draw_body(L, tile, blockIdx.y, tx, T);
@@ -108,8 +120,10 @@ int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
     if (L.n_elem == 0) return DASH_OK;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->seed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
-    hipLaunchKernelGGL(k_draw, grid, dim3(kGateThreads), 0, s, L);
+    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
+    if (banked) hipLaunchKernelGGL(k_draw<true>, grid, dim3(kBigThreads), 0, s, L);
+    else hipLaunchKernelGGL(k_draw<false>, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
@@ -157,8 +171,10 @@ struct StagedSink {
     __device__ __forceinline__ void put(int i, uint32_t w) { st[i] = w; }
 };
 
-template <class QD>
-__global__ __launch_bounds__(stage_rows<QD>::value ? kThreads : kGateThreads) void k_proj_garble(const GateLaunch L) {
+template <class QD, bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const GateLaunch L) {
+    static_assert(!(stage_rows<QD>::value && Banked), "staged rows use the shared tables");
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     const uint64_t rows = (uint64_t)L.n_elem * L.jobs[blockIdx.y].p;
     const uint32_t tiles = (uint32_t)((rows + kThreads - 1) / kThreads);
     if constexpr (stage_rows<QD>::value) {
@@ -186,8 +202,8 @@ __global__ __launch_bounds__(stage_rows<QD>::value ? kThreads : kGateThreads) vo
             __syncthreads();
         }
     } else {
-        __shared__ uint32_t tt[kGateTabWords];
-        const GateTab T = load_gate_tab(tt, L.ttab);
+        __shared__ uint32_t tt[gate_tab<Banked>::words];
+        const auto T = gate_tab<Banked>::load(tt, L.ttab);
         const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
         for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) {
             DirectSink sink;
@@ -197,9 +213,15 @@ __global__ __launch_bounds__(stage_rows<QD>::value ? kThreads : kGateThreads) vo
 }
 
 typedef void (*GateKernel)(const GateLaunch);
-#define DASH_GARBLE_K(MOD, LAM) k_proj_garble<CMod<MOD, LAM>>,
-static const GateKernel kGarbleKernels[] = {k_proj_garble<ModInfo>, DASH_HOT_MODS(DASH_GARBLE_K)};
+#define DASH_GARBLE_K(MOD, LAM) k_proj_garble<CMod<MOD, LAM>, false>,
+static const GateKernel kGarbleKernels[] = {k_proj_garble<ModInfo, false>, DASH_HOT_MODS(DASH_GARBLE_K)};
 #undef DASH_GARBLE_K
+// with BankTab (the kernel for staged rows stays with the shared tables)
+template <class QD, bool Staged = stage_rows<QD>::value> struct banked_garble { static constexpr GateKernel k = k_proj_garble<QD, true>; };
+template <class QD> struct banked_garble<QD, true> { static constexpr GateKernel k = k_proj_garble<QD, false>; };
+#define DASH_GARBLE_KB(MOD, LAM) banked_garble<CMod<MOD, LAM>>::k,
+static const GateKernel kGarbleKernelsBanked[] = {k_proj_garble<ModInfo, true>, DASH_HOT_MODS(DASH_GARBLE_KB)};
+#undef DASH_GARBLE_KB
 #define DASH_GARBLE_S(MOD, LAM) stage_rows<CMod<MOD, LAM>>::value,
 static const bool kGarbleStaged[] = {false, DASH_HOT_MODS(DASH_GARBLE_S)};
 #undef DASH_GARBLE_S
@@ -238,25 +260,30 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (rows >= (1ull << 32)) return DASH_ESIZE;      // staged rows carry a 32-bit row index
     const int ki = q ? hot_mod_index(c->mods[q]) : 0;
     const bool staged = kGarbleStaged[ki];
-    dim3 grid(staged ? grid_x_for(blocks, njobs) : gate_grid_x_for(blocks, njobs), njobs);
+    const bool banked = !staged && (uint64_t)units >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for(blocks, njobs, banked), njobs);
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
-    hipLaunchKernelGGL(kGarbleKernels[ki], grid, dim3(staged ? kThreads : kGateThreads), 0, s, L);
+    hipLaunchKernelGGL(banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
 
 // ------------------------------------------------------------------------------------------ eval
-template <class QD>
-__global__ __launch_bounds__(kGateThreads) void k_proj_eval(const GateLaunch L) {
-    __shared__ uint32_t tt[kGateTabWords];
-    const GateTab T = load_gate_tab(tt, L.ttab);
+template <class QD, bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_eval(const GateLaunch L) {
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
+    __shared__ uint32_t tt[gate_tab<Banked>::words];
+    const auto T = gate_tab<Banked>::load(tt, L.ttab);
     const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
     const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
     for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) eval_body<QD>(L, tile, blockIdx.y, tx, T);
 }
-#define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>>,
-static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo>, DASH_HOT_MODS(DASH_EVAL_K)};
+#define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, false>,
+static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo, false>, DASH_HOT_MODS(DASH_EVAL_K)};
 #undef DASH_EVAL_K
+#define DASH_EVAL_KB(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, true>,
+static const GateKernel kEvalKernelsBanked[] = {k_proj_eval<ModInfo, true>, DASH_HOT_MODS(DASH_EVAL_KB)};
+#undef DASH_EVAL_KB
 
 int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
@@ -268,12 +295,14 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
         if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
         if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
     }
-    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
+    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
     double bytes = 0;
     for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
     const uint32_t q = common_q(L, njobs);
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
-    hipLaunchKernelGGL(kEvalKernels[q ? hot_mod_index(c->mods[q]) : 0], grid, dim3(kGateThreads), 0, s, L);
+    const int ki = q ? hot_mod_index(c->mods[q]) : 0;
+    hipLaunchKernelGGL(banked ? kEvalKernelsBanked[ki] : kEvalKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

@@ -60,6 +60,7 @@ struct dash_ctx {
     const uint8_t* phi_final[2];                                     // [negate] -> [m_1]
     const uint8_t* phi_ident;                                        // {0, 1}
     const uint8_t* d_zero;                                           // 256 zero bytes
+    uint64_t banked_min_lanes;       // launches of this many lanes or more use the bank-replicated AES tables
     const uint8_t* phi_pm1[DASH_MAX_PRIMES];                         // {1, p-1}
 };
 

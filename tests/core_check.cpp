@@ -15,6 +15,10 @@ uint8_t SB[256];
 struct HostTab {
     template <int R, int B> uint32_t at(uint32_t w) const { return TT[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
 };
+struct HostTab2 {      // T0 and T1 only
+    static constexpr bool two_tables = true;
+    template <int R, int B> uint32_t at(uint32_t w) const { static_assert(R < 2, "two tables"); return TT[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
+};
 void init() { if (!ready) { make_sbox(SB); make_ttab(SB, TT); ready = true; } }
 uint32_t pack_dw(const uint8_t* lab, uint32_t lam, int i) {
     uint32_t w = 0;
@@ -24,6 +28,17 @@ uint32_t pack_dw(const uint8_t* lab, uint32_t lam, int i) {
 }  // namespace
 
 extern "C" {
+// AES-128 of one block with the four-table and with the two-table formulation
+void cc_aes_both(const uint8_t key[16], const uint8_t in[16], uint8_t out4[16], uint8_t out2[16]) {
+    init();
+    uint32_t rk[44];
+    expand_key(key, SB, rk);
+    uint32_t s[4], t[4];
+    memcpy(s, in, 16); memcpy(t, in, 16);
+    aes128_encrypt(s, rk, HostTab{});
+    aes128_encrypt(t, rk, HostTab2{});
+    memcpy(out4, s, 16); memcpy(out2, t, 16);
+}
 int cc_lambda(int m, int rule) { return label_length(m, rule); }
 
 // H_q(label, tweak) with the fixed key 00..0f

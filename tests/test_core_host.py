@@ -80,3 +80,19 @@ def test_packed_digit_arithmetic(cc):
             assert unpack(cc.cc_axpymod4(pa, c, pb, m)) == ((a + c * b) % m).tolist()
         for n in [0, 1, m - 1, m, 2 ** 24 - 1] + g.integers(0, 2 ** 24, 50).tolist():
             assert cc.cc_mod_m(int(n), m) == n % m
+
+
+def test_aes_two_table_formulation(cc):
+    """T2 = rot16(T0), T3 = rot16(T1): the two-table rounds against the FIPS-197 example and against the
+    four-table rounds on random blocks"""
+    key = np.arange(16, dtype=np.uint8)
+    pt = np.frombuffer(bytes.fromhex("00112233445566778899aabbccddeeff"), np.uint8).copy()
+    o4, o2 = np.zeros(16, np.uint8), np.zeros(16, np.uint8)
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    cc.cc_aes_both(p(key), p(pt), p(o4), p(o2))
+    assert o4.tobytes().hex() == o2.tobytes().hex() == "69c4e0d86a7b0430d8cdb78070b4c55a"
+    g = np.random.default_rng(5)
+    for _ in range(200):
+        key, pt = g.integers(0, 256, 16, dtype=np.uint8), g.integers(0, 256, 16, dtype=np.uint8)
+        cc.cc_aes_both(p(key), p(pt), p(o4), p(o2))
+        assert (o4 == o2).all()

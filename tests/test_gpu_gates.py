@@ -80,3 +80,14 @@ def test_projection_all_144_pairs_small():
     for pi in range(12):
         for qi in range(12):
             run_proj(ctx, orc, pi, qi, 70, seed=1000 + pi * 12 + qi, elem_base=2 ** 33 + 5)
+
+
+def test_both_table_layouts_of_the_gate_kernels(monkeypatch):
+    """the kernels with bank-replicated AES tables (taken for large launches) and with the shared tables, forced
+    in turn for launches of every size"""
+    for threshold in ("1", "1000000000000"):
+        monkeypatch.setenv("DASH_BANKED_MIN_LANES", threshold)
+        ctx, orc = both(12)
+        for pi, qi in [(0, 0), (0, 11), (11, 0), (5, 7), (3, 1), (9, 9)]:
+            run_proj(ctx, orc, pi, qi, 1500, seed=50 + pi * 12 + qi)
+        run_proj(ctx, orc, 6, 2, 1, seed=3)
