@@ -205,9 +205,23 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const
         __shared__ uint32_t tt[gate_tab<Banked>::words];
         const auto T = gate_tab<Banked>::load(tt, L.ttab);
         const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
-        for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) {
-            DirectSink sink;
-            garble_body<QD>(L, tile, blockIdx.y, tx, T, sink);
+        if constexpr (Banked) {
+            // one-dimensional grid: the jobs differ in length (n_elem * p rows), so the blocks share the
+            // concatenation of all jobs' tiles evenly.  job, base and next are the same in all lanes of a wave.
+            auto tiles_of = [&](uint32_t j) { return (uint32_t)(((uint64_t)L.n_elem * L.jobs[j].p + kThreads - 1) / kThreads); };
+            uint32_t total = 0;
+            for (uint32_t j = 0; j < L.njobs; j++) total += tiles_of(j);
+            uint32_t job = 0, base = 0, next = tiles_of(0);
+            for (uint32_t t = blockIdx.x * kGateTiles + sub; t < total; t += gridDim.x * kGateTiles) {
+                while (t >= next) { job++; base = next; next += tiles_of(job); }
+                DirectSink sink;
+                garble_body<QD>(L, t - base, __builtin_amdgcn_readfirstlane(job), tx, T, sink);
+            }
+        } else {
+            for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) {
+                DirectSink sink;
+                garble_body<QD>(L, tile, blockIdx.y, tx, T, sink);
+            }
         }
     }
 }
@@ -261,7 +275,14 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     const int ki = q ? hot_mod_index(c->mods[q]) : 0;
     const bool staged = kGarbleStaged[ki];
     const bool banked = !staged && (uint64_t)units >= c->banked_min_lanes;
+    L.njobs = (uint32_t)njobs;
     dim3 grid(gate_grid_x_for(blocks, njobs, banked), njobs);
+    if (banked) {       // one-dimensional: all jobs' tiles, 1024 lanes (4 tiles) per block at a time, two blocks per CU
+        uint64_t tiles = 0;
+        for (int j = 0; j < njobs; j++) tiles += ((uint64_t)L.n_elem * L.jobs[j].p + kThreads - 1) / kThreads;
+        const uint64_t nb = (tiles + 3) / 4;
+        grid = dim3((uint32_t)(nb < 512 ? nb : 512));
+    }
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
     hipLaunchKernelGGL(banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());

@@ -55,6 +55,8 @@ struct GateLaunch {
     uint64_t elem_base;
     uint32_t layer;
     uint32_t n_elem;
+    uint32_t njobs;             // set by the launcher
+    uint32_t pad_;
     GateJob jobs[kMaxJobs];
 };
 
