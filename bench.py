@@ -17,15 +17,18 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
-# 32-bit integer vector issue rate: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
-ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# vector issue rate of the simple 32-bit integer instructions (and, xor, add, shift right, three-input bit operation):
+# 256 compute units x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-instructions/s, the same unit count that gives the
+# published 157.3 TFLOP/s of fp32 FMA.  (Measured with a loop of independent v_add_u32: 70.7 T/s.  Shift left, byte
+# permute, three-operand forms and all multiplies issue at half of that.)
+ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 # Figures taken from the rocprofv3 --pmc runs of this same command (profiles/k_proj_garble_lenet_b16_pmc.txt):
 # vector instructions per ciphertext row of k_proj_garble / per gate of the evaluator's gate kernels, averaged over
 # the launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per row (FETCH_SIZE,
 # WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up: 2.0 and 1.0).
-PMC = dict(garble_valu_per_row=746.7, eval_valu_per_gate=728.7,
-           garble_fetch_bytes_per_row=5.42, garble_write_bytes_per_row=26.70)
+PMC = dict(garble_valu_per_row=804.5, eval_valu_per_gate=744.7,
+           garble_fetch_bytes_per_row=6.33, garble_write_bytes_per_row=25.97)
 
 
 def gate_counts(net, k, n_digits):
@@ -344,7 +347,7 @@ def main():
     kg, ke, kl = (kernel_line(prof[n_], a.steps) for n_ in ("garble", "eval", "linear"))
     valu = PMC["garble_valu_per_row"]
     roofline = dict(
-        kernel="k_proj_garble", bound="alu", unit="Tlane-op/s (32-bit integer vector operations)", peak=ALU_PEAK_TOPS,
+        kernel="k_proj_garble", bound="alu", unit="Tlane-instr/s (32-bit integer vector instructions)", peak=ALU_PEAK_TOPS,
         achieved=kg["units_per_s"] * valu / 1e12 if valu else None,
         avg_launch_ms=kg["avg_launch_ms"], launches_per_step=kg["launches_per_step"],
         rows_per_launch=kg["units_per_launch"], rows_per_s=kg["units_per_s"], lane_ops_per_row=valu,

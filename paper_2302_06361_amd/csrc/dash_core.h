@@ -91,7 +91,10 @@ template <uint32_t MOD, uint32_t LAM> struct cmod_m<CMod<MOD, LAM>> { static con
 struct U128 { uint32_t w[4]; };
 
 DASH_HD uint32_t mulhi(uint32_t a, uint32_t b) { return (uint32_t)(((uint64_t)a * b) >> 32); }
-// 24-bit multiply (both operands below 2^24, product below 2^32): full rate on the vector ALU
+// 24-bit multiply (both operands below 2^24, product below 2^32).
+// Measured issue cost of a wave64 instruction on this chip, in cycles per SIMD: and / or / xor / add / sub / shift right /
+// three-input bit operation 2; shift left, byte permute, sub-dword selects, three-operand integer forms, 24-bit and 32-bit
+// multiplies (low and high half alike), 64-bit multiply-add, byte dot product 4.
 DASH_HD uint32_t mul24(uint32_t a, uint32_t b) {
 #if defined(__HIP_DEVICE_COMPILE__)
     return __umul24(a, b);
@@ -123,7 +126,7 @@ template <class MI> DASH_HD uint32_t mod_m(uint32_t n, const MI& M) { return n -
 DASH_HD uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xffu; }
 
 // 0xff in every byte of x whose top bit is set, 0x00 elsewhere (shifts and subtractions only: a
-// multiplication by 255 would run at a quarter of the rate)
+// multiplication by 255 costs twice an addition)
 DASH_HD uint32_t ge_mask(uint32_t x) {
     uint32_t hi = x & 0x80808080u;
     return (hi - (hi >> 7)) | hi;
@@ -367,7 +370,7 @@ DASH_HD uint32_t take_superdigit(U128& x, const MI& M, uint32_t bits) {
 // Compile-time descriptions: the gd digits of a super-digit S < m^G are split by halving, S = hi * m^G1 + lo,
 // so that all but the first division work on numbers below 2^15, where floor(n / D) = (n * M) >> s with a
 // 24-bit multiplication (M = ceil(2^s / D), s = bits(n) + ceil(log2 D): n * (M D - 2^s) < 2^s, so the result is
-// exact, and n * M < 2^32).  A 32-bit multiply-high runs at a quarter of that rate.
+// exact, and n * M < 2^32).  The halving also shortens the chain of dependent divisions from G to log2 G.
 template <class MI, int G>
 DASH_HD void split_digits(uint32_t S, uint32_t* d) {
     if constexpr (G == 1) {
