@@ -24,6 +24,7 @@
 // 4 x 4 MFMA 32x32x32 per 32 of K, accumulators 256 registers per lane (so one wave per SIMD).  MFMA s
 // (0..3) of a wave covers digit 4g+s of the 32 (group, g) pairs that its lanes stand for, so that after the
 // last K-step a lane holds, for its pair, the four digits of one output dword for 64 output features.
+// (A second shape, 128 x 512 with 8 waves of 64 x 128 and two waves per SIMD, serves layers with few outputs.)
 //
 // Pipeline.  With one wave per SIMD nothing but the wave's own instruction order hides latency: global
 // data is fetched two K-steps ahead into one of two register sets, transposed and written to LDS one step
@@ -32,6 +33,7 @@
 // case: 1.38 ms, 35 % of the 5.0 POP/s int8 peak (a loop of nothing but MFMAs reaches 4.2 - 4.7 POP/s on
 // this chip); per K-step 2200 cycles against 1150 for the MFMAs alone, plus 0.25 ms of prologue and
 // epilogue that one block per CU cannot overlap with another block's MFMAs.
+#include <stdlib.h>
 #include <string.h>
 
 #include <type_traits>
@@ -43,8 +45,18 @@ namespace dash {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 256;        // output features per block
-constexpr int kBG = 16;         // groups per block (256 columns)
+// A block is NWM x NWN waves, a wave tile (32 IFR) rows x 8 groups (128 columns).
+template <int NWM_, int NWN_, int IFR_>
+struct Tile {
+    static constexpr int NWM = NWM_, NWN = NWN_, IFR = IFR_;
+    static constexpr int BM = NWM * 32 * IFR;      // output features per block
+    static constexpr int BG = NWN * 8;             // groups per block (16 columns each)
+    static constexpr int T = 64 * NWM * NWN;       // lanes per block
+    static constexpr int AP = BM * 4 / T;          // 16-byte pieces of the weight tile per lane and stage
+    static_assert(BG * 16 == T && AP >= 1 && AP <= 4, "loader roles");
+};
+typedef Tile<2, 2, 4> TileBig;      // 256 x 256 block tile, 4 waves of 128 x 128: one wave per SIMD
+typedef Tile<2, 4, 2> TileWide;     // 128 x 512 block tile, 8 waves of 64 x 128: two waves per SIMD
 constexpr int kKT = 64;         // K per stage
 constexpr int kRow = 80;        // bytes per LDS row (64 + 16 pad)
 
@@ -81,7 +93,9 @@ struct GemmArgs {
 // (Layers with fewer than 4 row blocks use 2 x 16 or 1 x 32.)
 constexpr int kStBlocks = 32, kXcds = 8;
 
-__global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
+template <class TL>
+__global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
+    constexpr int kBM = TL::BM, kBG = TL::BG, IFR = TL::IFR, AP = TL::AP, T = TL::T;
     const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
     const int st = (seq / kStBlocks) * kXcds + xcd, within = seq % kStBlocks;
     if (st >= A.st_total) return;
@@ -102,14 +116,14 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     const uint32_t prime = P.p, mmagic = P.mmagic, pow12 = P.pow12;
     const bool small_acc = A.small_acc != 0;
     const int32_t* const bias = A.bias;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / TL::NWN, wn = wave % TL::NWN;
     const int row0 = by * kBM, grp0 = bx * kBG;
 
     __shared__ __attribute__((aligned(16))) uint8_t As[2][kBM * kRow];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][4 * kBG * 4 * kRow];
 
     // ---- loader roles ----
-    // A: 1024 16-byte pieces per stage, 4 per thread: piece id -> (row = id / 4, part = id % 4)
+    // A: 4 kBM 16-byte pieces per stage, AP per thread: piece id -> (row = id / 4, part = id % 4)
     // B: thread -> (group G = tid / 16, k quad kq = tid % 16): rows k = 4kq..4kq+3 of X_G, 16 bytes each
     const int bG = tid >> 4, bkq = tid & 15;
     const int gglob = grp0 + bG;
@@ -134,9 +148,9 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // (a plain vector: HIP's uint4 is a struct and was left in scratch memory)
     struct Regs { u32x4 a0, a1, a2, a3, b0, b1, b2, b3; };
     Regs Rx, Ry;
-    const int arow = tid >> 2, apart = tid & 3;         // A piece i of this thread: row arow + 64 i, 16-byte part apart
+    const int arow = tid >> 2, apart = tid & 3;         // A piece i of this thread: row arow + (T / 4) i, 16-byte part apart
     auto a_src = [&](int i, int k0) __attribute__((always_inline)) {
-        const int row = row0 + arow + 64 * i;
+        const int row = row0 + arow + (T / 4) * i;
         return (const u32x4*)(wbase + (int64_t)(row < mpad ? row : mpad - 1) * kpad + k0 + apart * 16);   // rows past M are never stored
     };
     auto b_src = [&](int kk, int k0) __attribute__((always_inline)) {
@@ -154,7 +168,9 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
         return (const u32x4*)(ok ? src : zero);
     };
     auto load_stage = [&](int k0, Regs& R) __attribute__((always_inline)) {
-        R.a0 = *a_src(0, k0); R.a1 = *a_src(1, k0); R.a2 = *a_src(2, k0); R.a3 = *a_src(3, k0);
+        R.a0 = *a_src(0, k0);
+        if constexpr (AP > 1) R.a1 = *a_src(1, k0);
+        if constexpr (AP > 2) { R.a2 = *a_src(2, k0); R.a3 = *a_src(3, k0); }
         if (conv) {
             const u32x4* src = conv_src(k0);
             R.b0 = src[0]; R.b1 = src[1]; R.b2 = src[2]; R.b3 = src[3];
@@ -164,7 +180,9 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     };
     auto store_stage = [&](int buf, const Regs& R) __attribute__((always_inline)) {
         uint8_t* ad = As[buf] + arow * kRow + apart * 16;
-        *(u32x4*)(ad) = R.a0; *(u32x4*)(ad + 64 * kRow) = R.a1; *(u32x4*)(ad + 128 * kRow) = R.a2; *(u32x4*)(ad + 192 * kRow) = R.a3;
+        *(u32x4*)(ad) = R.a0;
+        if constexpr (AP > 1) *(u32x4*)(ad + (T / 4) * kRow) = R.a1;
+        if constexpr (AP > 2) { *(u32x4*)(ad + 2 * (T / 4) * kRow) = R.a2; *(u32x4*)(ad + 3 * (T / 4) * kRow) = R.a3; }
         auto put = [&](int g, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) __attribute__((always_inline)) {      // dword g of rows k..k+3
             // v_perm_b32(hi, lo, sel): byte k of the result = byte sel.k of the 8 bytes {hi:lo} (lo = bytes 0..3)
             const uint32_t ab02 = __builtin_amdgcn_perm(w1, w0, 0x06020400u), ab13 = __builtin_amdgcn_perm(w1, w0, 0x07030501u);
@@ -181,9 +199,9 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
         put(3, R.b0.w, R.b1.w, R.b2.w, R.b3.w);
     };
 
-    v16i acc[4][4];
+    v16i acc[IFR][4];
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < IFR; i++)
 #pragma unroll
         for (int s = 0; s < 4; s++) acc[i][s] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
@@ -193,7 +211,7 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     __syncthreads();
     if (nk > 1) load_stage(kKT, Ry);
     const int n = lane & 31, kh = lane >> 5;
-    const int fa = (wm * 128 + n) * kRow + kh * 16;                              // + rb*32*kRow + ks*32
+    const int fa = (wm * 32 * IFR + n) * kRow + kh * 16;                         // + i*32*kRow + ks*32
     const int fb = (((wn * 8 + (n >> 2)) * 4) + (n & 3)) * kRow + kh * 16;       // + s*kBG*4*kRow + ks*32
     // Software pipeline inside the wave (one wave per SIMD: nothing else hides latency).  Per stage:
     //   global loads of the stage after next
@@ -201,16 +219,16 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     //   16 MFMAs of the second K half  | the next stage's data: byte transposes and LDS writes
     // then the barrier and the fragment reads of the first half of the next stage.
     // sched_group_barrier(mask, n, id): 0x8 MFMA, 0x100 LDS read, 0x200 LDS write, 0x2 vector ALU.
-    v4i a0[4], b0[4], a1[4], b1[4];
-    auto read_frags = [&](int buf, int ks, v4i (&a)[4], v4i (&b)[4]) __attribute__((always_inline)) {
+    v4i a0[IFR], b0[4], a1[IFR], b1[4];
+    auto read_frags = [&](int buf, int ks, v4i (&a)[IFR], v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; i++) a[i] = *(const v4i*)(As[buf] + fa + i * 32 * kRow + ks * 32);
+        for (int i = 0; i < IFR; i++) a[i] = *(const v4i*)(As[buf] + fa + i * 32 * kRow + ks * 32);
 #pragma unroll
         for (int q = 0; q < 4; q++) b[q] = *(const v4i*)(Bs[buf] + fb + q * kBG * 4 * kRow + ks * 32);
     };
-    auto mfma16 = [&](const v4i (&a)[4], const v4i (&b)[4]) __attribute__((always_inline)) {
+    auto mfma16 = [&](const v4i (&a)[IFR], const v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < IFR; i++)
 #pragma unroll
             for (int q = 0; q < 4; q++) acc[i][q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[q], acc[i][q], 0, 0, 0);
     };
@@ -222,18 +240,18 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
         read_frags(cur, 1, a1, b1);
         mfma16(a0, b0);
 #pragma unroll
-        for (int t = 0; t < 8; t++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        for (int t = 0; t < IFR + 4; t++) {      // IFR + 4 fragment reads among 4 IFR MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x008, IFR == 4 ? 2 : 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         store_stage(cur ^ 1, Rs);
         mfma16(a1, b1);
 #pragma unroll
-        for (int t = 0; t < 16; t++) {
+        for (int t = 0; t < 4 * IFR; t++) {      // 32 byte permutes and 8 + AP LDS writes among 4 IFR MFMAs
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, IFR == 4 ? 3 : 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, IFR == 4 ? 1 : 2, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -259,10 +277,10 @@ __global__ __launch_bounds__(256) void k_dense_mfma(const GemmArgs A) {
     auto red1 = [&](uint32_t v) -> uint32_t { return v - mul24(mulhi(v, mmagic), prime); };      // v < 2^24
     auto emit = [&](auto small) {
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < IFR; i++)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int j = row0 + wm * 128 + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                const int j = row0 + wm * 32 * IFR + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
                 if (j >= M) continue;
                 uint32_t d[4];
 #pragma unroll
@@ -327,22 +345,32 @@ int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         bytes += (double)batch * (M + K) * Mi.lam + (double)M * K;
     }
     (void)max_nchunk;
-    const int gy = (M + kBM - 1) / kBM;
-    A.sty = gy >= 4 ? 4 : gy >= 2 ? 2 : 1;
-    const int kStX = kStBlocks / A.sty;
-    A.gy4 = (gy + A.sty - 1) / A.sty;
-    int64_t st_total = 0;
-    for (int i = 0; i < c->k; i++) {
-        A.st_first[i] = (int)st_total;
-        const int64_t gb = ((int64_t)A.pr[i].nchunk * batch + kBG - 1) / kBG;
-        st_total += (gb + kStX - 1) / kStX * A.gy4;
-        if (st_total > (1 << 24)) return DASH_ESIZE;
-    }
-    A.st_first[c->k] = (int)st_total;
-    A.st_total = (int)st_total;
-    dim3 grid((uint32_t)((st_total + kXcds - 1) / kXcds * kXcds * kStBlocks));
-    ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
-    hipLaunchKernelGGL(k_dense_mfma, grid, dim3(256), 0, s, A);
+    // tile shape.  Measured on 4096 x 4096, batch 128, 12 primes: 256 x 256 (one wave per SIMD) 1.30 ms, 128 x 512
+    // (two waves per SIMD) 1.41 ms; the latter wastes half as many rows when there are at most 128 outputs.
+    const char* force = getenv("DASH_GEMM_TILE");       // tuning and test hook: "wide" or "big"
+    const bool wide = force ? force[0] == 'w' : M <= 128;
+    auto launch = [&](auto tl) -> int {
+        typedef decltype(tl) TL;
+        const int gy = (M + TL::BM - 1) / TL::BM;
+        A.sty = gy >= 4 ? 4 : gy >= 2 ? 2 : 1;
+        const int kStX = kStBlocks / A.sty;
+        A.gy4 = (gy + A.sty - 1) / A.sty;
+        int64_t st_total = 0;
+        for (int i = 0; i < c->k; i++) {
+            A.st_first[i] = (int)st_total;
+            const int64_t gb = ((int64_t)A.pr[i].nchunk * batch + TL::BG - 1) / TL::BG;
+            st_total += (gb + kStX - 1) / kStX * A.gy4;
+            if (st_total > (1 << 24)) return DASH_ESIZE;
+        }
+        A.st_first[c->k] = (int)st_total;
+        A.st_total = (int)st_total;
+        dim3 grid((uint32_t)((st_total + kXcds - 1) / kXcds * kXcds * kStBlocks));
+        ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
+        hipLaunchKernelGGL(k_dense_mfma<TL>, grid, dim3(TL::T), 0, s, A);
+        return DASH_OK;
+    };
+    const int st = wide ? launch(TileWide{}) : launch(TileBig{});
+    if (st) return st;
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

@@ -95,3 +95,12 @@ def test_conv_mfma_shapes():
     run_linear(8, 1, 5, 5, 64, 64, 1, 1, 0, -8, 7, True, 33, garble=False)
     run_linear(12, 1, 16, 16, 12, 48, 3, 1, 1, -16, 15, False, 34)
     run_linear(5, 2, 7, 7, 20, 33, 3, 1, 0, -3, 3, True, 35)
+
+
+def test_dense_mfma_both_tile_shapes(monkeypatch):
+    """the 256 x 256 and the 128 x 512 block tiles of the MFMA kernel, forced in turn"""
+    for shape in ("big", "wide"):
+        monkeypatch.setenv("DASH_GEMM_TILE", shape)
+        run_linear(12, 5, 1, 1, 500, 300, 1, 1, 0, -64, 63, True, 41)
+        run_linear(8, 40, 1, 1, 192, 100, 1, 1, 0, -8, 7, False, 42, garble=False)
+        run_linear(12, 2, 9, 7, 8, 40, 3, 2, 1, -16, 15, True, 43)
