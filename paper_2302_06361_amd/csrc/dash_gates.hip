@@ -4,105 +4,16 @@
 //   k_affine      : free gates: out = sum_t coef_t * term_t mod m   (Sec. Arithmetic Garbled Circuits)
 //   k_proj_garble : one lane per ciphertext row: hash the label of value a, add the payload, store
 //                   the row at the position its colour names            (projection gates, point-and-permute)
-//   k_proj_eval   : one lane per gate: hash the active label, fetch the row its colour names, subtract
-//   k_hg_finish   : evaluator side of the mixed-modulus half gate       (Appendix)
+//   (the evaluator's kernels are in dash_gates_eval.hip)
 //
 // A launch carries up to 16 homogeneous gate batches ("jobs", blockIdx.y); every lane of a block
 // works on the same pair of moduli, so all modulus-dependent control flow is wave-uniform.  The
 // moduli that carry nearly all of the work (the CRT primes and the accumulation moduli of the
 // default digit sets, under the ceil label-length rule) run through compile-time descriptions; any
 // other modulus takes the same code with run-time constants.
-#include "dash_bodies.h"
-#include "dash_internal.h"
+#include "dash_tabs.h"
 
 namespace dash {
-
-// AES tables in LDS, two layouts.
-//
-// LdsTab: T0..T3 once, 4 KB, shared by the block.  A wave's 64 look-ups fall on the 32 banks at random
-// (bank = index mod 32): two thirds of the LDS cycles are bank collisions (SQ_LDS_BANK_CONFLICT /
-// SQ_LDS_IDX_ACTIVE = 0.68), and AES alone runs at 3.8e10 blocks/s on the chip, exactly what 160 look-ups of
-// 6.4 LDS cycles each allow.
-//
-// BankTab: every entry of T0 and T1 once per bank, 64 KB, for blocks of 1024 lanes (two blocks per CU, eight
-// waves per SIMD); T2 and T3 are T0 and T1 rotated by 16 bits, one rotation per column for both.  Byte address
-// of entry x of table R (0 or 1) for a lane that owns bank b:  x * 256 + R * 128 + b * 4,  so a look-up never
-// collides, and the address still costs ONE instruction, a byte permute: byte 0 <- 4b (from the lane's
-// constant), byte 1 <- the state byte; R * 128 goes into the instruction's offset.
-//
-// Measured on the LeNet batch-16 step: BankTab garbles 3.4e10 rows/s against 2.9e10, but launches that do not
-// fill the chip get slower (64 KB to fill per block, fewer and larger blocks), so each kernel exists in both
-// forms and the launcher takes BankTab from kBankedMinLanes lanes up.
-constexpr int kTabWords = 1024;
-constexpr int kBankTabWords = 16384;
-constexpr int kBigThreads = 1024;                               // lanes per block with BankTab
-
-
-struct LdsTab {
-    const uint32_t* t;
-    template <int R, int B> __device__ __forceinline__ uint32_t at(uint32_t w) const { return t[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
-};
-
-__device__ __forceinline__ LdsTab load_ttab(uint32_t* lds, const uint32_t* g) {
-    for (int i = threadIdx.x; i < kTabWords; i += blockDim.x) lds[i] = g[i];
-    __syncthreads();
-    return LdsTab{lds};
-}
-
-struct BankTab {
-    static constexpr bool two_tables = true;
-    const uint8_t* t;
-    uint32_t lane;       // byte 0: 4 * bank
-    template <int R, int B> __device__ __forceinline__ uint32_t at(uint32_t w) const {
-        static_assert(R < 2, "T0 and T1 only");
-        // v_perm_b32(hi = w, lo = lane): selector 0..3 bytes of lane, 4..7 bytes of w, 0x0c zero
-        constexpr uint32_t sel = 0x0c0c0000u | ((4u + B) << 8);
-        const uint32_t a = __builtin_amdgcn_perm(w, lane, sel);
-        return *(const uint32_t*)(t + a + R * 128);
-    }
-};
-
-__device__ __forceinline__ BankTab load_banktab(uint32_t* lds, const uint32_t* g) {
-    // one global load per lane (entry x of table R), then its 32 copies as 8 16-byte LDS writes
-    for (int e = threadIdx.x; e < 512; e += blockDim.x) {
-        const uint32_t v = g[e];
-        const int R = e >> 8, x = e & 255;
-        uint4* dst = (uint4*)(lds + x * 64 + R * 32);
-        const uint4 v4 = make_uint4(v, v, v, v);
-#pragma unroll
-        for (int i = 0; i < 8; i++) dst[i] = v4;
-    }
-    __syncthreads();
-    return BankTab{(const uint8_t*)lds, (threadIdx.x & 31u) << 2};
-}
-
-template <bool Banked> struct gate_tab {
-    typedef LdsTab type;
-    static constexpr int threads = kThreads, words = kTabWords;
-    static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_ttab(lds, g); }
-};
-template <> struct gate_tab<true> {
-    typedef BankTab type;
-    static constexpr int threads = kBigThreads, words = kBankTabWords;
-    static __device__ __forceinline__ type load(uint32_t* lds, const uint32_t* g) { return load_banktab(lds, g); }
-};
-
-// Blocks walk over tiles of kThreads lanes with a grid stride, so that the table copy in LDS is paid
-// once per block and not once per tile.
-__host__ inline uint32_t grid_x_for(uint64_t tiles, int njobs) {
-    uint64_t cap = 2560 / (uint64_t)njobs;           // about two resident rounds of blocks on 256 CUs
-    if (cap < 1) cap = 1;
-    return (uint32_t)(tiles < cap ? tiles : cap);
-}
-// the same for blocks of kBigThreads lanes (kBigThreads / kThreads tiles at a time)
-__host__ inline uint32_t gate_grid_x_for(uint64_t tiles, int njobs, bool banked) {
-    if (!banked) return grid_x_for(tiles, njobs);
-    constexpr int kGateTiles = kBigThreads / kThreads;
-    uint64_t blocks = (tiles + kGateTiles - 1) / kGateTiles;
-    uint64_t cap = 1024 / (uint64_t)njobs;           // two blocks per CU, two rounds
-    if (cap < 1) cap = 1;
-    return (uint32_t)(blocks < cap ? blocks : cap);
-}
 
 // ------------------------------------------------------------------------------------------ draw
 template <bool Banked>
@@ -226,7 +137,6 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const
     }
 }
 
-typedef void (*GateKernel)(const GateLaunch);
 #define DASH_GARBLE_K(MOD, LAM) k_proj_garble<CMod<MOD, LAM>, false>,
 static const GateKernel kGarbleKernels[] = {k_proj_garble<ModInfo, false>, DASH_HOT_MODS(DASH_GARBLE_K)};
 #undef DASH_GARBLE_K
@@ -240,11 +150,6 @@ static const GateKernel kGarbleKernelsBanked[] = {k_proj_garble<ModInfo, true>, 
 static const bool kGarbleStaged[] = {false, DASH_HOT_MODS(DASH_GARBLE_S)};
 #undef DASH_GARBLE_S
 
-// every job of a gate launch must have the same output modulus; returns it (0 if they differ)
-static uint32_t common_q(const GateLaunch& L, int njobs) {
-    for (int j = 1; j < njobs; j++) if (L.jobs[j].q != L.jobs[0].q) return 0;
-    return L.jobs[0].q;
-}
 
 int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
@@ -285,109 +190,6 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     }
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
     hipLaunchKernelGGL(banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
-    DASH_HIP(hipGetLastError());
-    return DASH_OK;
-}
-
-// ------------------------------------------------------------------------------------------ eval
-template <class QD, bool Banked>
-__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_eval(const GateLaunch L) {
-    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
-    __shared__ uint32_t tt[gate_tab<Banked>::words];
-    const auto T = gate_tab<Banked>::load(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
-    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) eval_body<QD>(L, tile, blockIdx.y, tx, T);
-}
-#define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, false>,
-static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo, false>, DASH_HOT_MODS(DASH_EVAL_K)};
-#undef DASH_EVAL_K
-#define DASH_EVAL_KB(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, true>,
-static const GateKernel kEvalKernelsBanked[] = {k_proj_eval<ModInfo, true>, DASH_HOT_MODS(DASH_EVAL_KB)};
-#undef DASH_EVAL_KB
-
-int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
-    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
-    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    for (int j = 0; j < njobs; j++) {
-        const GateJob& J = L.jobs[j];
-        if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
-        if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
-    }
-    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
-    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
-    double bytes = 0;
-    for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
-    const uint32_t q = common_q(L, njobs);
-    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
-    const int ki = q ? hot_mod_index(c->mods[q]) : 0;
-    hipLaunchKernelGGL(banked ? kEvalKernelsBanked[ki] : kEvalKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
-    DASH_HIP(hipGetLastError());
-    return DASH_OK;
-}
-
-// ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
-// One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
-// whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
-// other set takes the body with run-time constants.
-template <class MC, class M1>
-__global__ __launch_bounds__(kThreads) void k_chain_eval(const ChainLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1>(L, tile, threadIdx.x, T);
-}
-__global__ __launch_bounds__(kThreads) void k_chain_eval_generic(const ChainLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_generic_body(L, tile, threadIdx.x, T);
-}
-
-int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
-    if (L.n < 2 || L.n > (uint32_t)kMaxChain) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
-    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    bool uniform = true;
-    double bytes = 0;
-    for (uint32_t j = 1; j <= L.n; j++) {
-        if (L.m[j] < 2 || L.m[j] > 255 || !L.table[j] || !L.sum[j].p || (j < L.n && !L.carry[j].p)) return DASH_EINVAL;
-        if (j >= 3 && L.m[j] != L.m[2]) uniform = false;
-        bytes += (double)L.n_elem * (c->mods[L.m[j]].lam + (j >= 2 ? c->mods[L.m[j - 1]].lam : 128));
-    }
-    if ((uint64_t)L.n_elem * 255 >= (1ull << 32)) return DASH_ESIZE;
-    const ModInfo &Mc = c->mods[L.m[2]], &M1 = c->mods[L.m[1]];
-    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
-    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
-    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
-    if (uniform && is(Mc, 96, 20) && is(M1, 26, 28))
-        hipLaunchKernelGGL((k_chain_eval<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, L);
-    else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24))
-        hipLaunchKernelGGL((k_chain_eval<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
-    else
-        hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
-    DASH_HIP(hipGetLastError());
-    return DASH_OK;
-}
-
-// ----------------------------------------------------------------------------- half gate, evaluator
-__global__ __launch_bounds__(kThreads) void k_hg_finish(const HgLaunch L) {
-    __shared__ uint32_t tt[kTabWords];
-    const LdsTab T = load_ttab(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) hg_finish_body(L, tile, blockIdx.y, threadIdx.x, T);
-}
-
-int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s) {
-    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
-    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
-    hipLaunchKernelGGL(k_hg_finish, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

@@ -1,0 +1,116 @@
+// dash_gates_eval.hip -- the evaluator's gate kernels over LabelTensors.
+//
+//   k_proj_eval   : one lane per gate: hash the active label, fetch the row its colour names, subtract
+//                   (Sec. Arithmetic Garbled Circuits, projection gates)
+//   k_chain_eval  : the n dependent gates of the mixed-radix addition of a sign gadget, one lane per element
+//   k_hg_finish   : evaluator side of the mixed-modulus half gate       (Appendix)
+//
+// Jobs, table layouts and compile-time moduli as in dash_gates.hip.
+#include "dash_tabs.h"
+
+namespace dash {
+
+// ------------------------------------------------------------------------------------------ eval
+template <class QD, bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_eval(const GateLaunch L) {
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
+    __shared__ uint32_t tt[gate_tab<Banked>::words];
+    const auto T = gate_tab<Banked>::load(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) eval_body<QD>(L, tile, blockIdx.y, tx, T);
+}
+#define DASH_EVAL_K(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, false>,
+static const GateKernel kEvalKernels[] = {k_proj_eval<ModInfo, false>, DASH_HOT_MODS(DASH_EVAL_K)};
+#undef DASH_EVAL_K
+#define DASH_EVAL_KB(MOD, LAM) k_proj_eval<CMod<MOD, LAM>, true>,
+static const GateKernel kEvalKernelsBanked[] = {k_proj_eval<ModInfo, true>, DASH_HOT_MODS(DASH_EVAL_KB)};
+#undef DASH_EVAL_KB
+
+int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
+    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    for (int j = 0; j < njobs; j++) {
+        const GateJob& J = L.jobs[j];
+        if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
+        if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
+    }
+    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
+    double bytes = 0;
+    for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
+    const uint32_t q = common_q(L, njobs);
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
+    const int ki = q ? hot_mod_index(c->mods[q]) : 0;
+    hipLaunchKernelGGL(banked ? kEvalKernelsBanked[ki] : kEvalKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+// ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
+// One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
+// whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
+// other set takes the body with run-time constants.
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_chain_eval(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1>(L, tile, threadIdx.x, T);
+}
+__global__ __launch_bounds__(kThreads) void k_chain_eval_generic(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_generic_body(L, tile, threadIdx.x, T);
+}
+
+int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
+    if (L.n < 2 || L.n > (uint32_t)kMaxChain) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    bool uniform = true;
+    double bytes = 0;
+    for (uint32_t j = 1; j <= L.n; j++) {
+        if (L.m[j] < 2 || L.m[j] > 255 || !L.table[j] || !L.sum[j].p || (j < L.n && !L.carry[j].p)) return DASH_EINVAL;
+        if (j >= 3 && L.m[j] != L.m[2]) uniform = false;
+        bytes += (double)L.n_elem * (c->mods[L.m[j]].lam + (j >= 2 ? c->mods[L.m[j - 1]].lam : 128));
+    }
+    if ((uint64_t)L.n_elem * 255 >= (1ull << 32)) return DASH_ESIZE;
+    const ModInfo &Mc = c->mods[L.m[2]], &M1 = c->mods[L.m[1]];
+    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
+    if (uniform && is(Mc, 96, 20) && is(M1, 26, 28))
+        hipLaunchKernelGGL((k_chain_eval<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, L);
+    else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24))
+        hipLaunchKernelGGL((k_chain_eval<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
+    else
+        hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+// ----------------------------------------------------------------------------- half gate, evaluator
+__global__ __launch_bounds__(kThreads) void k_hg_finish(const HgLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) hg_finish_body(L, tile, blockIdx.y, threadIdx.x, T);
+}
+
+int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s) {
+    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
+    hipLaunchKernelGGL(k_hg_finish, grid, dim3(kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+}  // namespace dash
