@@ -119,8 +119,13 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / TL::NWN, wn = wave % TL::NWN;
     const int row0 = by * kBM, grp0 = bx * kBG;
 
-    __shared__ __attribute__((aligned(16))) uint8_t As[2][kBM * kRow];
-    __shared__ __attribute__((aligned(16))) uint8_t Bs[2][4 * kBG * 4 * kRow];
+    // one LDS block: two stages of the A tile, two of the B tile; the epilogue reuses it for the output tile
+    constexpr int kAbytes = kBM * kRow, kBbytes = 4 * kBG * 4 * kRow;
+    constexpr int kOutStride = kBM * 16 + 16;                      // bytes per group of the staged output tile (padded)
+    static_assert(kBG * kOutStride <= 2 * (kAbytes + kBbytes), "output tile fits the operand buffers");
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * (kAbytes + kBbytes)];
+    auto As = [&](int b) __attribute__((always_inline)) { return smem + b * kAbytes; };
+    auto Bs = [&](int b) __attribute__((always_inline)) { return smem + 2 * kAbytes + b * kBbytes; };
 
     // ---- loader roles ----
     // A: 4 kBM 16-byte pieces per stage, AP per thread: piece id -> (row = id / 4, part = id % 4)
@@ -179,7 +184,7 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
         }
     };
     auto store_stage = [&](int buf, const Regs& R) __attribute__((always_inline)) {
-        uint8_t* ad = As[buf] + arow * kRow + apart * 16;
+        uint8_t* ad = As(buf) + arow * kRow + apart * 16;
         *(u32x4*)(ad) = R.a0;
         if constexpr (AP > 1) *(u32x4*)(ad + (T / 4) * kRow) = R.a1;
         if constexpr (AP > 2) { *(u32x4*)(ad + 2 * (T / 4) * kRow) = R.a2; *(u32x4*)(ad + 3 * (T / 4) * kRow) = R.a3; }
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
             // v_perm_b32(hi, lo, sel): byte k of the result = byte sel.k of the 8 bytes {hi:lo} (lo = bytes 0..3)
             const uint32_t ab02 = __builtin_amdgcn_perm(w1, w0, 0x06020400u), ab13 = __builtin_amdgcn_perm(w1, w0, 0x07030501u);
             const uint32_t cd02 = __builtin_amdgcn_perm(w3, w2, 0x06020400u), cd13 = __builtin_amdgcn_perm(w3, w2, 0x07030501u);
-            uint8_t* dst = Bs[buf] + ((bG * 4 + g) * kRow) + 4 * bkq;                    // + s * kBG * 4 * kRow: digit 4g+s
+            uint8_t* dst = Bs(buf) + ((bG * 4 + g) * kRow) + 4 * bkq;                    // + s * kBG * 4 * kRow: digit 4g+s
             *(uint32_t*)(dst + 0 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd02, ab02, 0x05040100u);
             *(uint32_t*)(dst + 1 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd13, ab13, 0x05040100u);
             *(uint32_t*)(dst + 2 * kBG * 4 * kRow) = __builtin_amdgcn_perm(cd02, ab02, 0x07060302u);
@@ -222,9 +227,9 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
     v4i a0[IFR], b0[4], a1[IFR], b1[4];
     auto read_frags = [&](int buf, int ks, v4i (&a)[IFR], v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < IFR; i++) a[i] = *(const v4i*)(As[buf] + fa + i * 32 * kRow + ks * 32);
+        for (int i = 0; i < IFR; i++) a[i] = *(const v4i*)(As(buf) + fa + i * 32 * kRow + ks * 32);
 #pragma unroll
-        for (int q = 0; q < 4; q++) b[q] = *(const v4i*)(Bs[buf] + fb + q * kBG * 4 * kRow + ks * 32);
+        for (int q = 0; q < 4; q++) b[q] = *(const v4i*)(Bs(buf) + fb + q * kBG * 4 * kRow + ks * 32);
     };
     auto mfma16 = [&](const v4i (&a)[IFR], const v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
@@ -267,21 +272,23 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
         mfma16(a1, b1);
     }
 
-    // ---- epilogue: reduce mod p, pack the four digits of a dword, store ----
-    const int G = grp0 + wn * 8 + (n >> 2), g = n & 3;
-    if (G >= ngroups) return;
-    const int och = G / A.batch, ob = G - och * A.batch;
-    uint8_t* og = P.out.p + (int64_t)och * P.out.cs + ((int64_t)ob * M) * 16 + 4 * g;
+    // ---- epilogue: reduce mod p, pack the four digits of a dword, stage the output tile in LDS as
+    // [group][row][16 digits] and store it 16 bytes per lane, consecutive lanes consecutive rows (rows of one
+    // group are consecutive 16-byte words in memory) ----
+    __syncthreads();                                    // every wave is done with the operand buffers
+    const int Gl = wn * 8 + (n >> 2), g = n & 3;
     uint32_t one4 = 0;
-    if (bias) one4 = *(const uint32_t*)(P.one + och * 16 + 4 * g);
+    if (bias) {
+        const int G = grp0 + Gl;
+        if (G < ngroups) one4 = *(const uint32_t*)(P.one + (G / A.batch) * 16 + 4 * g);
+    }
     auto red1 = [&](uint32_t v) -> uint32_t { return v - mul24(mulhi(v, mmagic), prime); };      // v < 2^24
     auto emit = [&](auto small) {
 #pragma unroll
         for (int i = 0; i < IFR; i++)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int j = row0 + wm * 32 * IFR + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                if (j >= M) continue;
+                const int jl = wm * 32 * IFR + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
                 uint32_t d[4];
 #pragma unroll
                 for (int s = 0; s < 4; s++) {
@@ -290,15 +297,26 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
                     d[s] = red1(v);
                 }
                 if (bias) {
-                    int32_t bj = bias[j] % (int32_t)prime;
+                    const int j = row0 + jl;
+                    int32_t bj = j < M ? bias[j] % (int32_t)prime : 0;
                     uint32_t bm = (uint32_t)(bj < 0 ? bj + (int32_t)prime : bj);
 #pragma unroll
                     for (int s = 0; s < 4; s++) d[s] = red1(d[s] + mul24(bm, (one4 >> (8 * s)) & 0xffu));
                 }
-                *(uint32_t*)(og + (int64_t)j * 16) = d[0] | (d[1] << 8) | (d[2] << 16) | (d[3] << 24);
+                *(uint32_t*)(smem + Gl * kOutStride + jl * 16 + 4 * g) = d[0] | (d[1] << 8) | (d[2] << 16) | (d[3] << 24);
             }
     };
     if (small_acc) emit(std::true_type{}); else emit(std::false_type{});
+    __syncthreads();
+#pragma unroll 4
+    for (int id = tid; id < kBG * kBM; id += T) {
+        const int gl = id / kBM, jl = id - gl * kBM;
+        const int G = grp0 + gl, j = row0 + jl;
+        if (G < ngroups && j < M) {
+            const int och = G / A.batch, ob = G - och * A.batch;
+            *(u32x4*)(P.out.p + (int64_t)och * P.out.cs + ((int64_t)ob * M + j) * 16) = *(const u32x4*)(smem + gl * kOutStride + jl * 16);
+        }
+    }
 }
 
 // true if the MFMA path should take this dense or convolution layer (large enough to fill tiles; for a
