@@ -189,7 +189,9 @@ def micro_contraction(torch, workloads, reps=5):
                ms=ms, label_mac_per_s=macs / (ms * 1e-3),
                roofline=dict(bound="mfma", kernel="k_dense_mfma", unit="TOP/s", peak=INT8_MFMA_PEAK_TOPS,
                              achieved=2 * macs / (kms * 1e-3) / 1e12, frac=2 * macs / (kms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
-                             avg_launch_ms=kms, ops_per_launch=2 * macs, traffic=None))
+                             avg_launch_ms=kms, ops_per_launch=2 * macs,
+                             # HBM bytes per launch from the rocprofv3 --pmc runs in profiles/k_dense_mfma_dense4096_b128_pmc.txt
+                             traffic=1.965e9 + 0.327e9, algorithmic_bytes_per_launch=float(M) * K * len(ctx.primes) + 2.0 * Bn * (M + K) / 2 * 16 * sum((ctx.lam(p) + 15) // 16 for p in ctx.primes)))
     ctx.close()
     torch.cuda.empty_cache()
     return out
