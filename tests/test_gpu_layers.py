@@ -94,3 +94,22 @@ def test_reduced_accuracy_digit_sets():
         run_activation(8, kind, X, repeat=rep, digits=workloads.DIGITS_REDUCED[8], exact=False)
     P4 = int(np.prod(workloads.PRIMES[:4]))
     run_activation(4, "relu", np.arange(P4), digits=(4, 15), exact=False)
+
+
+def test_empty_layer_calls_are_accepted():
+    """zero elements: every layer kind returns without launching anything"""
+    from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN, DENSE, CONV2D, SUMPOOL
+    ctx, orc = both(3)
+    t = Labels(ctx, 0)
+    w = ctx.weights_prepare(np.ones((4, 8), np.int32))
+    for lay in (Layer(RELU, 1, 0), Layer(SCALE, 2, 0, repeat=2), Layer(SIGN, 3, 0),
+                Layer(DENSE, 4, 0, in_c=8, out_c=4, weights=w),
+                Layer(CONV2D, 5, 0, in_h=2, in_w=2, in_c=2, out_c=4, kh=1, kw=1, stride=1, pad=0, weights=w),
+                Layer(SUMPOOL, 6, 0, in_h=2, in_w=2, in_c=2)):
+        oe, tb, sb = ctx.layer_sizes(lay)
+        assert tb == 0
+        ctx.garble_layer(lay, t, t, None, None)
+        ctx.eval_layer(lay, t, None, t, None)
+    ctx.encode(torch.zeros(0, dtype=torch.int64, device=ctx.device), t, t)
+    ctx.decode(t, t, torch.zeros(0, dtype=torch.int64, device=ctx.device), torch.zeros(0, dtype=torch.uint8, device=ctx.device))
+    torch.cuda.synchronize()
