@@ -144,15 +144,18 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
     const QD Q = make_mod<QD>::from(Mq);
     uint32_t g = bx * kThreads + tx;
     if (g >= L.n_elem) return;
-    uint32_t colour = 0;
+    // the row is named by the colour (digit 0 of the label): its loads are issued before the hash, not after
+    uint32_t colour = ld_dw(J.in, g, 0) & 0xffu;
+    const uint32_t* row = (const uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
+    uint32_t rw[cmod_ndw<QD>::value];
+    if constexpr (cmod_m<QD>::value != 0) {
+#pragma unroll
+        for (int i = 0; i < (int)QD::ndw; i++) rw[i] = row[i];
+    }
     U128 K = {{0, 0, 0, 0}};
     with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(J.in, g, i); }, &colour); });
     U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
-    const uint32_t* row = (const uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
     if constexpr (cmod_m<QD>::value != 0) {
-        uint32_t rw[QD::ndw];           // the whole row first: wide loads, none of them behind a store
-#pragma unroll
-        for (int i = 0; i < (int)QD::ndw; i++) rw[i] = row[i];
         decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(rw[i], hd, Q)); });
     } else {
         decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(row[i], hd, Q)); });
@@ -165,14 +168,16 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
 // goes dword by dword to out.
 template <class MI, class MO, class Tab, class In, class Out>
 DASH_HD void chain_gate(const ChainLaunch& L, const MI& Mi, const MO& Mo, uint32_t e, int j, In in_dw, Out out, const Tab& T) {
-    uint32_t colour = 0;
-    U128 K = compress(Mi, in_dw, &colour);
-    U128 h = hash_block(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T);
+    uint32_t colour = in_dw(0) & 0xffu;       // the row's loads go out before the hash
     const uint32_t* row = (const uint32_t*)(L.table[j] + ((size_t)e * Mi.m + colour) * (Mo.ndw * 4));
+    uint32_t rw[cmod_ndw<MO>::value];
     if constexpr (cmod_m<MO>::value != 0) {
-        uint32_t rw[MO::ndw];
 #pragma unroll
         for (int i = 0; i < (int)MO::ndw; i++) rw[i] = row[i];
+    }
+    U128 K = compress(Mi, in_dw, &colour);
+    U128 h = hash_block(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T);
+    if constexpr (cmod_m<MO>::value != 0) {
         decompress(Mo, h, [&](int i, uint32_t hd) { out(i, submod4(rw[i], hd, Mo)); });
     } else {
         decompress(Mo, h, [&](int i, uint32_t hd) { out(i, submod4(row[i], hd, Mo)); });

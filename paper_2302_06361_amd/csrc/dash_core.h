@@ -87,6 +87,9 @@ struct CMod {
 // the modulus of a compile-time description, 0 for the run-time one
 template <class T> struct cmod_m { static constexpr uint32_t value = 0; };
 template <uint32_t MOD, uint32_t LAM> struct cmod_m<CMod<MOD, LAM>> { static constexpr uint32_t value = MOD; };
+// dwords per label of a compile-time description, 1 for the run-time one (array sizes)
+template <class T> struct cmod_ndw { static constexpr uint32_t value = 1; };
+template <uint32_t MOD, uint32_t LAM> struct cmod_ndw<CMod<MOD, LAM>> { static constexpr uint32_t value = (LAM + 3) / 4; };
 
 struct U128 { uint32_t w[4]; };
 
