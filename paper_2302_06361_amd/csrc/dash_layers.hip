@@ -388,8 +388,9 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         const uint32_t sb = rep * slots_per_rep;
         LView nxt[DASH_MAX_PRIMES];
         for (int i = 0; i < k; i++) nxt[i] = (rep == L->repeat - 1) ? view_of(out, i) : pl.buf[rep & 1][i];
-        // (1) ShiftUp: + P/2, i.e. +1 on the mod-2 residue only
-        {
+        // (1) ShiftUp: + P/2, i.e. +1 on the mod-2 residue only (after the first repetition it was
+        //     formed together with the previous ShiftDown)
+        if (rep == 0) {
             AffineBatcher ab(c, E, s);
             Term t[2] = {Term{cur[0], 1}, Term{one[0], 1}};
             ab.add(2, pl.up, t, 2);
@@ -427,8 +428,13 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         // (4) ShiftDown: - floor(P/4)
         {
             AffineBatcher ab(c, E, s);
-            Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], (uint32_t)((2 - quarter % 2) % 2)}};
+            const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
+            Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};
             ab.add(2, nxt[0], t0, 2);
+            if (rep + 1 < L->repeat) {      // the next repetition's ShiftUp of the same wire
+                Term tu[2] = {Term{pl.w.bit, 1}, Term{one[0], (c0 + 1) % 2}};
+                ab.add(2, pl.up, tu, 2);
+            }
             for (int i = 1; i < k; i++) {
                 uint32_t p = c->prime[i];
                 Term t[2] = {Term{pl.b[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};

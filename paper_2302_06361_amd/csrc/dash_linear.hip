@@ -41,20 +41,31 @@ __global__ __launch_bounds__(kThreads) void k_weights_prepare(const PrepArgs A) 
     }
 }
 
-struct LinArgs {
-    const ModInfo* mods;
+struct LinPrime {
     uint32_t p;
     const int8_t* w;        // [Mpad][Kpad] residues of this prime
-    const int32_t* bias;    // [out_c] or NULL
     const uint8_t* one;     // chunked label of the constant-one wire (zero or active), or NULL
     LView in, out;
+};
+struct LinArgs {
+    const ModInfo* mods;
+    const int32_t* bias;    // [out_c] or NULL
     int64_t kpad;
     int batch, in_h, in_w, in_c, out_c, kh, kw, stride, pad, out_h, out_w;
+    LinPrime pr[DASH_MAX_PRIMES];
 };
 
-// one lane per (output value, chunk): 16 accumulators, one 16-byte label word per tap
-__global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs A) {
-    const ModInfo M = A.mods[A.p];
+// one lane per (output value, chunk): 16 accumulators, one 16-byte label word per tap; blockIdx.y = prime
+__global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs AA) {
+    struct { uint32_t p; const int8_t* w; const int32_t* bias; const uint8_t* one; LView in, out; int64_t kpad;
+             int batch, in_h, in_w, in_c, out_c, kh, kw, stride, pad, out_h, out_w; } A;
+    {
+        const LinPrime& P = AA.pr[blockIdx.y];
+        A.p = P.p; A.w = P.w; A.bias = AA.bias; A.one = P.one; A.in = P.in; A.out = P.out; A.kpad = AA.kpad;
+        A.batch = AA.batch; A.in_h = AA.in_h; A.in_w = AA.in_w; A.in_c = AA.in_c; A.out_c = AA.out_c; A.kh = AA.kh; A.kw = AA.kw;
+        A.stride = AA.stride; A.pad = AA.pad; A.out_h = AA.out_h; A.out_w = AA.out_w;
+    }
+    const ModInfo M = AA.mods[A.p];
     const int64_t n_out = (int64_t)A.batch * A.out_h * A.out_w * A.out_c;
     int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= n_out * M.nchunk) return;
@@ -103,14 +114,18 @@ __global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs A) {
     *(uint4*)(A.out.p + (int64_t)ch * A.out.cs + o * 16) = make_uint4(outw[0], outw[1], outw[2], outw[3]);
 }
 
+struct PoolPrime { uint32_t p; LView in, out; };
 struct PoolArgs {
     const ModInfo* mods;
-    uint32_t p;
-    LView in, out;
     int batch, in_h, in_w, ch;
+    PoolPrime pr[DASH_MAX_PRIMES];
 };
-__global__ __launch_bounds__(kThreads) void k_sumpool(const PoolArgs A) {
-    const ModInfo M = A.mods[A.p];
+// blockIdx.y = prime
+__global__ __launch_bounds__(kThreads) void k_sumpool(const PoolArgs AA) {
+    struct { uint32_t p; LView in, out; int batch, in_h, in_w, ch; } A;
+    A.p = AA.pr[blockIdx.y].p; A.in = AA.pr[blockIdx.y].in; A.out = AA.pr[blockIdx.y].out;
+    A.batch = AA.batch; A.in_h = AA.in_h; A.in_w = AA.in_w; A.ch = AA.ch;
+    const ModInfo M = AA.mods[A.p];
     const int oh = A.in_h / 2, ow = A.in_w / 2;
     const int64_t n_out = (int64_t)A.batch * oh * ow * A.ch;
     int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -151,11 +166,16 @@ int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_label
             return DASH_EINVAL;
     }
     if (L->kind == DASH_SUMPOOL) {
+        PoolArgs A;
+        memset(&A, 0, sizeof(A));
+        A.mods = c->d_mods; A.batch = (int)batch; A.in_h = in_h; A.in_w = in_w; A.ch = L->in_c;
+        int64_t lanes = 0;          // of the prime with the most chunks; the others' surplus blocks exit
         for (int i = 0; i < c->k; i++) {
-            PoolArgs A{c->d_mods, (uint32_t)c->prime[i], view_of(in, i), view_of(out, i), (int)batch, in_h, in_w, L->in_c};
-            int64_t lanes = n_out * c->mods[c->prime[i]].nchunk;
-            hipLaunchKernelGGL(k_sumpool, dim3((uint32_t)((lanes + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, A);
+            A.pr[i] = PoolPrime{(uint32_t)c->prime[i], view_of(in, i), view_of(out, i)};
+            const int64_t l = n_out * c->mods[c->prime[i]].nchunk;
+            lanes = l > lanes ? l : lanes;
         }
+        hipLaunchKernelGGL(k_sumpool, dim3((uint32_t)((lanes + kThreads - 1) / kThreads), c->k), dim3(kThreads), 0, s, A);
         DASH_HIP(hipGetLastError());
         return DASH_OK;
     }
@@ -168,19 +188,28 @@ int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_label
     }
     if (dense_mfma_wanted(L, batch)) return dense_mfma(c, L, garble, in, out, s);
     const int out_h = (in_h + 2 * pad - kh) / stride + 1, out_w = (in_w + 2 * pad - kw) / stride + 1;
+    LinArgs A;
+    memset(&A, 0, sizeof(A));
+    A.mods = c->d_mods; A.bias = L->bias; A.kpad = Kp;
+    A.batch = (int)batch; A.in_h = in_h; A.in_w = in_w; A.in_c = L->in_c; A.out_c = out_c;
+    A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.out_h = out_h; A.out_w = out_w;
+    int64_t lanes = 0;              // of the prime with the most chunks; the others' surplus blocks exit
+    double macs = 0, bytes = 0;
     for (int i = 0; i < c->k; i++) {
-        LinArgs A;
-        memset(&A, 0, sizeof(A));
-        A.mods = c->d_mods; A.p = c->prime[i];
-        A.w = (const int8_t*)L->weights + (int64_t)i * Mp * Kp;
-        A.bias = L->bias; A.one = L->bias ? (garble ? c->d_one0[i] : c->d_one[i]) : nullptr;
-        A.in = view_of(in, i); A.out = view_of(out, i); A.kpad = Kp;
-        A.batch = (int)batch; A.in_h = in_h; A.in_w = in_w; A.in_c = L->in_c; A.out_c = out_c;
-        A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.out_h = out_h; A.out_w = out_w;
-        int64_t lanes = n_out * c->mods[c->prime[i]].nchunk;
-        double lam = c->mods[c->prime[i]].lam;
-        ProfScope ps(c->prof, DASH_PROF_LINEAR, s, (double)n_out * K * lam, ((double)n_in + n_out) * lam + (double)out_c * K);
-        hipLaunchKernelGGL(k_linear_direct, dim3((uint32_t)((lanes + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, A);
+        LinPrime& P = A.pr[i];
+        P.p = c->prime[i];
+        P.w = (const int8_t*)L->weights + (int64_t)i * Mp * Kp;
+        P.one = L->bias ? (garble ? c->d_one0[i] : c->d_one[i]) : nullptr;
+        P.in = view_of(in, i); P.out = view_of(out, i);
+        const int64_t l = n_out * c->mods[c->prime[i]].nchunk;
+        lanes = l > lanes ? l : lanes;
+        const double lam = c->mods[c->prime[i]].lam;
+        macs += (double)n_out * K * lam;
+        bytes += ((double)n_in + n_out) * lam + (double)out_c * K;
+    }
+    {
+        ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
+        hipLaunchKernelGGL(k_linear_direct, dim3((uint32_t)((lanes + kThreads - 1) / kThreads), c->k), dim3(kThreads), 0, s, A);
     }
     DASH_HIP(hipGetLastError());
     return DASH_OK;
