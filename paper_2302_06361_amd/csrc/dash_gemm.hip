@@ -27,12 +27,17 @@
 // (A second shape, 128 x 512 with 8 waves of 64 x 128 and two waves per SIMD, serves layers with few outputs.)
 //
 // Pipeline.  With one wave per SIMD nothing but the wave's own instruction order hides latency: global
-// data is fetched two K-steps ahead into one of two register sets, transposed and written to LDS one step
-// ahead, and the 32 MFMAs of a step are interleaved with the fragment reads of its second half and with
-// the LDS writes of the next step (sched_group_barrier).  Measured on the 4096 x 4096, batch 128, 12-prime
-// case: 1.38 ms, 35 % of the 5.0 POP/s int8 peak (a loop of nothing but MFMAs reaches 4.2 - 4.7 POP/s on
-// this chip); per K-step 2200 cycles against 1150 for the MFMAs alone, plus 0.25 ms of prologue and
-// epilogue that one block per CU cannot overlap with another block's MFMAs.
+// data is fetched a stage and a half ahead into one of two register sets, transposed and written to LDS
+// during the first K half of the stage before, and ONE barrier in the middle of a stage separates these
+// writes from the fragment reads of the next stage, which run under the MFMAs of the second half
+// (sched_group_barrier interleaving; the global loads are spread over the whole stage).  Measured on the
+// 4096 x 4096, batch 128, 12-prime case (per block tile, from time stamps inside the kernel): 3.1 us until
+// the first MFMA, 64 stages of 0.86 us (a loop of nothing but the 32 MFMAs of a stage runs at 0.55 us per
+// stage in the same launch shape: the matrix clock under load is about 2.1 GHz), 4.7 us of epilogue;
+// 1.24 ms in all, 38 % of the 5.0 POP/s int8 peak.  Taking parts out of the loop: without the global loads
+// 0.64 us per stage, without the fragment reads no change, without the byte transposes 0.83; the L2 answers
+// in 380 cycles on average (counter TCP_TCC_READ_REQ_LATENCY), far less than the prefetch distance, three
+// register sets (two and a half stages ahead) were slower, and so were two blocks of half the size per CU.
 #include <stdlib.h>
 #include <string.h>
 
@@ -93,7 +98,8 @@ struct GemmArgs {
 // (Layers with fewer than 4 row blocks use 2 x 16 or 1 x 32.)
 constexpr int kStBlocks = 32, kXcds = 8;
 
-template <class TL>
+// Plain: no bias and every accumulator below 2^24, the common case: its epilogue has no branches at all
+template <class TL, bool Conv, bool Plain>
 __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
     constexpr int kBM = TL::BM, kBG = TL::BG, IFR = TL::IFR, AP = TL::AP, T = TL::T;
     const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
@@ -135,13 +141,13 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
     const bool gvalid = gglob < ngroups;
     // a group past the end reads group 0 (its results are never stored): loads need no predicate
     const int gch = gvalid ? gglob / A.batch : 0, gb = gvalid ? gglob - gch * A.batch : 0;
-    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + (A.conv ? (int64_t)0 : ((int64_t)gb * K) * 16);
+    const uint8_t* xg = P.in.p + (int64_t)gch * P.in.cs + (Conv ? (int64_t)0 : ((int64_t)gb * K) * 16);
     // convolution: gb = (image, oy, ox)
-    const int conv = A.conv, in_h = A.in_h, in_w = A.in_w, in_c = A.in_c, kw = A.kw;
+    const int in_h = A.in_h, in_w = A.in_w, in_c = A.in_c, kw = A.kw;
     const uint32_t c_magic = A.c_magic, kw_magic = A.kw_magic;
     const uint8_t* const zero = A.zero;
     int img = 0, iy0 = 0, ix0 = 0;
-    if (conv) {
+    if constexpr (Conv) {
         const int per = A.out_h * A.out_w;
         img = gb / per;
         const int r = gb - img * per, oy = r / A.out_w, ox = r - oy * A.out_w;
@@ -172,17 +178,20 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
         const uint8_t* src = xg + ((((int64_t)img * in_h + iy) * in_w + ix) * in_c + ci) * 16;
         return (const u32x4*)(ok ? src : zero);
     };
-    auto load_stage = [&](int k0, Regs& R) __attribute__((always_inline)) {
+    auto load_a = [&](int k0, Regs& R) __attribute__((always_inline)) {
         R.a0 = *a_src(0, k0);
         if constexpr (AP > 1) R.a1 = *a_src(1, k0);
         if constexpr (AP > 2) { R.a2 = *a_src(2, k0); R.a3 = *a_src(3, k0); }
-        if (conv) {
+    };
+    auto load_b = [&](int k0, Regs& R, int half) __attribute__((always_inline)) {      // half 0: rows 0, 1; 1: rows 2, 3
+        if constexpr (Conv) {
             const u32x4* src = conv_src(k0);
-            R.b0 = src[0]; R.b1 = src[1]; R.b2 = src[2]; R.b3 = src[3];
+            if (half == 0) { R.b0 = src[0]; R.b1 = src[1]; } else { R.b2 = src[2]; R.b3 = src[3]; }
         } else {
-            R.b0 = *b_src(0, k0); R.b1 = *b_src(1, k0); R.b2 = *b_src(2, k0); R.b3 = *b_src(3, k0);
+            if (half == 0) { R.b0 = *b_src(0, k0); R.b1 = *b_src(1, k0); } else { R.b2 = *b_src(2, k0); R.b3 = *b_src(3, k0); }
         }
     };
+    auto load_stage = [&](int k0, Regs& R) __attribute__((always_inline)) { load_a(k0, R); load_b(k0, R, 0); load_b(k0, R, 1); };
     auto store_stage = [&](int buf, const Regs& R) __attribute__((always_inline)) {
         uint8_t* ad = As(buf) + arow * kRow + apart * 16;
         *(u32x4*)(ad) = R.a0;
@@ -211,66 +220,97 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
         for (int s = 0; s < 4; s++) acc[i][s] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
     const int nk = (int)(kpad / kKT);
-    load_stage(0, Rx);
-    store_stage(0, Rx);
-    __syncthreads();
-    if (nk > 1) load_stage(kKT, Ry);
     const int n = lane & 31, kh = lane >> 5;
     const int fa = (wm * 32 * IFR + n) * kRow + kh * 16;                         // + i*32*kRow + ks*32
     const int fb = (((wn * 8 + (n >> 2)) * 4) + (n & 3)) * kRow + kh * 16;       // + s*kBG*4*kRow + ks*32
-    // Software pipeline inside the wave (one wave per SIMD: nothing else hides latency).  Per stage:
-    //   global loads of the stage after next
-    //   16 MFMAs of the first K half   | LDS reads of the fragments of the second half
-    //   16 MFMAs of the second K half  | the next stage's data: byte transposes and LDS writes
-    // then the barrier and the fragment reads of the first half of the next stage.
-    // sched_group_barrier(mask, n, id): 0x8 MFMA, 0x100 LDS read, 0x200 LDS write, 0x2 vector ALU.
-    v4i a0[IFR], b0[4], a1[IFR], b1[4];
+    // Software pipeline inside the wave (one wave per SIMD: nothing else hides latency).  Stage kt works on
+    // LDS buffer kt & 1 and holds ALL its fragments in registers when it starts; its two halves of K are
+    //   MFMAs of the first half   | byte transposes and LDS writes of stage kt + 1 (other buffer)
+    //   barrier
+    //   MFMAs of the second half  | fragment reads of stage kt + 1 (both halves), global loads of stage kt + 3
+    // so the barrier is followed by MFMAs whose operands are already there, and no LDS latency is exposed.
+    // Why one barrier is enough: a wave in the first half of stage kt has passed the barrier of stage kt - 1,
+    // before which every wave finished its reads of buffer (kt + 1) & 1 (they belong to the second half of
+    // stage kt - 2); and the reads after the barrier of stage kt see all writes before it.
+    // Registers: first-half fragments (a0, b0) are free again after the first half; second-half fragments
+    // alternate between two sets by the parity of the stage; global data of stage j lives in set j & 1.
+    // sched_group_barrier(mask, n, id): 0x8 MFMA, 0x100 LDS read, 0x200 LDS write, 0x2 vector ALU, 0x20 global load.
+    v4i a0[IFR], b0[4], a1[IFR], b1[4], a2[IFR], b2[4];
     auto read_frags = [&](int buf, int ks, v4i (&a)[IFR], v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < IFR; i++) a[i] = *(const v4i*)(As(buf) + fa + i * 32 * kRow + ks * 32);
 #pragma unroll
         for (int q = 0; q < 4; q++) b[q] = *(const v4i*)(Bs(buf) + fb + q * kBG * 4 * kRow + ks * 32);
     };
-    auto mfma16 = [&](const v4i (&a)[IFR], const v4i (&b)[4]) __attribute__((always_inline)) {
+    auto mfma_rows = [&](int i0, int i1, const v4i (&a)[IFR], const v4i (&b)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < IFR; i++)
+        for (int i = i0; i < i1; i++)
 #pragma unroll
             for (int q = 0; q < 4; q++) acc[i][q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[q], acc[i][q], 0, 0, 0);
     };
-    // one stage that has a successor: Rl receives stage kt + 2, Rs holds stage kt + 1
-    auto stage = [&](int kt, Regs& Rl, const Regs& Rs) __attribute__((always_inline)) {
+    auto mfma16 = [&](const v4i (&a)[IFR], const v4i (&b)[4]) __attribute__((always_inline)) { mfma_rows(0, IFR, a, b); };
+    // one stage that has a successor: Rn holds stage kt + 1 and receives stage kt + 3; (as, bs) are this
+    // stage's second-half fragments, (an, bn) receive the next stage's
+    auto stage = [&](int kt, Regs& Rn, const v4i (&as)[IFR], const v4i (&bs)[4], v4i (&an)[IFR], v4i (&bn)[4]) __attribute__((always_inline)) {
         const int cur = kt & 1;
-        load_stage((kt + 2 < nk ? kt + 2 : nk - 1) * kKT, Rl);      // past the end: the last stage again, unused (no branch, so the
-                                                                    // wait before the LDS writes can leave these loads in flight)
-        read_frags(cur, 1, a1, b1);
+        const int knext = (kt + 3 < nk ? kt + 3 : nk - 1) * kKT;    // past the end: the last stage again, unused (no branch, so no
+                                                                    // wait on these loads is forced before they are needed)
+        // The global loads are spread over the whole stage, one per four MFMAs: the four waves of a block run in step,
+        // and eight loads per wave in a row fill the queue to the texture unit, which then holds up the MFMAs behind them.
+        store_stage(cur ^ 1, Rn);
+        load_a(knext, Rn);                       // (after the LDS writes of the weight pieces have read these registers)
         mfma16(a0, b0);
 #pragma unroll
-        for (int t = 0; t < IFR + 4; t++) {      // IFR + 4 fragment reads among 4 IFR MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x008, IFR == 4 ? 2 : 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        store_stage(cur ^ 1, Rs);
-        mfma16(a1, b1);
-#pragma unroll
-        for (int t = 0; t < 4 * IFR; t++) {      // 32 byte permutes and 8 + AP LDS writes among 4 IFR MFMAs
+        for (int t = 0; t < 4 * IFR; t++) {      // 32 byte permutes, 8 + AP LDS writes and AP global loads among 4 IFR MFMAs
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, IFR == 4 ? 3 : 5, 0);
             __builtin_amdgcn_sched_group_barrier(0x200, IFR == 4 ? 1 : 2, 0);
+            if (t >= AP && (t - AP) % 3 == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        load_b(knext, Rn, 0);
+        // the fragments the next stage needs first are read first: two scheduling regions
         read_frags(cur ^ 1, 0, a0, b0);
+        mfma_rows(0, IFR / 2, as, bs);
+#pragma unroll
+        for (int t = 0; t < 2 * IFR; t++) {      // IFR + 4 fragment reads, AP + 4 global loads and their addresses among 2 IFR MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, IFR == 4 ? 1 : 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, Conv ? 6 : 2, 0);
+            if (t % (IFR == 4 ? 4 : 2) == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_b(knext, Rn, 1);
+        read_frags(cur ^ 1, 1, an, bn);
+        mfma_rows(IFR / 2, IFR, as, bs);
+#pragma unroll
+        for (int t = 0; t < 2 * IFR; t++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, IFR == 4 ? 1 : 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, Conv ? 6 : 2, 0);
+            if (t % (IFR == 4 ? 4 : 2) == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
+    load_stage(0, Rx);
+    if (nk > 1) load_stage(kKT, Ry);
+    store_stage(0, Rx);
+    __syncthreads();
+    load_stage((2 < nk ? 2 : nk - 1) * kKT, Rx);
     read_frags(0, 0, a0, b0);
+    read_frags(0, 1, a1, b1);
     int kt = 0;
-    for (; kt + 2 < nk; kt += 2) { stage(kt, Rx, Ry); stage(kt + 1, Ry, Rx); }
-    if (kt + 1 < nk) { stage(kt, Rx, Ry); kt++; }
-    {   // last stage: nothing left to fetch
-        read_frags(kt & 1, 1, a1, b1);
-        mfma16(a0, b0);
-        mfma16(a1, b1);
+    for (; kt + 2 < nk; kt += 2) { stage(kt, Ry, a1, b1, a2, b2); stage(kt + 1, Rx, a2, b2, a1, b1); }
+    if (kt + 1 < nk) {      // nk even: one more stage with a successor, which leaves the last fragments in the second set
+        stage(kt, Ry, a1, b1, a2, b2);
+#pragma unroll
+        for (int i = 0; i < IFR; i++) a1[i] = a2[i];
+#pragma unroll
+        for (int q = 0; q < 4; q++) b1[q] = b2[q];
     }
+    mfma16(a0, b0);         // last stage: nothing left to fetch
+    mfma16(a1, b1);
 
     // ---- epilogue: reduce mod p, pack the four digits of a dword, stage the output tile in LDS as
     // [group][row][16 digits] and store it 16 bytes per lane, consecutive lanes consecutive rows (rows of one
@@ -283,38 +323,64 @@ __global__ __launch_bounds__(TL::T) void k_dense_mfma(const GemmArgs A) {
         if (G < ngroups) one4 = *(const uint32_t*)(P.one + (G / A.batch) * 16 + 4 * g);
     }
     auto red1 = [&](uint32_t v) -> uint32_t { return v - mul24(mulhi(v, mmagic), prime); };      // v < 2^24
-    auto emit = [&](auto small) {
+    // 16 accumulators (four output dwords) at a time: enough independent work to fill the latencies (one wave per SIMD:
+    // nothing else does), the two rare steps under one uniform branch per 16 instead of one per element, and the
+    // scheduler cannot pull all 256 accumulator reads to the front.
 #pragma unroll
-        for (int i = 0; i < IFR; i++)
+    for (int i = 0; i < IFR; i++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int jl = wm * 32 * IFR + i * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
-                uint32_t d[4];
+        for (int rq = 0; rq < 4; rq++) {
+            uint32_t v[4][4];
 #pragma unroll
-                for (int s = 0; s < 4; s++) {
-                    uint32_t v = (uint32_t)acc[i][s][r];
-                    if (!decltype(small)::value) v = mul24(red1(v >> 12), pow12) + (v & 4095u);    // v = hi * 4096 + lo
-                    d[s] = red1(v);
-                }
-                if (bias) {
-                    const int j = row0 + jl;
-                    int32_t bj = j < M ? bias[j] % (int32_t)prime : 0;
-                    uint32_t bm = (uint32_t)(bj < 0 ? bj + (int32_t)prime : bj);
+            for (int rr = 0; rr < 4; rr++)
 #pragma unroll
-                    for (int s = 0; s < 4; s++) d[s] = red1(d[s] + mul24(bm, (one4 >> (8 * s)) & 0xffu));
-                }
-                *(uint32_t*)(smem + Gl * kOutStride + jl * 16 + 4 * g) = d[0] | (d[1] << 8) | (d[2] << 16) | (d[3] << 24);
+                for (int s = 0; s < 4; s++) v[rr][s] = (uint32_t)acc[i][s][rq * 4 + rr];
+            const int jl0 = wm * 32 * IFR + i * 32 + rq * 8 + kh * 4;           // + rr
+            if (!Plain && !small_acc) {       // large accumulators: below 2^24 first (v = hi * 4096 + lo)
+#pragma unroll
+                for (int rr = 0; rr < 4; rr++)
+#pragma unroll
+                    for (int s = 0; s < 4; s++) v[rr][s] = mul24(red1(v[rr][s] >> 12), pow12) + (v[rr][s] & 4095u);
             }
-    };
-    if (small_acc) emit(std::true_type{}); else emit(std::false_type{});
+            if (!Plain && bias) {
+#pragma unroll
+                for (int rr = 0; rr < 4; rr++) {
+                    const int j = row0 + jl0 + rr;
+                    const int32_t bj = j < M ? bias[j] % (int32_t)prime : 0;
+                    const uint32_t bm = (uint32_t)(bj < 0 ? bj + (int32_t)prime : bj);
+#pragma unroll
+                    for (int s = 0; s < 4; s++) v[rr][s] = red1(v[rr][s]) + mul24(bm, (one4 >> (8 * s)) & 0xffu);
+                }
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; rr++) {
+                const uint32_t d0 = red1(v[rr][0]), d1 = red1(v[rr][1]), d2 = red1(v[rr][2]), d3 = red1(v[rr][3]);
+                *(uint32_t*)(smem + Gl * kOutStride + (jl0 + rr) * 16 + 4 * g) = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     __syncthreads();
+    // group gl of the tile is stored by all lanes together, lane -> row (kBM a multiple of T, or T of kBM)
+    {
+        constexpr int kPerGroup = kBM >= T ? kBM / T : 1;          // pieces per lane and group
+        constexpr int kGroupsPerPass = kBM >= T ? 1 : T / kBM;     // groups stored side by side
+        const int gsub = kBM >= T ? 0 : tid / kBM, jbase = kBM >= T ? tid : tid % kBM;
+        int G = grp0 + gsub;
+        int och = G / A.batch, ob = G - och * A.batch;             // one division; the rest is counted up
+        const int batch = A.batch;
+        const int64_t ocs = P.out.cs;
+        uint8_t* const obase = P.out.p;
 #pragma unroll 4
-    for (int id = tid; id < kBG * kBM; id += T) {
-        const int gl = id / kBM, jl = id - gl * kBM;
-        const int G = grp0 + gl, j = row0 + jl;
-        if (G < ngroups && j < M) {
-            const int och = G / A.batch, ob = G - och * A.batch;
-            *(u32x4*)(P.out.p + (int64_t)och * P.out.cs + ((int64_t)ob * M + j) * 16) = *(const u32x4*)(smem + gl * kOutStride + jl * 16);
+        for (int gl = gsub; gl < kBG; gl += kGroupsPerPass) {
+            if (G < ngroups) {
+#pragma unroll
+                for (int t = 0; t < kPerGroup; t++) {
+                    const int jl = jbase + t * T, j = row0 + jl;
+                    if (j < M) *(u32x4*)(obase + (int64_t)och * ocs + ((int64_t)ob * M + j) * 16) = *(const u32x4*)(smem + gl * kOutStride + jl * 16);
+                }
+            }
+            G += kGroupsPerPass; ob += kGroupsPerPass;
+            while (ob >= batch) { ob -= batch; och++; }
         }
     }
 }
@@ -384,7 +450,10 @@ int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         A.st_total = (int)st_total;
         dim3 grid((uint32_t)((st_total + kXcds - 1) / kXcds * kXcds * kStBlocks));
         ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
-        hipLaunchKernelGGL(k_dense_mfma<TL>, grid, dim3(TL::T), 0, s, A);
+        const bool plain = A.small_acc && !A.bias;
+        auto kernel = conv ? (plain ? k_dense_mfma<TL, true, true> : k_dense_mfma<TL, true, false>)
+                           : (plain ? k_dense_mfma<TL, false, true> : k_dense_mfma<TL, false, false>);
+        hipLaunchKernelGGL(kernel, grid, dim3(TL::T), 0, s, A);
         return DASH_OK;
     };
     const int st = wide ? launch(TileWide{}) : launch(TileBig{});

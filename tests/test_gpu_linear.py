@@ -82,9 +82,17 @@ def test_dense_mfma_ragged_tiles_and_bias():
 
 
 def test_dense_mfma_config4_sample():
-    """config 4 shape on a slice: K = 4096 inputs (one-step reduction no longer applies for the larger
-    primes), 96 output rows, batch 2, all 12 primes, weights in [-64, 63]"""
+    """config 4 shape on a slice: K = 4096 inputs, 96 output rows, batch 2, all 12 primes, weights in [-64, 63]"""
     run_linear(12, 2, 1, 1, 4096, 96, 1, 1, 0, -64, 63, False, 24)
+
+
+def test_dense_mfma_large_accumulators_and_stage_counts():
+    """K = 13000: (p - 1)^2 K passes 2^24 for p = 37, so the two-step reduction of the accumulators runs (with and
+    without bias); K = 250 and 192: four and three K stages (every exit of the software pipeline)"""
+    run_linear(12, 1, 1, 1, 13000, 70, 1, 1, 0, -64, 63, True, 25)
+    run_linear(12, 2, 1, 1, 13000, 40, 1, 1, 0, -64, 63, False, 26, garble=False)
+    run_linear(8, 3, 1, 1, 250, 130, 1, 1, 0, -8, 7, False, 27)
+    run_linear(8, 3, 1, 1, 192, 130, 1, 1, 0, -8, 7, True, 28)
 
 
 def test_conv_mfma_shapes():
