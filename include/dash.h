@@ -149,6 +149,17 @@ int dash_encode(dash_ctx *ctx, const int64_t *values, int64_t n, const dash_labe
 int dash_decode(dash_ctx *ctx, const dash_labels *act, const dash_labels *zero, int64_t n, int64_t *values,
                 uint8_t *valid, void *hip_stream);
 
+/* The 128-bit wire format of labels (Sec. Evaluation, online communication: every label is compressed
+ * to 128 bits for transfer; Sec. Implementation: compress(l) = (...(l_n p + l_{n-1}) p + ...) p + l_1).
+ * packed: device, 16-byte aligned, [k residues][n][16 bytes], each entry the little-endian 128-bit
+ * integer sum_j l_j p^j of the label of element e (elements 0 .. n-1 of the LabelTensor), residue i.
+ * 16 bytes per label instead of 16 * ceil(lambda / 16).  unpack is the inverse (base-p digits, least
+ * significant first, digits past lambda zero).  Lossless only if p^lambda <= 2^128 for every residue,
+ * i.e. for contexts created with the floor rule of the LabelTensor figure; otherwise both calls
+ * return DASH_EUNSUPPORTED and touch nothing.  Asynchronous on the stream, no allocation. */
+int dash_labels_pack(dash_ctx *ctx, const dash_labels *labels, int64_t n, void *packed, void *hip_stream);
+int dash_labels_unpack(dash_ctx *ctx, const void *packed, int64_t n, dash_labels *labels, void *hip_stream);
+
 /* Benchmark instrumentation (not part of the scheme): while enabled, every launch of the kernel
  * classes below is bracketed by two HIP events on its stream.  dash_profile_read synchronises,
  * returns the summed kernel time, the number of launches, the units processed (ciphertext rows for

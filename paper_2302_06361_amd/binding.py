@@ -18,7 +18,7 @@ LAMBDA_CEIL, LAMBDA_FLOOR = 0, 1
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_input_labels", "dash_encode", "dash_decode", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
+           "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
 
 
 class DashError(RuntimeError):
@@ -230,6 +230,17 @@ class Context:
         ca, cz = act.c(), zero.c()
         _check(self.L.dash_decode(self.h, C.byref(ca), C.byref(cz), C.c_int64(values.numel()), C.c_void_p(values.data_ptr()),
                                   C.c_void_p(valid.data_ptr()), _stream()), "dash_decode")
+
+    def labels_pack(self, labels, packed):
+        """labels -> packed (uint8 tensor [k][n][16]): the 128-bit wire format; floor-rule contexts only"""
+        cl = labels.c()
+        _check(self.L.dash_labels_pack(self.h, C.byref(cl), C.c_int64(labels.n_elem), C.c_void_p(packed.data_ptr()), _stream()),
+               "dash_labels_pack")
+
+    def labels_unpack(self, packed, labels):
+        cl = labels.c()
+        _check(self.L.dash_labels_unpack(self.h, C.c_void_p(packed.data_ptr()), C.c_int64(labels.n_elem), C.byref(cl), _stream()),
+               "dash_labels_unpack")
 
     def garble_layer(self, layer, in_zero, out_zero, tables=None, scratch=None):
         ci, co = in_zero.c(), out_zero.c()

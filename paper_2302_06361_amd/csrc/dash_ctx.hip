@@ -113,6 +113,41 @@ __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
     A.valid[e] = ok ? 1 : 0;
 }
 
+// 128-bit wire format (Sec. Evaluation, online communication: labels travel compressed to 128 bits;
+// Sec. Implementation: compress by Horner's method): one lane per label.
+__global__ __launch_bounds__(kThreads) void k_pack(const ModInfo* mods, uint32_t m, uint32_t n, LView lab, uint8_t* packed) {
+    const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    const ModInfo M = mods[m];
+    uint32_t colour;
+    const U128 x = compress(M, [&](int i) { return *(const uint32_t*)(lab.p + (int64_t)(i >> 2) * lab.cs + (uint64_t)e * 16 + (i & 3) * 4); },
+                            &colour);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    *(u32x4*)(packed + (uint64_t)e * 16) = u32x4{x.w[0], x.w[1], x.w[2], x.w[3]};
+}
+__global__ __launch_bounds__(kThreads) void k_unpack(const ModInfo* mods, uint32_t m, uint32_t n, const uint8_t* packed, LView lab) {
+    const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    const ModInfo M = mods[m];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = *(const u32x4*)(packed + (uint64_t)e * 16);
+    const U128 x = {{v.x, v.y, v.z, v.w}};
+    auto put = [&](int i, uint32_t w) { *(uint32_t*)(lab.p + (int64_t)(i >> 2) * lab.cs + (uint64_t)e * 16 + (i & 3) * 4) = w; };
+    decompress(M, x, put);
+    for (uint32_t i = M.ndw; i < M.nchunk * 4; i++) put((int)i, 0u);      // digits past lambda are zero in a LabelTensor
+}
+
+// true if every label of modulus m with lam digits is below 2^128 as a base-m number (m^lam <= 2^128)
+static bool fits_128_bits(uint32_t m, uint32_t lam) {
+    if ((m & (m - 1)) == 0) { uint32_t t = 0; while ((1u << t) < m) t++; return t * lam <= 128; }
+    u128 r = 1;
+    for (uint32_t j = 0; j < lam; j++) {
+        if (r > ~(u128)0 / m) return false;
+        r *= m;
+    }
+    return true;
+}
+
 }  // namespace dash
 
 // ------------------------------------------------------------------------------------------------
@@ -415,6 +450,43 @@ int dash_decode(dash_ctx* c, const dash_labels* act, const dash_labels* zero, in
         A.zero[i] = view_of(zero, i);
     }
     hipLaunchKernelGGL(k_decode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream, A);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+static int pack_args(const dash_ctx* c, const dash_labels* labels, const void* packed, int64_t n) {
+    if (!c || n < 0 || (n > 0 && !packed)) return DASH_EINVAL;
+    if (n > 0x7fffffff) return DASH_ESIZE;
+    if ((uintptr_t)packed & 15) return DASH_EINVAL;
+    const int st = check_labels(c, labels, n);
+    if (st) return st;
+    for (int i = 0; i < c->k; i++) {
+        const ModInfo& M = c->mods[c->prime[i]];
+        if (labels->data[i] && !dash::fits_128_bits(M.m, M.lam)) return DASH_EUNSUPPORTED;
+    }
+    return DASH_OK;
+}
+
+int dash_labels_pack(dash_ctx* c, const dash_labels* labels, int64_t n, void* packed, void* stream) {
+    const int st = pack_args(c, labels, packed, n);
+    if (st || n == 0) return st;
+    for (int i = 0; i < c->k; i++) {
+        if (!labels->data[i]) continue;
+        hipLaunchKernelGGL(k_pack, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream, c->d_mods,
+                           (uint32_t)c->prime[i], (uint32_t)n, view_of(labels, i), (uint8_t*)packed + (size_t)i * (size_t)n * 16);
+    }
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+int dash_labels_unpack(dash_ctx* c, const void* packed, int64_t n, dash_labels* labels, void* stream) {
+    const int st = pack_args(c, labels, packed, n);
+    if (st || n == 0) return st;
+    for (int i = 0; i < c->k; i++) {
+        if (!labels->data[i]) continue;
+        hipLaunchKernelGGL(k_unpack, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream, c->d_mods,
+                           (uint32_t)c->prime[i], (uint32_t)n, (const uint8_t*)packed + (size_t)i * (size_t)n * 16, view_of(labels, i));
+    }
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

@@ -78,3 +78,61 @@ def test_bad_arguments_are_refused():
         Context([2, 4, 5], bytes(16))       # 4 is not prime
     with pytest.raises(DashError):
         Context([2, 3, 5], bytes(16), digits=[3, 5, 9])    # d_1 must be even
+
+
+@pytest.mark.parametrize("k,n", [(8, 0), (8, 1), (8, 700), (12, 300)])
+def test_labels_pack_unpack_wire_format(k, n):
+    """the 128-bit wire format (Sec. Evaluation, online communication; compress of Sec. Implementation) under the
+    floor rule: pack == the oracle's compress label by label, unpack == its decompress, on uniform labels that
+    include the largest one (all digits p - 1) and on bytes the GPU never produced"""
+    from paper_2302_06361_amd import Labels
+    from oracle import capi
+    ctx, orc = both(k, rule=1)
+    g = np.random.default_rng(100 + n)
+    lab = [workloads.uniform_labels(g, n, orc.lam(p), p) for p in orc.primes]
+    if n > 1:
+        for i, p in enumerate(orc.primes):
+            lab[i][0, :] = p - 1
+            lab[i][1, :] = 0
+    t = upload_bundle(ctx, lab) if n else Labels(ctx, 0)
+    packed = torch.full((k, n, 16), 0xEE, dtype=torch.uint8, device=ctx.device)
+    ctx.labels_pack(t, packed)
+    back = Labels(ctx, n)
+    for i in range(k):
+        if n:
+            back.tensors[i].fill_(0xEE)
+    ctx.labels_unpack(packed, back)
+    torch.cuda.synchronize()
+    if n == 0:
+        return
+    got = packed.cpu().numpy()
+    foreign = np.zeros((k, n, 16), np.uint8)
+    for i, p in enumerate(orc.primes):
+        for e in range(n):
+            want = np.frombuffer(capi.compress(lab[i][e], p).to_bytes(16, "little"), np.uint8)
+            assert (got[i, e] == want).all(), (i, e)
+            # bytes the GPU did not write: the oracle's packing of another label
+            foreign[i, e] = np.frombuffer(capi.compress(lab[i][n - 1 - e], p).to_bytes(16, "little"), np.uint8)
+    assert_bundle_equal(back, lab, "unpack(pack(labels))")
+    ctx.labels_unpack(torch.as_tensor(foreign).to(ctx.device), back)
+    torch.cuda.synchronize()
+    for i, p in enumerate(orc.primes):
+        for e in (0, n // 2, n - 1):
+            h = int.from_bytes(foreign[i, e].tobytes(), "little")
+            assert (back.to_numpy(i)[e] == capi.decompress(h, p, orc.lam(p))).all(), (i, e)
+    assert_bundle_equal(back, [a[::-1] for a in lab], "unpack of the oracle's bytes")
+
+
+def test_labels_pack_needs_the_floor_rule():
+    """with the ceil rule a label can exceed 128 bits: both calls refuse and leave the buffers alone"""
+    from paper_2302_06361_amd import Labels
+    from paper_2302_06361_amd.binding import DashError
+    ctx, _ = both(8, rule=0)
+    t = Labels(ctx, 4, zero=True)
+    packed = torch.full((8, 4, 16), 7, dtype=torch.uint8, device=ctx.device)
+    with pytest.raises(DashError):
+        ctx.labels_pack(t, packed)
+    with pytest.raises(DashError):
+        ctx.labels_unpack(packed, t)
+    torch.cuda.synchronize()
+    assert bool((packed == 7).all().item())
