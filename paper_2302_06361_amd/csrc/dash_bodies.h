@@ -242,6 +242,46 @@ DASH_HD void chain_eval_generic_body(const ChainLaunch& L, uint32_t bx, uint32_t
     }
 }
 
+// ---- evaluator, digit gates of the sign gadget -------------------------------------------------
+// gate (residue, digit j) of element e with the compressed input label K and its colour already known
+template <class MO, class Tab>
+DASH_HD void digit_gate(const DigitsLaunch& L, const DigitsRes& R, const MO& Mo, const U128& K, uint32_t colour, uint32_t e, int j, const Tab& T) {
+    const uint8_t* seg = R.table + (size_t)L.n_elem * R.p * L.row_prefix[j];
+    const uint32_t* row = (const uint32_t*)(seg + ((size_t)e * R.p + colour) * (Mo.ndw * 4));
+    uint32_t rw[cmod_ndw<MO>::value];
+    if constexpr (cmod_m<MO>::value != 0) {
+#pragma unroll
+        for (int i = 0; i < (int)MO::ndw; i++) rw[i] = row[i];
+    }
+    const LView out{R.out + L.out_prefix[j], L.out_cs, 16u};
+    U128 h = hash_block(K, L.elem_base + e, R.slot0 + (uint32_t)(j - 1), L.layer, L.key.rk, T);
+    if constexpr (cmod_m<MO>::value != 0) {
+        decompress(Mo, h, [&](int i, uint32_t hd) { st_dw(out, e, i, submod4(rw[i], hd, Mo)); });
+    } else {
+        decompress(Mo, h, [&](int i, uint32_t hd) { st_dw(out, e, i, submod4(row[i], hd, Mo)); });
+    }
+    for (int i = (int)Mo.ndw; i < (int)Mo.nchunk * 4; i++) st_dw(out, e, i, 0);
+}
+// MC, M1: descriptions of the accumulation moduli of digits 2..n and of digit 1 (compile time), or ModInfo for
+// both (any digit set: then every digit's constants are read from the table of moduli)
+template <class MC, class M1, class Tab>
+DASH_HD void digits_eval_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+    const DigitsRes& R = L.res[by];
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem) return;
+    const ModInfo Mp = L.mods[R.p];
+    uint32_t colour = 0;
+    U128 K = {{0, 0, 0, 0}};
+    with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(R.in, e, i); }, &colour); });
+    if constexpr (cmod_m<MC>::value != 0) {
+        digit_gate(L, R, M1{nullptr}, K, colour, e, 1, T);
+        const MC Mc{nullptr};
+        for (int j = 2; j <= (int)L.n; j++) digit_gate(L, R, Mc, K, colour, e, j, T);
+    } else {
+        for (int j = 1; j <= (int)L.n; j++) digit_gate(L, R, L.mods[L.m[j]], K, colour, e, j, T);
+    }
+}
+
 // evaluator side of the mixed-modulus half gate: z = V + beta * x - U
 template <class Tab>
 DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {

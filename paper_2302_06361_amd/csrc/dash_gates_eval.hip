@@ -49,6 +49,56 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     return DASH_OK;
 }
 
+// ------------------------------------------------------------------- digit gates of the sign gadget, evaluator
+// One launch for the k n digit gates of a sign gadget (four launches of k_proj_eval before), lane = (element,
+// residue): the label is loaded and compressed once for its n gates.
+template <class MC, class M1, bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_digits_eval(const DigitsLaunch L) {
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
+    __shared__ uint32_t tt[gate_tab<Banked>::words];
+    const auto T = gate_tab<Banked>::load(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles)
+        digits_eval_body<MC, M1>(L, tile, blockIdx.y, tx, T);
+}
+
+int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
+    if (L.n < 1 || L.n > (uint32_t)kMaxChain || L.nres < 1 || L.nres > 16) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    bool uniform = L.n >= 2;
+    double bytes = 0;
+    for (uint32_t j = 1; j <= L.n; j++) {
+        if (L.m[j] < 2 || L.m[j] > 255 || !c->mods[L.m[j]].dtab) return DASH_EINVAL;
+        if (j >= 3 && L.m[j] != L.m[2]) uniform = false;
+    }
+    for (uint32_t i = 0; i < L.nres; i++) {
+        const DigitsRes& R = L.res[i];
+        if (R.p < 2 || R.p > 255 || !c->mods[R.p].dtab || !R.in.p || !R.table || !R.out) return DASH_EINVAL;
+        for (uint32_t j = 1; j <= L.n; j++) bytes += (double)L.n_elem * (c->mods[R.p].lam + 2.0 * c->mods[L.m[j]].lam);
+    }
+    const bool banked = (uint64_t)L.n_elem * L.nres >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)L.nres, banked), L.nres);
+    const dim3 block(banked ? kBigThreads : kThreads);
+    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
+    const ModInfo &M1 = c->mods[L.m[1]], &Mc = c->mods[L.m[L.n >= 2 ? 2 : 1]];
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.nres * L.n, bytes);
+    if (uniform && is(Mc, 96, 20) && is(M1, 26, 28)) {
+        if (banked) hipLaunchKernelGGL((k_digits_eval<CMod<96, 20>, CMod<26, 28>, true>), grid, block, 0, s, L);
+        else hipLaunchKernelGGL((k_digits_eval<CMod<96, 20>, CMod<26, 28>, false>), grid, block, 0, s, L);
+    } else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24)) {
+        if (banked) hipLaunchKernelGGL((k_digits_eval<CMod<204, 17>, CMod<46, 24>, true>), grid, block, 0, s, L);
+        else hipLaunchKernelGGL((k_digits_eval<CMod<204, 17>, CMod<46, 24>, false>), grid, block, 0, s, L);
+    } else {
+        if (banked) hipLaunchKernelGGL((k_digits_eval<ModInfo, ModInfo, true>), grid, block, 0, s, L);
+        else hipLaunchKernelGGL((k_digits_eval<ModInfo, ModInfo, false>), grid, block, 0, s, L);
+    }
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
 // ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
 // One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
 // whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any

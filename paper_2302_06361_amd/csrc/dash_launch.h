@@ -120,5 +120,31 @@ struct ChainLaunch {
     LView bit;                           // output wire (Z_2)
 };
 
+// evaluator side of the digit gates of one sign gadget (Appendix, approximated sign: residue i -> digit j of its
+// rounded CRT fraction): the n gates of a residue share their input label, so one lane takes (element, residue),
+// compresses the label once and evaluates its n gates.  Output wire (i, j) and table segment (i, j) are at fixed
+// offsets from those of (i, 1).
+struct DigitsRes {
+    uint32_t p, slot0;       // input modulus; slot of the gate to digit 1 (digit j: slot0 + j - 1)
+    LView in;                // active label of the residue
+    uint8_t* table;          // segment of gate (i, 1)
+    uint8_t* out;            // label tensor of wire (i, 1)
+};
+struct DigitsLaunch {
+    AesKey key;
+    const uint32_t* ttab;
+    const ModInfo* mods;
+    uint64_t elem_base;
+    uint32_t layer;
+    uint32_t n_elem;
+    uint32_t n, nres;
+    uint32_t m[kMaxChain + 1];            // accumulation modulus of digit j (1-based)
+    uint32_t row_prefix[kMaxChain + 1];   // sum of the row pitches of digits 1 .. j-1: segment (i, j) starts
+                                          // n_elem * p_i * row_prefix[j] bytes after segment (i, 1)
+    uint64_t out_prefix[kMaxChain + 1];   // wire (i, j) starts this many bytes after wire (i, 1)
+    int64_t out_cs;                       // chunk stride of the output wires
+    DigitsRes res[16];
+};
+
 }  // namespace dash
 

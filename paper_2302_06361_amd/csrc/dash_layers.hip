@@ -164,12 +164,36 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     }
     GateBatcher gb(c, garble, E, layer, elem_base, s);
     // digit gates: residue i -> digit j of its rounded CRT fraction
-    for (int i = first_res; i < k; i++)
+    if (garble) {
+        for (int i = first_res; i < k; i++)
+            for (int j = 1; j <= n; j++) {
+                int sl = i * n + (j - 1);
+                gb.add(phi_job(c->prime[i], c->mj[j], x[i], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]));
+            }
+        gb.flush();
+    } else {
+        // evaluator: the n gates of a residue share their input label; one launch for all k n gates
+        DigitsLaunch DL;
+        memset(&DL, 0, sizeof(DL));
+        DL.n_elem = E; DL.layer = layer; DL.elem_base = elem_base; DL.n = (uint32_t)n; DL.nres = (uint32_t)(k - first_res);
+        DL.out_cs = w.A[first_res][1].cs;
         for (int j = 1; j <= n; j++) {
-            int sl = i * n + (j - 1);
-            gb.add(phi_job(c->prime[i], c->mj[j], x[i], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]));
+            DL.m[j] = (uint32_t)c->mj[j];
+            DL.row_prefix[j] = j == 1 ? 0 : DL.row_prefix[j - 1] + (uint32_t)pitch_of(c, c->mj[j - 1]);
+            DL.out_prefix[j] = (uint64_t)(w.A[first_res][j].p - w.A[first_res][1].p);
         }
-    gb.flush();
+        for (int i = first_res; i < k; i++) {
+            DigitsRes& R = DL.res[i - first_res];
+            R.p = (uint32_t)c->prime[i]; R.slot0 = slot_base + (uint32_t)(i * n); R.in = x[i];
+            R.table = seg + off[i * n]; R.out = w.A[i][1].p;
+            for (int j = 1; j <= n; j++) {     // the kernel's address rule must be the layout planned above
+                if (off[i * n + j - 1] != off[i * n] + (size_t)E * c->prime[i] * DL.row_prefix[j]) return DASH_EINVAL;
+                if (w.A[i][j].p != R.out + DL.out_prefix[j] || w.A[i][j].cs != DL.out_cs || w.A[i][j].es != 16u) return DASH_EINVAL;
+            }
+        }
+        const int st = launch_digits_eval(c, DL, s);
+        if (st) return st;
+    }
     // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
     // The garbler knows every zero label up front, so it sums all digits first and garbles the n
     // gates of the chain in one launch; the evaluator has to follow the chain.
@@ -199,7 +223,8 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         return gb.status;
     }
     if (n >= 2) {
-        // evaluator: all digit sums (without carries) in one free-gate launch, then the whole chain in one
+        // evaluator: all digit sums (without carries) in one free-gate launch, then the whole chain in one (adding the
+        // digit wires inside the chain's lanes instead was measured slower: one lane per element, its loads in a row)
         AffineBatcher ab(c, E, s);
         for (int j = n; j >= 1; j--) {
             Term t[kMaxTerms];

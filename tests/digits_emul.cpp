@@ -1,0 +1,105 @@
+// Host emulation of the evaluator's fused digit-gate kernel: runs digits_eval_body (the code the __global__
+// kernel calls) lane by lane over exactly-sized host buffers under the sanitizers.  Test code, not part of libdash.
+//
+// usage: digits_emul <in.bin> <out.bin>
+//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 pad; uint64 elem_base;
+//        int32 m[n] (digit 1..n); int32 p[nres];
+//        for t < nres: u8 act_t[n_elem][lam(p_t)];
+//        for t < nres, j = 1..n: u8 table_tj[n_elem][p_t][pitch(m_j)]
+//   out: for t < nres, j = 1..n: u8 out_tj[n_elem][lam(m_j)]
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../paper_2302_06361_amd/csrc/dash_bodies.h"
+#include "../paper_2302_06361_amd/csrc/dash_hostconst.h"
+
+using namespace dash;
+using namespace dash::hostconst;
+
+static uint32_t TT[1024];
+struct HostTab {
+    template <int R, int B> uint32_t at(uint32_t w) const { return TT[R * 256 + ((w >> (8 * B)) & 0xffu)]; }
+};
+
+int main(int argc, char** argv) {
+    if (argc != 3) return 2;
+    FILE* f = fopen(argv[1], "rb");
+    if (!f) return 2;
+    int32_t hd[8];
+    uint64_t elem_base;
+    if (fread(hd, 4, 8, f) != 8 || fread(&elem_base, 8, 1, f) != 1) return 2;
+    const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6];
+    const uint32_t E = (uint32_t)hd[1];
+    if (n < 1 || n > kMaxChain || nres < 1 || nres > 16) return 2;
+    std::vector<int32_t> m(n + 1), p(nres);
+    if (fread(m.data() + 1, 4, n, f) != (size_t)n || fread(p.data(), 4, nres, f) != (size_t)nres) return 2;
+    std::vector<ModInfo> mods(256);
+    for (int q = 2; q < 256; q++) fill_modinfo(mods[q], q, rule);
+    uint8_t S[256];
+    make_sbox(S);
+    make_ttab(S, TT);
+
+    DigitsLaunch L;
+    memset(&L, 0, sizeof(L));
+    const uint8_t key[16] = {0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15};
+    expand_key(key, S, L.key.rk);
+    L.mods = mods.data(); L.elem_base = elem_base; L.layer = (uint32_t)layer; L.n_elem = E; L.n = (uint32_t)n; L.nres = (uint32_t)nres;
+    L.out_cs = (int64_t)16 * E;
+    size_t out_bytes = 0;
+    for (int j = 1; j <= n; j++) {
+        L.m[j] = (uint32_t)m[j];
+        L.row_prefix[j] = j == 1 ? 0 : L.row_prefix[j - 1] + mods[m[j - 1]].ndw * 4;
+        L.out_prefix[j] = out_bytes;
+        out_bytes += (size_t)mods[m[j]].nchunk * E * 16;
+    }
+    const uint32_t rows_pitch = L.row_prefix[n] + mods[m[n]].ndw * 4;
+    std::vector<std::vector<uint8_t>> act(nres), table(nres), out(nres);
+    for (int t = 0; t < nres; t++) {
+        const ModInfo& Mp = mods[p[t]];
+        std::vector<uint8_t> c((size_t)E * Mp.lam);
+        if (fread(c.data(), 1, c.size(), f) != c.size()) return 2;
+        act[t].assign((size_t)Mp.nchunk * E * 16, 0);
+        for (uint32_t e = 0; e < E; e++)
+            for (uint32_t d = 0; d < Mp.lam; d++) act[t][((size_t)(d / 16) * E + e) * 16 + d % 16] = c[(size_t)e * Mp.lam + d];
+    }
+    for (int t = 0; t < nres; t++) {
+        table[t].resize((size_t)E * p[t] * rows_pitch);
+        if (fread(table[t].data(), 1, table[t].size(), f) != table[t].size()) return 2;
+        out[t].assign(out_bytes, 0xEE);
+        DigitsRes& R = L.res[t];
+        R.p = (uint32_t)p[t]; R.slot0 = (uint32_t)(slot0 + t * n);
+        R.in = LView{act[t].data(), (int64_t)16 * E, 16u};
+        R.table = table[t].data(); R.out = out[t].data();
+    }
+    fclose(f);
+    HostTab T;
+    const uint32_t tiles = (E + kThreads - 1) / kThreads;
+    for (uint32_t by = 0; by < (uint32_t)nres; by++)
+        for (uint32_t bx = 0; bx < tiles; bx++)
+            for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
+                if (variant == 1) digits_eval_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T);
+                else if (variant == 2) digits_eval_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T);
+                else digits_eval_body<ModInfo, ModInfo>(L, bx, by, tx, T);
+            }
+    f = fopen(argv[2], "wb");
+    if (!f) return 2;
+    for (int t = 0; t < nres; t++)
+        for (int j = 1; j <= n; j++) {
+            const ModInfo& M = mods[m[j]];
+            std::vector<uint8_t> c((size_t)E * M.lam);
+            const uint8_t* base = out[t].data() + L.out_prefix[j];
+            for (uint32_t e = 0; e < E; e++)
+                for (uint32_t d = 0; d < M.lam; d++) c[(size_t)e * M.lam + d] = base[((size_t)(d / 16) * E + e) * 16 + d % 16];
+            // digits past lambda must have been cleared
+            for (uint32_t e = 0; e < E; e++)
+                for (uint32_t d = M.lam; d < M.nchunk * 16; d++)
+                    if (base[((size_t)(d / 16) * E + e) * 16 + d % 16] != 0) return 3;
+            fwrite(c.data(), 1, c.size(), f);
+        }
+    fclose(f);
+    return 0;
+}

@@ -119,3 +119,60 @@ def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
     run_chain(chain_emul, tmp_path, [2, 15, 27], 0, 65)
     run_chain(chain_emul, tmp_path, [4, 60, 56], 0, 33, rule=1)
     run_chain(chain_emul, tmp_path, [26, 96], 1, 5)                 # n = 2: no same-modulus step
+
+
+# ---- the evaluator's fused digit gates --------------------------------------------------------------
+DIGITS_EXE = os.path.join(HERE, "digits_emul.bin")
+
+
+@pytest.fixture(scope="module")
+def digits_emul():
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-o", DIGITS_EXE, os.path.join(HERE, "digits_emul.cpp")])
+    return DIGITS_EXE
+
+
+def run_digits(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):
+    """the n digit gates of every residue in one pass over its label: gate (t, j) is an ordinary projection gate
+    p_t -> m_j with slot slot0 + t n + (j - 1) (Appendix, approximated sign), so every output must equal the
+    oracle's evaluation of that gate on the same table segment"""
+    orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
+    n = len(m)
+    g = np.random.default_rng(sum(m) + n_elem + len(primes))
+    acts = [workloads.uniform_labels(g, n_elem, orc.lam(p), p) for p in primes]
+    tabs = []
+    for p in primes:
+        row = []
+        for mj in m:
+            lam_o = orc.lam(mj)
+            t = np.zeros((n_elem, p, capi.pitch(lam_o)), np.uint8)
+            t[:, :, :lam_o] = g.integers(0, mj, (n_elem, p, lam_o))
+            row.append(t)
+        tabs.append(row)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 0, elem_base)
+    blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % len(primes), *primes)
+    blob += b"".join(a.tobytes() for a in acts)
+    blob += b"".join(t.tobytes() for row in tabs for t in row)
+    fin, fout = str(tmp_path / "din.bin"), str(tmp_path / "dout.bin")
+    open(fin, "wb").write(blob)
+    r = subprocess.run([digits_emul, fin, fout], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr[-3000:])
+    got = np.fromfile(fout, np.uint8)
+    at = 0
+    for t, p in enumerate(primes):
+        for j, mj in enumerate(m):
+            lam_o = orc.lam(mj)
+            want = orc.proj_eval(p, mj, acts[t], tabs[t][j], layer, slot0 + t * n + j, elem_base)
+            assert (got[at:at + n_elem * lam_o].reshape(n_elem, lam_o) == want).all(), (p, mj)
+            at += n_elem * lam_o
+    assert at == got.size
+
+
+def test_digit_gate_bodies_under_sanitizers(digits_emul, tmp_path):
+    run_digits(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 300)
+    run_digits(digits_emul, tmp_path, [3, 19], [26] + [96] * 6, 0, 70)
+    run_digits(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 260)
+    run_digits(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
+    run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
+    run_digits(digits_emul, tmp_path, [13], [26], 0, 5)                 # one digit, one residue
+    run_digits(digits_emul, tmp_path, [5, 7], [26, 12, 12], 0, 100)      # a reduced-accuracy set
