@@ -282,6 +282,53 @@ DASH_HD void digits_eval_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, u
     }
 }
 
+// ---- garbler, digit gates of the sign gadget ---------------------------------------------------
+// One lane per (element g, value a) of a residue: the label of a is formed and compressed once, then one
+// ciphertext row per digit: rows[colour] = out0 + phi_j(a) R_{m_j} + H_{m_j}(label, slot_j).
+template <class MO, class Tab>
+DASH_HD void digit_row(const DigitsLaunch& L, const DigitsRes& R, const MO& Mo, const U128& K, uint32_t colour, uint32_t g, uint32_t a, int j,
+                       const Tab& T) {
+    uint8_t* seg = R.table + (size_t)L.n_elem * R.p * L.row_prefix[j];
+    uint32_t* row = (uint32_t*)(seg + ((size_t)g * R.p + colour) * (Mo.ndw * 4));
+    const LView out0{R.out + L.out_prefix[j], L.out_cs, 16u};
+    const uint32_t f = R.phi[(size_t)(j - 1) * R.p + a];
+    const uint32_t* df = Mo.dtab + f * Mo.ndw;
+    U128 h = hash_block(K, L.elem_base + g, R.slot0 + (uint32_t)(j - 1), L.layer, L.key.rk, T);
+    if constexpr (cmod_m<MO>::value != 0) {
+        uint32_t pay[MO::ndw];
+#pragma unroll
+        for (int i = 0; i < (int)MO::ndw; i++) pay[i] = addmod4(ld_dw(out0, g, i), gload32(df + i), Mo);
+        decompress(Mo, h, [&](int i, uint32_t hd) { row[i] = addmod4(pay[i], hd, Mo); });
+    } else {
+        decompress(Mo, h, [&](int i, uint32_t hd) { row[i] = addmod4(addmod4(ld_dw(out0, g, i), gload32(df + i), Mo), hd, Mo); });
+    }
+}
+template <class MC, class M1, class Tab>
+DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+    const DigitsRes& R = L.res[by];
+    const ModInfo Mp = L.mods[R.p];
+    const uint64_t r0 = (uint64_t)bx * kThreads;
+    if (r0 >= (uint64_t)L.n_elem * Mp.m) return;
+    const uint32_t g0 = (uint32_t)(r0 / Mp.m);
+    const uint32_t off = (uint32_t)(r0 - (uint64_t)g0 * Mp.m) + tx;
+    const uint32_t dg = div_m(off, Mp);
+    const uint32_t g = g0 + dg, a = off - dg * Mp.m;
+    if (g >= L.n_elem) return;
+    uint32_t colour = 0;
+    U128 K = {{0, 0, 0, 0}};
+    with_mod(Mp, [&](auto P) {
+        const uint32_t* da = P.dtab + a * P.ndw;
+        K = compress(P, [&](int i) { return addmod4(ld_dw(R.in, g, i), gload32(da + i), P); }, &colour);
+    });
+    if constexpr (cmod_m<MC>::value != 0) {
+        digit_row(L, R, M1{L.mods[L.m[1]].dtab}, K, colour, g, a, 1, T);
+        const MC Mc{L.mods[L.m[2]].dtab};
+        for (int j = 2; j <= (int)L.n; j++) digit_row(L, R, Mc, K, colour, g, a, j, T);
+    } else {
+        for (int j = 1; j <= (int)L.n; j++) digit_row(L, R, L.mods[L.m[j]], K, colour, g, a, j, T);
+    }
+}
+
 // evaluator side of the mixed-modulus half gate: z = V + beta * x - U
 template <class Tab>
 DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {

@@ -120,15 +120,16 @@ struct ChainLaunch {
     LView bit;                           // output wire (Z_2)
 };
 
-// evaluator side of the digit gates of one sign gadget (Appendix, approximated sign: residue i -> digit j of its
+// the digit gates of one sign gadget (Appendix, approximated sign: residue i -> digit j of its
 // rounded CRT fraction): the n gates of a residue share their input label, so one lane takes (element, residue),
-// compresses the label once and evaluates its n gates.  Output wire (i, j) and table segment (i, j) are at fixed
+// compresses the label once and evaluates its n gates (the garbler: one lane per (element, value a, residue)).  Output wire (i, j) and table segment (i, j) are at fixed
 // offsets from those of (i, 1).
 struct DigitsRes {
     uint32_t p, slot0;       // input modulus; slot of the gate to digit 1 (digit j: slot0 + j - 1)
-    LView in;                // active label of the residue
+    LView in;                // label of the residue: active (evaluator) or zero label (garbler)
     uint8_t* table;          // segment of gate (i, 1)
     uint8_t* out;            // label tensor of wire (i, 1)
+    const uint8_t* phi;      // garbler: function tables [n][p] of the residue's gates
 };
 struct DigitsLaunch {
     AesKey key;

@@ -163,16 +163,10 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         if (db.status) return db.status;
     }
     GateBatcher gb(c, garble, E, layer, elem_base, s);
-    // digit gates: residue i -> digit j of its rounded CRT fraction
-    if (garble) {
-        for (int i = first_res; i < k; i++)
-            for (int j = 1; j <= n; j++) {
-                int sl = i * n + (j - 1);
-                gb.add(phi_job(c->prime[i], c->mj[j], x[i], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]));
-            }
-        gb.flush();
-    } else {
-        // evaluator: the n gates of a residue share their input label; one launch for all k n gates
+    // digit gates: residue i -> digit j of its rounded CRT fraction.  The n gates of a residue share their input
+    // label: one launch for all k n gates, whose lanes form and compress a label once for n rows (garbler) or n
+    // gates (evaluator).
+    {
         DigitsLaunch DL;
         memset(&DL, 0, sizeof(DL));
         DL.n_elem = E; DL.layer = layer; DL.elem_base = elem_base; DL.n = (uint32_t)n; DL.nres = (uint32_t)(k - first_res);
@@ -185,13 +179,14 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         for (int i = first_res; i < k; i++) {
             DigitsRes& R = DL.res[i - first_res];
             R.p = (uint32_t)c->prime[i]; R.slot0 = slot_base + (uint32_t)(i * n); R.in = x[i];
-            R.table = seg + off[i * n]; R.out = w.A[i][1].p;
-            for (int j = 1; j <= n; j++) {     // the kernel's address rule must be the layout planned above
+            R.table = seg + off[i * n]; R.out = w.A[i][1].p; R.phi = c->phi_digit[i][1];
+            for (int j = 1; j <= n; j++) {     // the kernels' address rules must be the layout planned above
                 if (off[i * n + j - 1] != off[i * n] + (size_t)E * c->prime[i] * DL.row_prefix[j]) return DASH_EINVAL;
                 if (w.A[i][j].p != R.out + DL.out_prefix[j] || w.A[i][j].cs != DL.out_cs || w.A[i][j].es != 16u) return DASH_EINVAL;
+                if (c->phi_digit[i][j] != R.phi + (size_t)(j - 1) * c->prime[i]) return DASH_EINVAL;
             }
         }
-        const int st = launch_digits_eval(c, DL, s);
+        const int st = garble ? launch_digits_garble(c, DL, s) : launch_digits_eval(c, DL, s);
         if (st) return st;
     }
     // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1

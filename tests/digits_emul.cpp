@@ -1,12 +1,17 @@
-// Host emulation of the evaluator's fused digit-gate kernel: runs digits_eval_body (the code the __global__
-// kernel calls) lane by lane over exactly-sized host buffers under the sanitizers.  Test code, not part of libdash.
+// Host emulation of the fused digit-gate kernels: runs digits_eval_body / digits_garble_body (the code the
+// __global__ kernels call) lane by lane over exactly-sized host buffers under the sanitizers.  Test code, not part
+// of libdash.
 //
 // usage: digits_emul <in.bin> <out.bin>
-//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 pad; uint64 elem_base;
+//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 garble; uint64 elem_base;
 //        int32 m[n] (digit 1..n); int32 p[nres];
-//        for t < nres: u8 act_t[n_elem][lam(p_t)];
+//        for t < nres: u8 label_t[n_elem][lam(p_t)]            (active labels; garble: zero labels)
+//      evaluate:
 //        for t < nres, j = 1..n: u8 table_tj[n_elem][p_t][pitch(m_j)]
-//   out: for t < nres, j = 1..n: u8 out_tj[n_elem][lam(m_j)]
+//      garble:
+//        for t < nres: u8 delta_t[lam(p_t)];  for j: u8 delta_mj[lam(m_j)];
+//        for t < nres, j: u8 out0_tj[n_elem][lam(m_j)];  for t < nres: u8 phi_t[n][p_t]
+//   out: evaluate: for t < nres, j = 1..n: u8 out_tj[n_elem][lam(m_j)];  garble: for t, j: table_tj
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -32,7 +37,7 @@ int main(int argc, char** argv) {
     int32_t hd[8];
     uint64_t elem_base;
     if (fread(hd, 4, 8, f) != 8 || fread(&elem_base, 8, 1, f) != 1) return 2;
-    const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6];
+    const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6], garble = hd[7];
     const uint32_t E = (uint32_t)hd[1];
     if (n < 1 || n > kMaxChain || nres < 1 || nres > 16) return 2;
     std::vector<int32_t> m(n + 1), p(nres);
@@ -66,17 +71,66 @@ int main(int argc, char** argv) {
         for (uint32_t e = 0; e < E; e++)
             for (uint32_t d = 0; d < Mp.lam; d++) act[t][((size_t)(d / 16) * E + e) * 16 + d % 16] = c[(size_t)e * Mp.lam + d];
     }
+    std::vector<std::vector<uint32_t>> dtab(256);
+    std::vector<std::vector<uint8_t>> phi(nres);
+    auto read_dtab = [&](int q) {
+        ModInfo& M = mods[q];
+        std::vector<uint8_t> delta(M.lam);
+        if (fread(delta.data(), 1, delta.size(), f) != delta.size()) exit(2);
+        dtab[q].assign((size_t)M.m * M.ndw, 0);
+        for (uint32_t a = 0; a < M.m; a++)
+            for (uint32_t d = 0; d < M.lam; d++) dtab[q][(size_t)a * M.ndw + d / 4] |= (uint32_t)((a * delta[d]) % M.m) << (8 * (d % 4));
+        M.dtab = dtab[q].data();
+    };
+    if (garble) {
+        for (int t = 0; t < nres; t++) read_dtab(p[t]);
+        for (int j = 1; j <= n; j++) read_dtab(m[j]);
+    }
     for (int t = 0; t < nres; t++) {
         table[t].resize((size_t)E * p[t] * rows_pitch);
-        if (fread(table[t].data(), 1, table[t].size(), f) != table[t].size()) return 2;
-        out[t].assign(out_bytes, 0xEE);
+        out[t].assign(out_bytes, garble ? 0 : 0xEE);
+        if (!garble) {
+            if (fread(table[t].data(), 1, table[t].size(), f) != table[t].size()) return 2;
+        } else {
+            memset(table[t].data(), 0xEE, table[t].size());
+            for (int j = 1; j <= n; j++) {
+                const ModInfo& M = mods[m[j]];
+                std::vector<uint8_t> c((size_t)E * M.lam);
+                if (fread(c.data(), 1, c.size(), f) != c.size()) return 2;
+                uint8_t* base = out[t].data() + L.out_prefix[j];
+                for (uint32_t e = 0; e < E; e++)
+                    for (uint32_t d = 0; d < M.lam; d++) base[((size_t)(d / 16) * E + e) * 16 + d % 16] = c[(size_t)e * M.lam + d];
+            }
+        }
         DigitsRes& R = L.res[t];
         R.p = (uint32_t)p[t]; R.slot0 = (uint32_t)(slot0 + t * n);
         R.in = LView{act[t].data(), (int64_t)16 * E, 16u};
         R.table = table[t].data(); R.out = out[t].data();
     }
+    if (garble)
+        for (int t = 0; t < nres; t++) {
+            phi[t].resize((size_t)n * p[t]);
+            if (fread(phi[t].data(), 1, phi[t].size(), f) != phi[t].size()) return 2;
+            L.res[t].phi = phi[t].data();
+        }
     fclose(f);
     HostTab T;
+    if (garble) {
+        for (uint32_t by = 0; by < (uint32_t)nres; by++) {
+            const uint32_t tiles = (uint32_t)(((uint64_t)E * p[by] + kThreads - 1) / kThreads);
+            for (uint32_t bx = 0; bx < tiles; bx++)
+                for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
+                    if (variant == 1) digits_garble_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T);
+                    else if (variant == 2) digits_garble_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T);
+                    else digits_garble_body<ModInfo, ModInfo>(L, bx, by, tx, T);
+                }
+        }
+        f = fopen(argv[2], "wb");
+        if (!f) return 2;
+        for (int t = 0; t < nres; t++) fwrite(table[t].data(), 1, table[t].size(), f);      // [j][e][a][pitch_j] per residue
+        fclose(f);
+        return 0;
+    }
     const uint32_t tiles = (E + kThreads - 1) / kThreads;
     for (uint32_t by = 0; by < (uint32_t)nres; by++)
         for (uint32_t bx = 0; bx < tiles; bx++)

@@ -176,3 +176,42 @@ def test_digit_gate_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5)                 # one digit, one residue
     run_digits(digits_emul, tmp_path, [5, 7], [26, 12, 12], 0, 100)      # a reduced-accuracy set
+
+
+def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):
+    """the garbler's side of the same gates: rows[colour(l0 + a R_p)] = out0 + phi_j(a) R_{m_j} + H(l0 + a R_p), every
+    table segment against the oracle's projection gate with the same zero labels and function table"""
+    orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
+    n = len(m)
+    g = np.random.default_rng(7 * sum(m) + n_elem + len(primes))
+    in0 = [workloads.uniform_labels(g, n_elem, orc.lam(p), p) for p in primes]
+    phis = [np.stack([g.integers(0, mj, p).astype(np.uint8) for mj in m]) for p in primes]
+    want = [[orc.proj_garble(p, mj, in0[t], phis[t][j], layer, slot0 + t * n + j, elem_base) for j, mj in enumerate(m)]
+            for t, p in enumerate(primes)]
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 1, elem_base)
+    blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % len(primes), *primes)
+    blob += b"".join(a.tobytes() for a in in0)
+    blob += b"".join(orc.delta(p).tobytes() for p in primes) + b"".join(orc.delta(mj).tobytes() for mj in m)
+    blob += b"".join(want[t][j][0].tobytes() for t in range(len(primes)) for j in range(n))
+    blob += b"".join(ph.tobytes() for ph in phis)
+    fin, fout = str(tmp_path / "gin.bin"), str(tmp_path / "gout.bin")
+    open(fin, "wb").write(blob)
+    r = subprocess.run([digits_emul, fin, fout], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr[-3000:])
+    got = np.fromfile(fout, np.uint8)
+    at = 0
+    for t, p in enumerate(primes):
+        for j, mj in enumerate(m):
+            size = n_elem * p * capi.pitch(orc.lam(mj))
+            assert (got[at:at + size] == want[t][j][1].reshape(-1)).all(), (p, mj)
+            at += size
+    assert at == got.size
+
+
+def test_digit_row_bodies_under_sanitizers(digits_emul, tmp_path):
+    run_digits_garble(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 150)
+    run_digits_garble(digits_emul, tmp_path, [3, 19], [26] + [96] * 6, 0, 70)
+    run_digits_garble(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 130)
+    run_digits_garble(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
+    run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
+    run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5)
