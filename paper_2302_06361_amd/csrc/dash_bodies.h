@@ -184,6 +184,12 @@ DASH_HD void chain_gate(const ChainLaunch& L, const MI& Mi, const MO& Mo, uint32
     }
 }
 
+// dword i of the final gate's output: the sign bit wire, and (scaling gadget) the same wire plus a constant
+DASH_HD void chain_out(const ChainLaunch& L, uint32_t e, int i, uint32_t w) {
+    st_dw(L.bit, e, i, w);
+    if (L.up.p) st_dw(L.up, e, i, L.up_coef ? addmod4(w, ld_dw(L.up_one, e, i), CMod<2, 128>{nullptr}) : w);
+}
+
 // Digit sets whose digits 2..n share one accumulation modulus (description MC) and whose first digit has
 // description M1, both fixed at compile time: the carry label stays in registers from gate to gate.
 template <class MC, class M1, class Tab>
@@ -213,7 +219,7 @@ DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, con
         uint32_t in[M1::ndw];
 #pragma unroll
         for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(ld_dw(L.sum[1], e, i), c1[i], Mf);
-        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { st_dw(L.bit, e, i, w); }, T);
+        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { chain_out(L, e, i, w); }, T);
     }
 }
 
@@ -237,7 +243,7 @@ DASH_HD void chain_eval_generic_body(const ChainLaunch& L, uint32_t bx, uint32_t
             for (int i = (int)Mo.ndw; i < (int)Mo.nchunk * 4; i++) st_dw(L.carry[j - 1], e, i, 0);
         } else {
             const CMod<2, 128> M2{nullptr};
-            chain_gate(L, Mi, M2, e, 1, in_dw, [&](int i, uint32_t w) { st_dw(L.bit, e, i, w); }, T);
+            chain_gate(L, Mi, M2, e, 1, in_dw, [&](int i, uint32_t w) { chain_out(L, e, i, w); }, T);
         }
     }
 }
@@ -327,6 +333,33 @@ DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by,
     } else {
         for (int j = 1; j <= (int)L.n; j++) digit_row(L, R, L.mods[L.m[j]], K, colour, g, a, j, T);
     }
+}
+
+// evaluator, scaling gadget: cast = rows[colour(y)] - H_p(y) (two-row gate Z_2 -> Z_p, identity function), then
+// b = (x + addc * one - cast) * 2^-1 mod p.  The cast label itself is not stored.
+template <class Tab>
+DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+    const CastJob& J = L.jobs[by];
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem) return;
+    const ModInfo Mp = L.mods[J.p];
+    uint32_t colour = 0;
+    U128 K = compress(CMod<2, 128>{nullptr}, [&](int i) { return ld_dw(L.y, e, i); }, &colour);
+    U128 h = hash_block(K, L.elem_base + e, J.slot, L.layer, L.key.rk, T);
+    const uint32_t inv2 = (J.p + 1) / 2;
+    with_mod(Mp, [&](auto P) {
+        const uint32_t* row = (const uint32_t*)(J.table + ((size_t)e * 2 + colour) * (P.ndw * 4));
+        decompress(P, h, [&](int i, uint32_t hd) {
+            const uint32_t cast = submod4(row[i], hd, P);
+            uint32_t x = ld_dw(J.x, e, i);
+            if (J.addc) x = axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
+            uint32_t b = 0;
+            // digits past lambda: x and cast are 0 there, and inv2 * p = 0 mod p
+            for (int b8 = 0; b8 < 4; b8++) b |= mod_m(mul24(inv2, byte_of(x, b8) + P.m - byte_of(cast, b8)), P) << (8 * b8);
+            st_dw(J.out, e, i, b);
+        });
+        for (int i = (int)P.ndw; i < (int)P.nchunk * 4; i++) st_dw(J.out, e, i, 0);
+    });
 }
 
 // evaluator side of the mixed-modulus half gate: z = V + beta * x - U

@@ -79,6 +79,7 @@ int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
         if (R.p < 2 || R.p > 255 || !c->mods[R.p].dtab || !R.in.p || !R.table || !R.out) return DASH_EINVAL;
         for (uint32_t j = 1; j <= L.n; j++) bytes += (double)L.n_elem * (c->mods[R.p].lam + 2.0 * c->mods[L.m[j]].lam);
     }
+    // (by lanes, not by hashes: with n hashes per lane the 64 KB tables were still measured slower below this size)
     const bool banked = (uint64_t)L.n_elem * L.nres >= c->banked_min_lanes;
     dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)L.nres, banked), L.nres);
     const dim3 block(banked ? kBigThreads : kThreads);
@@ -140,6 +141,37 @@ int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
         hipLaunchKernelGGL((k_chain_eval<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
     else
         hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+// ----------------------------------------------------------------------------- scaling gadget, evaluator
+// cast of the mod-2 residue into every odd prime and the halving, one launch (a gate launch and a free-gate launch
+// before), blockIdx.y = odd prime.  (One lane per element that walks over the primes, compressing the 128-digit label
+// once, was measured three times slower: too few lanes.)
+__global__ __launch_bounds__(kThreads) void k_cast_halve(const CastLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) cast_halve_body(L, tile, blockIdx.y, threadIdx.x, T);
+}
+
+int launch_cast_halve(const dash_ctx* c, CastLaunch& L, int njobs, hipStream_t s) {
+    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    if (!L.y.p) return DASH_EINVAL;
+    double bytes = 0;
+    for (int j = 0; j < njobs; j++) {
+        const CastJob& J = L.jobs[j];
+        if (J.p < 3 || J.p > 255 || !(J.p & 1) || !c->mods[J.p].dtab || J.addc >= J.p) return DASH_EINVAL;
+        if (!J.table || !J.x.p || !J.out.p || (J.addc && !J.one.p)) return DASH_EINVAL;
+        bytes += (double)L.n_elem * (128 + 2.0 * c->mods[J.p].lam);
+    }
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs), njobs);
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
+    hipLaunchKernelGGL(k_cast_halve, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

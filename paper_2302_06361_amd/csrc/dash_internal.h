@@ -76,6 +76,7 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s);
 int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s);
 int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
 int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
+int launch_cast_halve(const dash_ctx* c, CastLaunch& L, int njobs, hipStream_t s);
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
 
 // layer pipelines (dash_layers.hip)

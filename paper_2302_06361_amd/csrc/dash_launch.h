@@ -118,6 +118,28 @@ struct ChainLaunch {
     LView sum[kMaxChain + 1];            // free sum of the digit wires of digit j, WITHOUT the carry
     LView carry[kMaxChain + 1];          // carry into digit j (j < n): written by gate j+1, read back by the same lane
     LView bit;                           // output wire (Z_2)
+    // optional second output: up = bit + up_coef * up_one (the shifts of the scaling gadget on the mod-2 residue)
+    LView up, up_one;
+    uint32_t up_coef, pad_;
+};
+
+// evaluator, scaling gadget (Sec. Scaling in the CRT representation): cast of the mod-2 wire y into Z_p (a two-row
+// gate) and the halving that uses it, b = (x + addc * one - cast) / 2 mod p, one lane per (element, odd prime)
+struct CastJob {
+    uint32_t p, slot;
+    uint8_t* table;          // [elem][2][pitch_p]
+    LView x, one, out;       // residue of the value, constant-one wire of the prime, b
+    uint32_t addc, pad_;     // constant added to x first (the ShiftDown of the repetition before), in [0, p)
+};
+struct CastLaunch {
+    AesKey key;
+    const uint32_t* ttab;
+    const ModInfo* mods;
+    uint64_t elem_base;
+    uint32_t layer;
+    uint32_t n_elem;
+    LView y;
+    CastJob jobs[kMaxJobs];
 };
 
 // the digit gates of one sign gadget (Appendix, approximated sign: residue i -> digit j of its

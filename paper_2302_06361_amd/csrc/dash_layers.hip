@@ -147,8 +147,10 @@ GateJob phi_job(int p, int q, LView in, const uint8_t* phi, uint32_t slot, LView
 // One sign gadget over E elements.  x[i]: input residues (i >= first_res).  seg: start of the gadget's
 // first segment inside the layer table (already offset for the element count), offsets per slot follow
 // the slot order.  On return w.bit holds [X >= P/2] (negate = 0) or its complement.
+// up (evaluator, optional): a second output wire, bit + up_coef * up_one.
 int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
-              int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s) {
+              int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s, const LView* up = nullptr,
+              const LView* up_one = nullptr, uint32_t up_coef = 0) {
     const int k = c->k, n = c->n;
     size_t off[DASH_MAX_PRIMES * DASH_MAX_DIGITS + DASH_MAX_DIGITS], cum = 0;
     for (int sl = 0; sl < sign_nslots(c); sl++) { off[sl] = cum * E; cum += sign_slot_bytes(c, sl, first_res); }
@@ -241,6 +243,7 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
             if (j < n) CL.carry[j] = w.C[j];
         }
         CL.bit = w.bit;
+        if (up) { CL.up = *up; CL.up_one = *up_one; CL.up_coef = up_coef; }
         return launch_chain_eval(c, CL, s);
     }
     for (int j = n; j >= 1; j--) {
@@ -250,6 +253,13 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         if (ab.status) return ab.status;
         chain_gate(j);
         gb.flush();
+    }
+    if (up && gb.status == DASH_OK) {      // single-digit sets: no fused chain, a free-gate launch instead
+        AffineBatcher ab(c, E, s);
+        Term t[2] = {Term{w.bit, 1}, Term{*up_one, up_coef}};
+        ab.add(2, *up, t, 2);
+        ab.flush();
+        return ab.status;
     }
     return gb.status;
 }
@@ -400,6 +410,68 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
     LView one[DASH_MAX_PRIMES];
     for (int i = 0; i < k; i++) one[i] = LView{garble ? c->d_one0[i] : c->d_one[i], 16, 0u};
     const uint64_t quarter = c->P / 4;
+
+    if (!garble) {
+        // Evaluator: per repetition a cast-and-halve launch (two-row gates and b_i = (x_i - cast_i) / 2 together), the
+        // sign gadget (whose last launch also writes the next repetition's shifted mod-2 wire), and nothing else: the
+        // ShiftDown of the odd residues is a constant that the next repetition's halving adds first; only the last
+        // repetition writes it out.
+        LView x[DASH_MAX_PRIMES];
+        for (int i = 0; i < k; i++) x[i] = view_of(in, i);
+        const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
+        {
+            AffineBatcher ab(c, E, s);
+            Term t[2] = {Term{x[0], 1}, Term{one[0], 1}};
+            ab.add(2, pl.up, t, 2);
+            ab.flush();
+            if (ab.status) return ab.status;
+        }
+        for (int rep = 0; rep < L->repeat; rep++) {
+            uint8_t* tb = tables + (size_t)rep * bpe * E;
+            const uint32_t sb = rep * slots_per_rep;
+            const bool last = rep == L->repeat - 1;
+            // b of this repetition alternates between two buffer sets (the halving reads the one before)
+            LView* bnew = rep & 1 ? pl.buf[0] : pl.b;
+            const LView* bold = rep & 1 ? pl.b : pl.buf[0];
+            CastLaunch CL;
+            memset(&CL, 0, sizeof(CL));
+            CL.n_elem = E; CL.layer = layer; CL.elem_base = eb; CL.y = pl.up;
+            size_t cum = 0;
+            int nj = 0;
+            for (int i = 1; i < k; i++) {
+                const uint32_t p = c->prime[i];
+                CastJob& J = CL.jobs[nj++];
+                J.p = p; J.slot = sb + (i - 1); J.table = tb + cum * E;
+                J.x = rep == 0 ? x[i] : bold[i];
+                J.one = one[i];
+                J.addc = rep == 0 ? 0u : (uint32_t)((p - quarter % p) % p);
+                J.out = bnew[i];
+                cum += 2 * pitch_of(c, p);
+                if (nj == kMaxJobs || i == k - 1) {
+                    const int st = launch_cast_halve(c, CL, nj, s);
+                    if (st) return st;
+                    nj = 0;
+                }
+            }
+            const uint32_t upc = (c0 + 1) % 2;
+            int st = sign_core(c, false, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
+                               last ? nullptr : &one[0], upc);
+            if (st) return st;
+            if (last) {
+                AffineBatcher ab(c, E, s);
+                Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};
+                ab.add(2, view_of(out, 0), t0, 2);
+                for (int i = 1; i < k; i++) {
+                    uint32_t p = c->prime[i];
+                    Term t[2] = {Term{bnew[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};
+                    ab.add(p, view_of(out, i), t, 2);
+                }
+                ab.flush();
+                if (ab.status) return ab.status;
+            }
+        }
+        return DASH_OK;
+    }
 
     LView cur[DASH_MAX_PRIMES];
     for (int i = 0; i < k; i++) cur[i] = view_of(in, i);
