@@ -24,11 +24,12 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
 ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 # Figures taken from the rocprofv3 --pmc runs of this same command (profiles/k_proj_garble_lenet_b16_pmc.txt):
-# vector instructions per ciphertext row of k_proj_garble / per gate of the evaluator's gate kernels, averaged over
+# vector instructions per ciphertext row of k_proj_garble and of k_digits_garble / per gate of the evaluator's gate kernels, averaged over
 # the launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per row (FETCH_SIZE,
 # WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up: 2.0 and 1.0).
-PMC = dict(garble_valu_per_row=804.5, eval_valu_per_gate=744.7,
-           garble_fetch_bytes_per_row=6.33, garble_write_bytes_per_row=25.97)
+PMC = dict(garble_valu_per_row=792.5, digits_valu_per_row=636.8, eval_valu_per_gate=654.2,
+           garble_fetch_bytes_per_row=4.27, garble_write_bytes_per_row=29.82,
+           digits_fetch_bytes_per_row=4.62, digits_write_bytes_per_row=21.47)
 
 
 def gate_counts(net, k, n_digits):
@@ -105,7 +106,7 @@ def kernel_line(pr, steps, bytes_per_unit_note=None):
 
 
 def read_profiles(ctx):
-    return {name: ctx.profile_read(kind) for name, kind in (("garble", 0), ("eval", 1), ("linear", 2))}
+    return {name: ctx.profile_read(kind) for name, kind in (("garble", 0), ("eval", 1), ("linear", 2), ("garble_digits", 3))}
 
 
 def micro_projection(torch, workloads, reps=2):
@@ -346,19 +347,25 @@ def main():
     ctx.profile_enable(False)
     prof = read_profiles(ctx)
 
-    kg, ke, kl = (kernel_line(prof[n_], a.steps) for n_ in ("garble", "eval", "linear"))
-    valu = PMC["garble_valu_per_row"]
-    roofline = dict(
-        kernel="k_proj_garble", bound="alu", unit="Tlane-instr/s (32-bit integer vector instructions)", peak=ALU_PEAK_TOPS,
-        achieved=kg["units_per_s"] * valu / 1e12 if valu else None,
-        avg_launch_ms=kg["avg_launch_ms"], launches_per_step=kg["launches_per_step"],
-        rows_per_launch=kg["units_per_launch"], rows_per_s=kg["units_per_s"], lane_ops_per_row=valu,
-        hbm_algorithmic_GBps=kg["gbytes_per_s"], hbm_frac=kg["gbytes_per_s"] / HBM_PEAK_GBS,
-        algorithmic_bytes_per_launch=kg["bytes_per_launch"],
-        traffic=(PMC["garble_fetch_bytes_per_row"] + PMC["garble_write_bytes_per_row"]) * kg["units_per_launch"])
-    roofline["frac"] = roofline["achieved"] / ALU_PEAK_TOPS if roofline["achieved"] else None
+    kg, ke, kl, kd = (kernel_line(prof[n_], a.steps) for n_ in ("garble", "eval", "linear", "garble_digits"))
+
+    def garble_roofline(kernel, kk, valu, traffic_per_row):
+        r = dict(kernel=kernel, bound="alu", unit="Tlane-instr/s (32-bit integer vector instructions)", peak=ALU_PEAK_TOPS,
+                 achieved=kk["units_per_s"] * valu / 1e12, ms_per_step=kk["ms_per_step"],
+                 avg_launch_ms=kk["avg_launch_ms"], launches_per_step=kk["launches_per_step"],
+                 rows_per_launch=kk["units_per_launch"], rows_per_s=kk["units_per_s"], lane_ops_per_row=valu,
+                 hbm_algorithmic_GBps=kk["gbytes_per_s"], hbm_frac=kk["gbytes_per_s"] / HBM_PEAK_GBS,
+                 algorithmic_bytes_per_launch=kk["bytes_per_launch"], traffic=traffic_per_row * kk["units_per_launch"])
+        r["frac"] = r["achieved"] / ALU_PEAK_TOPS
+        return r
+    # the dominant kernel of the step: the general projection-gate garbler (carry chains, half gates, casts); the
+    # digit gates of the sign gadgets run in the fused kernel, reported beside it
+    roofline = garble_roofline("k_proj_garble", kg, PMC["garble_valu_per_row"],
+                               PMC["garble_fetch_bytes_per_row"] + PMC["garble_write_bytes_per_row"])
+    roofline_digits = garble_roofline("k_digits_garble", kd, PMC["digits_valu_per_row"],
+                                      PMC["digits_fetch_bytes_per_row"] + PMC["digits_write_bytes_per_row"]) if kd else None
     ev_valu = PMC["eval_valu_per_gate"]
-    roofline_eval = dict(kernel="k_proj_eval", bound="alu", unit=roofline["unit"], peak=ALU_PEAK_TOPS,
+    roofline_eval = dict(kernel="k_digits_eval + k_chain_eval + k_cast_halve + k_proj_eval", bound="alu", unit=roofline["unit"], peak=ALU_PEAK_TOPS,
                          achieved=ke["units_per_s"] * ev_valu / 1e12 if ev_valu else None,
                          avg_launch_ms=ke["avg_launch_ms"], launches_per_step=ke["launches_per_step"],
                          gates_per_s=ke["units_per_s"], hbm_algorithmic_GBps=ke["gbytes_per_s"],
@@ -382,7 +389,7 @@ def main():
         ms_per_inference_garble=phase[0] / a.batch,
         phase_ms=dict(garble=phase[0], encode=phase[1], eval=phase[2], decode=phase[3]),
         gates_per_step=gates, label_macs_per_step=2 * macs,
-        roofline=roofline, roofline_eval_kernel=roofline_eval,
+        roofline=roofline, roofline_digits_kernel=roofline_digits, roofline_eval_kernel=roofline_eval,
         linear_kernels_config2=dict(ms_per_step=kl["ms_per_step"], label_mac_per_s=kl["units_per_s"],
                                     note="config-2 linear layers are tiny (launch-bound); config 4 below is the contraction figure"),
     )

@@ -284,7 +284,10 @@ DASH_HD void digits_eval_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, u
         const MC Mc{nullptr};
         for (int j = 2; j <= (int)L.n; j++) digit_gate(L, R, Mc, K, colour, e, j, T);
     } else {
-        for (int j = 1; j <= (int)L.n; j++) digit_gate(L, R, L.mods[L.m[j]], K, colour, e, j, T);
+        for (int j = 1; j <= (int)L.n; j++) {
+            const ModInfo Mo = L.mods[L.m[j]];      // a copy in registers: through the reference every use is a load
+            digit_gate(L, R, Mo, K, colour, e, j, T);
+        }
     }
 }
 
@@ -331,7 +334,10 @@ DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by,
         const MC Mc{L.mods[L.m[2]].dtab};
         for (int j = 2; j <= (int)L.n; j++) digit_row(L, R, Mc, K, colour, g, a, j, T);
     } else {
-        for (int j = 1; j <= (int)L.n; j++) digit_row(L, R, L.mods[L.m[j]], K, colour, g, a, j, T);
+        for (int j = 1; j <= (int)L.n; j++) {
+            const ModInfo Mo = L.mods[L.m[j]];      // a copy in registers: through the reference every use is a load
+            digit_row(L, R, Mo, K, colour, g, a, j, T);
+        }
     }
 }
 

@@ -181,6 +181,11 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     c->device = hip_device; c->k = k; c->rule = lambda_rule;
     c->banked_min_lanes = 1u << 20;
     if (const char* e = getenv("DASH_BANKED_MIN_LANES")) c->banked_min_lanes = strtoull(e, nullptr, 10);   // tuning and test hook
+    c->fused_min_elems[0] = 0; c->fused_min_elems[1] = 0;
+    c->digits_banked_min_lanes = 1u << 20;
+    if (const char* e = getenv("DASH_FUSED_MIN_ELEMS_GARBLE")) c->fused_min_elems[0] = strtoull(e, nullptr, 10);
+    if (const char* e = getenv("DASH_FUSED_MIN_ELEMS_EVAL")) c->fused_min_elems[1] = strtoull(e, nullptr, 10);
+    if (const char* e = getenv("DASH_DIGITS_BANKED_MIN_LANES")) c->digits_banked_min_lanes = strtoull(e, nullptr, 10);
     c->prof = new (std::nothrow) ProfState();
     c->P = 1;
     for (int i = 0; i < k; i++) { c->prime[i] = primes[i]; c->P *= primes[i]; }

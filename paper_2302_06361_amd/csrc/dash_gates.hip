@@ -193,12 +193,12 @@ int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
         for (uint32_t j = 1; j <= L.n; j++) bytes += (double)L.n_elem * (c->mods[R.p].lam + (1.0 + R.p) * c->mods[L.m[j]].lam);
     }
     if (tiles > 0x7fffffffull) return DASH_ESIZE;
-    const bool banked = (uint64_t)(units / L.n) >= c->banked_min_lanes;
+    const bool banked = (uint64_t)(units / L.n) >= c->digits_banked_min_lanes;
     dim3 grid(gate_grid_x_for(tiles, 1, banked));
     const dim3 block(banked ? kBigThreads : kThreads);
     auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
     const ModInfo &M1 = c->mods[L.m[1]], &Mc = c->mods[L.m[L.n >= 2 ? 2 : 1]];
-    ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
+    ProfScope ps(c->prof, DASH_PROF_GARBLE_DIGITS, s, units, bytes);
     if (uniform && is(Mc, 96, 20) && is(M1, 26, 28)) {
         if (banked) hipLaunchKernelGGL((k_digits_garble<CMod<96, 20>, CMod<26, 28>, true>), grid, block, 0, s, L);
         else hipLaunchKernelGGL((k_digits_garble<CMod<96, 20>, CMod<26, 28>, false>), grid, block, 0, s, L);

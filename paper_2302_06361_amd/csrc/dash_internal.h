@@ -61,6 +61,9 @@ struct dash_ctx {
     const uint8_t* phi_ident;                                        // {0, 1}
     const uint8_t* d_zero;                                           // 256 zero bytes
     uint64_t banked_min_lanes;       // launches of this many lanes or more use the bank-replicated AES tables
+    uint64_t fused_min_elems[2];     // [garble, eval]: sign gadgets over this many elements or more run their digit gates in
+                                     // the fused kernels (a lane walks the n gates of a residue); smaller ones one gate per lane
+    uint64_t digits_banked_min_lanes;   // the banked-table threshold of the fused garbling kernel (n hashes per lane)
     const uint8_t* phi_pm1[DASH_MAX_PRIMES];                         // {1, p-1}
 };
 

@@ -167,8 +167,15 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     GateBatcher gb(c, garble, E, layer, elem_base, s);
     // digit gates: residue i -> digit j of its rounded CRT fraction.  The n gates of a residue share their input
     // label: one launch for all k n gates, whose lanes form and compress a label once for n rows (garbler) or n
-    // gates (evaluator).
-    {
+    // gates (evaluator).  Small gadgets keep one gate per lane (n times the lanes, a chain n times shorter).
+    if (E < c->fused_min_elems[garble ? 0 : 1]) {
+        for (int i = first_res; i < k; i++)
+            for (int j = 1; j <= n; j++) {
+                int sl = i * n + (j - 1);
+                gb.add(phi_job(c->prime[i], c->mj[j], x[i], c->phi_digit[i][j], slot_base + sl, w.A[i][j], seg + off[sl]));
+            }
+        gb.flush();
+    } else {
         DigitsLaunch DL;
         memset(&DL, 0, sizeof(DL));
         DL.n_elem = E; DL.layer = layer; DL.elem_base = elem_base; DL.n = (uint32_t)n; DL.nres = (uint32_t)(k - first_res);

@@ -72,6 +72,19 @@ def test_activation_base12(kind, repeat):
     run_activation(12, kind, X, repeat=repeat, elem_base=2 ** 32 + 7)
 
 
+def test_activation_one_gate_per_lane_digit_path(monkeypatch):
+    """the digit gates of the sign gadget through the general gate kernels (one gate per lane) instead of the fused
+    kernels: the path that gadgets below the size thresholds take; thresholds forced through their tuning hooks"""
+    monkeypatch.setenv("DASH_FUSED_MIN_ELEMS_GARBLE", "1000000000")
+    monkeypatch.setenv("DASH_FUSED_MIN_ELEMS_EVAL", "1000000000")
+    P8 = int(np.prod(workloads.PRIMES[:8]))
+    X = np.random.default_rng(77).integers(0, P8, 300)
+    run_activation(8, "relu", X)
+    run_activation(8, "scale", X, repeat=2)
+    P7 = int(np.prod(workloads.PRIMES[:7]))
+    run_activation(7, "scale", np.random.default_rng(78).integers(0, P7, 200), repeat=2, digits=workloads.DIGITS[7])
+
+
 def test_activation_floor_rule():
     P = int(np.prod(workloads.PRIMES[:5]))
     g = np.random.default_rng(5)
