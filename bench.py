@@ -227,8 +227,8 @@ def micro_vgg(torch, workloads, images=1, reps=2):
                images=images, ms=ms, ms_per_image=ms / images, outputs_valid=bool(g.valid.all().item()),
                table_bytes_per_image=g.table_bytes // images, gates_per_image=gates // images,
                gates_per_s=2 * gates / (ms * 1e-3), label_macs_per_image=2 * macs // images,
-               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_proj_eval=kernel_line(pr["eval"], reps),
-                            linear=kernel_line(pr["linear"], reps)))
+               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_digits_garble=kernel_line(pr["garble_digits"], reps),
+                            eval_kernels=kernel_line(pr["eval"], reps), linear=kernel_line(pr["linear"], reps)))
     ctx.close()
     torch.cuda.empty_cache()
     return out
