@@ -21,6 +21,11 @@ DASH_HD void st_dw(const LView& v, uint32_t e, int i, uint32_t w) {
     *(uint32_t*)(base + lane_off(v, e)) = w;
 }
 
+// a whole 16-digit chunk of element e at once (label tensors are 16-byte aligned): one 16-byte access
+struct alignas(16) Dw4 { uint32_t w[4]; };
+DASH_HD Dw4 ld_chunk(const LView& v, uint32_t e, int ch) { return *(const Dw4*)(v.p + (int64_t)ch * v.cs + lane_off(v, e)); }
+DASH_HD void st_chunk(const LView& v, uint32_t e, int ch, const Dw4& d) { *(Dw4*)(v.p + (int64_t)ch * v.cs + lane_off(v, e)) = d; }
+
 // PRG labels: one lane per (job, element)
 template <class Tab>
 DASH_HD void draw_body(const DrawLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
@@ -84,7 +89,6 @@ template <class QD, class Tab, class Sink>
 DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T, Sink& sink) {
     const GateJob& J = L.jobs[by];
     const ModInfo Mp = L.mods[J.p], Mq = L.mods[J.q];
-    const QD Q = make_mod<QD>::from(Mq);
     // The block's first row is divided once (scalar unit); the lane's offset from it is small enough
     // for the 24-bit magic division.
     const uint64_t r0 = (uint64_t)bx * kThreads;
@@ -104,36 +108,44 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
     });
     U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
 
-    if (J.mode == PAY_SHORT) {
-        uint32_t v = mod_m(a + J.r[g] + mod_u128(h, Q), Q);
-        *(uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * 4) = v;
-        return;
-    }
-    sink.begin(J.table, (uint64_t)g * Mp.m + colour, Q.ndw * 4);
-    if (J.mode == PAY_EHALF) {
-        uint32_t cf = mod_m(a + J.r[g], Q);
-        cf = cf ? Q.m - cf : 0;                          // minus (a + r) * x0
-        decompress(Q, h, [&](int i, uint32_t hd) {
-            uint32_t pay = axpymod4(ld_dw(J.out, g, i), cf, ld_dw(J.x0, g, i), Q);
-            sink.put(i, addmod4(pay, hd, Q));
-        });
-        return;
-    }
-    uint32_t f;
-    if (J.mode == PAY_MULR) f = mod_m(a * J.r[g], Q);
-    else f = J.phi[(size_t)g * J.phi_stride + a];
-    const uint32_t* df = Q.dtab + f * Q.ndw;
-    if constexpr (cmod_m<QD>::value != 0) {
-        // payload first (its loads do not wait behind the row stores), then one pass over the hash digits
-        uint32_t pay[QD::ndw];
+    // the output modulus: the kernel's compile-time description, or the run-time record (the instantiation for any
+    // modulus, which also serves launches that mix output moduli; choosing a compile-time description per job inside
+    // it, as eval_body does, was measured much slower here: the kernel then needs the registers of its largest case)
+    auto finish = [&](const auto& Q) {
+        typedef std::decay_t<decltype(Q)> QT;
+        if (J.mode == PAY_SHORT) {
+            uint32_t v = mod_m(a + J.r[g] + mod_u128(h, Q), Q);
+            *(uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * 4) = v;
+            return;
+        }
+        sink.begin(J.table, (uint64_t)g * Mp.m + colour, Q.ndw * 4);
+        if (J.mode == PAY_EHALF) {
+            uint32_t cf = mod_m(a + J.r[g], Q);
+            cf = cf ? Q.m - cf : 0;                          // minus (a + r) * x0
+            decompress(Q, h, [&](int i, uint32_t hd) {
+                uint32_t pay = axpymod4(ld_dw(J.out, g, i), cf, ld_dw(J.x0, g, i), Q);
+                sink.put(i, addmod4(pay, hd, Q));
+            });
+            return;
+        }
+        uint32_t f;
+        if (J.mode == PAY_MULR) f = mod_m(a * J.r[g], Q);
+        else f = J.phi[(size_t)g * J.phi_stride + a];
+        const uint32_t* df = Q.dtab + f * Q.ndw;
+        if constexpr (cmod_m<QT>::value != 0) {
+            // payload first (its loads do not wait behind the row stores), then one pass over the hash digits
+            uint32_t pay[QT::ndw];
 #pragma unroll
-        for (int i = 0; i < (int)QD::ndw; i++) pay[i] = addmod4(ld_dw(J.out, g, i), gload32(df + i), Q);
-        decompress(Q, h, [&](int i, uint32_t hd) { sink.put(i, addmod4(pay[i], hd, Q)); });
-    } else {
-        decompress(Q, h, [&](int i, uint32_t hd) {
-            sink.put(i, addmod4(addmod4(ld_dw(J.out, g, i), gload32(df + i), Q), hd, Q));
-        });
-    }
+            for (int i = 0; i < (int)QT::ndw; i++) pay[i] = addmod4(ld_dw(J.out, g, i), gload32(df + i), Q);
+            decompress(Q, h, [&](int i, uint32_t hd) { sink.put(i, addmod4(pay[i], hd, Q)); });
+        } else {
+            decompress(Q, h, [&](int i, uint32_t hd) {
+                sink.put(i, addmod4(addmod4(ld_dw(J.out, g, i), gload32(df + i), Q), hd, Q));
+            });
+        }
+    };
+    if constexpr (cmod_m<QD>::value != 0) finish(make_mod<QD>::from(Mq));
+    else finish(Mq);
 }
 
 // eval: one lane per gate
@@ -141,26 +153,31 @@ template <class QD, class Tab>
 DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
     const GateJob& J = L.jobs[by];
     const ModInfo Mp = L.mods[J.p], Mq = L.mods[J.q];
-    const QD Q = make_mod<QD>::from(Mq);
     uint32_t g = bx * kThreads + tx;
     if (g >= L.n_elem) return;
-    // the row is named by the colour (digit 0 of the label): its loads are issued before the hash, not after
     uint32_t colour = ld_dw(J.in, g, 0) & 0xffu;
-    const uint32_t* row = (const uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
-    uint32_t rw[cmod_ndw<QD>::value];
-    if constexpr (cmod_m<QD>::value != 0) {
-#pragma unroll
-        for (int i = 0; i < (int)QD::ndw; i++) rw[i] = row[i];
-    }
     U128 K = {{0, 0, 0, 0}};
     with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(J.in, g, i); }, &colour); });
-    U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
-    if constexpr (cmod_m<QD>::value != 0) {
-        decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(rw[i], hd, Q)); });
-    } else {
-        decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(row[i], hd, Q)); });
-    }
-    for (int i = (int)Q.ndw; i < (int)Q.nchunk * 4; i++) st_dw(J.out, g, i, 0);
+    // (the output modulus as in garble_body; the row is named by the colour, digit 0 of the label: its loads are issued
+    // before the hash, not after)
+    auto finish = [&](const auto& Q) {
+        typedef std::decay_t<decltype(Q)> QT;
+        const uint32_t* row = (const uint32_t*)(J.table + ((size_t)g * Mp.m + colour) * (Q.ndw * 4));
+        uint32_t rw[cmod_ndw<QT>::value];
+        if constexpr (cmod_m<QT>::value != 0) {
+#pragma unroll
+            for (int i = 0; i < (int)QT::ndw; i++) rw[i] = row[i];
+        }
+        U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
+        if constexpr (cmod_m<QT>::value != 0) {
+            decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(rw[i], hd, Q)); });
+        } else {
+            decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(row[i], hd, Q)); });
+        }
+        for (int i = (int)Q.ndw; i < (int)Q.nchunk * 4; i++) st_dw(J.out, g, i, 0);
+    };
+    if constexpr (cmod_m<QD>::value != 0) finish(make_mod<QD>::from(Mq));
+    else with_mod(Mq, finish);
 }
 
 // ---- evaluator, carry chain of the sign gadget ------------------------------------------------
@@ -219,7 +236,21 @@ DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, con
         uint32_t in[M1::ndw];
 #pragma unroll
         for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(ld_dw(L.sum[1], e, i), c1[i], Mf);
-        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { chain_out(L, e, i, w); }, T);
+        Dw4 bits[8];                                // the 128 digits of the output wire: stored 16 bytes at a time
+        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { bits[i >> 2].w[i & 3] = w; }, T);
+#pragma unroll
+        for (int ch = 0; ch < 8; ch++) st_chunk(L.bit, e, ch, bits[ch]);
+        if (L.up.p) {
+#pragma unroll
+            for (int ch = 0; ch < 8; ch++) {
+                if (L.up_coef) {
+                    const Dw4 ow = ld_chunk(L.up_one, e, ch);
+#pragma unroll
+                    for (int q = 0; q < 4; q++) bits[ch].w[q] = addmod4(bits[ch].w[q], ow.w[q], M2);
+                }
+                st_chunk(L.up, e, ch, bits[ch]);
+            }
+        }
     }
 }
 
@@ -354,17 +385,45 @@ DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint
     U128 h = hash_block(K, L.elem_base + e, J.slot, L.layer, L.key.rk, T);
     const uint32_t inv2 = (J.p + 1) / 2;
     with_mod(Mp, [&](auto P) {
+        typedef decltype(P) PD;
         const uint32_t* row = (const uint32_t*)(J.table + ((size_t)e * 2 + colour) * (P.ndw * 4));
-        decompress(P, h, [&](int i, uint32_t hd) {
-            const uint32_t cast = submod4(row[i], hd, P);
-            uint32_t x = ld_dw(J.x, e, i);
-            if (J.addc) x = axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
+        auto halve = [&](uint32_t x, uint32_t cast) {
             uint32_t b = 0;
             // digits past lambda: x and cast are 0 there, and inv2 * p = 0 mod p
             for (int b8 = 0; b8 < 4; b8++) b |= mod_m(mul24(inv2, byte_of(x, b8) + P.m - byte_of(cast, b8)), P) << (8 * b8);
-            st_dw(J.out, e, i, b);
-        });
-        for (int i = (int)P.ndw; i < (int)P.nchunk * 4; i++) st_dw(J.out, e, i, 0);
+            return b;
+        };
+        if constexpr (cmod_m<PD>::value != 0) {
+            // compile-time label length: everything in registers, 16-byte loads and stores
+            constexpr int ndw = (int)PD::ndw, nch = (int)PD::nchunk;
+            uint32_t rw[ndw];
+            Dw4 xw[nch];
+#pragma unroll
+            for (int i = 0; i < ndw; i++) rw[i] = row[i];
+#pragma unroll
+            for (int ch = 0; ch < nch; ch++) xw[ch] = ld_chunk(J.x, e, ch);
+            if (J.addc) {
+#pragma unroll
+                for (int ch = 0; ch < nch; ch++) {
+                    const Dw4 ow = ld_chunk(J.one, e, ch);
+#pragma unroll
+                    for (int q = 0; q < 4; q++) xw[ch].w[q] = axpymod4(xw[ch].w[q], J.addc, ow.w[q], P);
+                }
+            }
+            decompress(P, h, [&](int i, uint32_t hd) { xw[i >> 2].w[i & 3] = halve(xw[i >> 2].w[i & 3], submod4(rw[i], hd, P)); });
+#pragma unroll
+            for (int i = ndw; i < nch * 4; i++) xw[i >> 2].w[i & 3] = 0;
+#pragma unroll
+            for (int ch = 0; ch < nch; ch++) st_chunk(J.out, e, ch, xw[ch]);
+        } else {
+            decompress(P, h, [&](int i, uint32_t hd) {
+                const uint32_t cast = submod4(row[i], hd, P);
+                uint32_t x = ld_dw(J.x, e, i);
+                if (J.addc) x = axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
+                st_dw(J.out, e, i, halve(x, cast));
+            });
+            for (int i = (int)P.ndw; i < (int)P.nchunk * 4; i++) st_dw(J.out, e, i, 0);
+        }
     });
 }
 
