@@ -27,7 +27,8 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_draw(const DrawLa
 }
 
 int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
-    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
+    static_assert(sizeof(DrawLaunch) <= 4096, "kernel argument block");
+    if (njobs < 1 || njobs > kMaxDrawJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->seed; L.ttab = c->d_ttab; L.mods = c->d_mods;

@@ -8,6 +8,7 @@
 namespace dash {
 
 constexpr int kMaxJobs = 16;    // gate batches per launch (blockIdx.y)
+constexpr int kMaxDrawJobs = 80;   // label draws per launch: all fresh zero labels of a sign gadget (their jobs are small)
 constexpr int kMaxTerms = 64;   // label terms per launch, shared by its jobs
 constexpr int kThreads = 256;
 constexpr int kMaxChain = 16;   // mixed-radix digits of the sign gadget
@@ -71,7 +72,7 @@ struct DrawLaunch {
     uint64_t elem_base;
     uint32_t layer;
     uint32_t n_elem;
-    DrawJob jobs[kMaxJobs];
+    DrawJob jobs[kMaxDrawJobs];
 };
 
 struct AffineJob {

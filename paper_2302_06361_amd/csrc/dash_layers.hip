@@ -121,7 +121,7 @@ struct DrawBatcher {
         L.n_elem = E; L.layer = layer; L.elem_base = elem_base;
     }
     void add(int m, int domain, uint32_t slot, LView out, bool digit0 = false) {
-        if (nj == kMaxJobs) flush();
+        if (nj == kMaxDrawJobs) flush();
         L.jobs[nj++] = DrawJob{(uint32_t)m, (uint32_t)domain, slot, digit0 ? 1u : 0u, out};
     }
     void flush() { if (nj && status == DASH_OK) status = launch_draw(c, L, nj, s); nj = 0; }
