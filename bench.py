@@ -27,8 +27,8 @@ ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # vector instructions per ciphertext row of k_proj_garble and of k_digits_garble / per gate of the evaluator's gate kernels, averaged over
 # the launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per row (FETCH_SIZE,
 # WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up: 2.0 and 1.0).
-PMC = dict(garble_valu_per_row=792.5, digits_valu_per_row=636.8, eval_valu_per_gate=654.2,
-           garble_fetch_bytes_per_row=4.27, garble_write_bytes_per_row=29.82,
+PMC = dict(garble_valu_per_row=792.5, digits_valu_per_row=636.8, eval_valu_per_gate=625.1,
+           garble_fetch_bytes_per_row=4.27, garble_write_bytes_per_row=29.83,
            digits_fetch_bytes_per_row=4.62, digits_write_bytes_per_row=21.47)
 
 
