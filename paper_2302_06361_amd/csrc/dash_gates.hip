@@ -4,6 +4,8 @@
 //   k_affine      : free gates: out = sum_t coef_t * term_t mod m   (Sec. Arithmetic Garbled Circuits)
 //   k_proj_garble : one lane per ciphertext row: hash the label of value a, add the payload, store
 //                   the row at the position its colour names            (projection gates, point-and-permute)
+//   k_digits_garble : the k n digit gates of a sign gadget (Appendix, approximated sign): one lane per (element,
+//                   value a) of a residue, which forms and compresses the label once for its n rows
 //   (the evaluator's kernels are in dash_gates_eval.hip)
 //
 // A launch carries up to 16 homogeneous gate batches ("jobs", blockIdx.y); every lane of a block

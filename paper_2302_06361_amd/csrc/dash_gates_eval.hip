@@ -2,7 +2,10 @@
 //
 //   k_proj_eval   : one lane per gate: hash the active label, fetch the row its colour names, subtract
 //                   (Sec. Arithmetic Garbled Circuits, projection gates)
+//   k_digits_eval : the k n digit gates of a sign gadget, one lane per (element, residue): one compress, n gates
 //   k_chain_eval  : the n dependent gates of the mixed-radix addition of a sign gadget, one lane per element
+//   k_cast_halve  : scaling gadget: cast of the mod-2 wire into an odd prime and the halving that uses it
+//                   (Sec. The Scaling Operation)
 //   k_hg_finish   : evaluator side of the mixed-modulus half gate       (Appendix)
 //
 // Jobs, table layouts and compile-time moduli as in dash_gates.hip.

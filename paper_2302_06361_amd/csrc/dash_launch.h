@@ -124,7 +124,7 @@ struct ChainLaunch {
     uint32_t up_coef, pad_;
 };
 
-// evaluator, scaling gadget (Sec. Scaling in the CRT representation): cast of the mod-2 wire y into Z_p (a two-row
+// evaluator, scaling gadget (Sec. The Scaling Operation): cast of the mod-2 wire y into Z_p (a two-row
 // gate) and the halving that uses it, b = (x + addc * one - cast) / 2 mod p, one lane per (element, odd prime)
 struct CastJob {
     uint32_t p, slot;
