@@ -137,6 +137,7 @@ DASH_HD uint32_t ge_mask(uint32_t x) {
 // (a + b) mod m on 4 packed digits, a, b < m per byte.
 template <class MI>
 DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
+    if constexpr (cmod_m<MI>::value == 2) return a ^ b;          // digits are bits (one per byte)
     if (M.m <= 128) {
         uint32_t t = a + b;                                       // bytes <= 2m-2 <= 254
         return t - (ge_mask(t + M.c4) & M.m4);
@@ -152,6 +153,7 @@ DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
 // (a - b) mod m on 4 packed digits.
 template <class MI>
 DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const MI& M) {
+    if constexpr (cmod_m<MI>::value == 2) return a ^ b;
     if (M.m <= 128) {
         uint32_t t = a + (M.m4 - b);                              // bytes in [1, 2m-1] <= 255
         return t - (ge_mask(t + M.c4) & M.m4);
@@ -167,6 +169,7 @@ DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const MI& M) {
 // (a + c * b) mod m on 4 packed digits, c < m.
 template <class MI>
 DASH_HD uint32_t axpymod4(uint32_t a, uint32_t c, uint32_t b, const MI& M) {
+    if constexpr (cmod_m<MI>::value == 2) return a ^ (b & (0u - (c & 1u)));
     uint32_t r = 0;
     for (int b8 = 0; b8 < 4; b8++) r |= mod_m(byte_of(a, b8) + mul24(c, byte_of(b, b8)), M) << (8 * b8);
     return r;
