@@ -134,6 +134,21 @@ DASH_HD uint32_t ge_mask(uint32_t x) {
     uint32_t hi = x & 0x80808080u;
     return (hi - (hi >> 7)) | hi;
 }
+// Moduli above 128 (the accumulation moduli k d_j of the 12-prime digit set): a sum of two digits does not fit a
+// byte, so the digits go through 16-bit fields, two per word; "x >= m ? x - m : x" is min(x, x - m) on unsigned
+// 16-bit fields (the difference wraps to a large number when x < m): packed 16-bit subtract and minimum.
+DASH_HD uint32_t redmod2x16(uint32_t x, uint32_t m) {      // both fields below 2 m
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const u16x2 v = __builtin_bit_cast(u16x2, x), mm = __builtin_bit_cast(u16x2, m * 0x00010001u);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(v, (u16x2)(v - mm)));
+#else
+    uint32_t lo = x & 0xffffu, hi = x >> 16;
+    lo = lo >= m ? lo - m : lo;
+    hi = hi >= m ? hi - m : hi;
+    return lo | (hi << 16);
+#endif
+}
 // (a + b) mod m on 4 packed digits, a, b < m per byte.
 template <class MI>
 DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
@@ -142,13 +157,9 @@ DASH_HD uint32_t addmod4(uint32_t a, uint32_t b, const MI& M) {
         uint32_t t = a + b;                                       // bytes <= 2m-2 <= 254
         return t - (ge_mask(t + M.c4) & M.m4);
     }
-    uint32_t r = 0;
-    for (int b8 = 0; b8 < 4; b8++) {
-        uint32_t t = byte_of(a, b8) + byte_of(b, b8);
-        t = t >= M.m ? t - M.m : t;
-        r |= t << (8 * b8);
-    }
-    return r;
+    const uint32_t ev = redmod2x16((a & 0x00ff00ffu) + (b & 0x00ff00ffu), M.m);
+    const uint32_t od = redmod2x16(((a >> 8) & 0x00ff00ffu) + ((b >> 8) & 0x00ff00ffu), M.m);
+    return ev | (od << 8);
 }
 // (a - b) mod m on 4 packed digits.
 template <class MI>
@@ -158,13 +169,10 @@ DASH_HD uint32_t submod4(uint32_t a, uint32_t b, const MI& M) {
         uint32_t t = a + (M.m4 - b);                              // bytes in [1, 2m-1] <= 255
         return t - (ge_mask(t + M.c4) & M.m4);
     }
-    uint32_t r = 0;
-    for (int b8 = 0; b8 < 4; b8++) {
-        uint32_t t = byte_of(a, b8) + M.m - byte_of(b, b8);
-        t = t >= M.m ? t - M.m : t;
-        r |= t << (8 * b8);
-    }
-    return r;
+    const uint32_t m2 = M.m * 0x00010001u;                        // fields a + m - b in [1, 2m-1]
+    const uint32_t ev = redmod2x16((a & 0x00ff00ffu) + (m2 - (b & 0x00ff00ffu)), M.m);
+    const uint32_t od = redmod2x16(((a >> 8) & 0x00ff00ffu) + (m2 - ((b >> 8) & 0x00ff00ffu)), M.m);
+    return ev | (od << 8);
 }
 // (a + c * b) mod m on 4 packed digits, c < m.
 template <class MI>
