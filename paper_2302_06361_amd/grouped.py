@@ -13,9 +13,12 @@ class ProjectionBatch:
     and position j is the gate's element index (its tweak).  Per group the buffers are
     in0 / act (input zero and active labels), out0 / out (output labels), phi [count][p], table."""
 
-    def __init__(self, ctx, pi, qi, layer_id=1):
+    def __init__(self, ctx, pi, qi, layer_id=1, streams=4):
         import torch
         self.ctx = ctx
+        # the groups are independent: their calls go round-robin to a few streams (default priority), so that the
+        # ramp-up and tail of one group's kernels overlap with its neighbours'
+        self._streams = [torch.cuda.Stream(device=ctx.device) for _ in range(max(1, streams))] if streams > 1 else []
         k = ctx.k
         key = np.asarray(pi, np.int64) * k + np.asarray(qi, np.int64)
         self.order = np.argsort(key, kind="stable")
@@ -41,10 +44,28 @@ class ProjectionBatch:
         self.table_bytes = sum(g["table"].numel() for g in self.groups)
         self.rows = sum(g["count"] * ctx.primes[g["pi"]] for g in self.groups)
 
-    def garble(self):
-        for g in self.groups:
-            self.ctx.garble_layer(g["layer"], g["in0"], g["out0"], g["table"])
+    def _each_group(self, call, serial=False):
+        import torch
+        if serial or not self._streams:
+            for g in self.groups:
+                call(g)
+            return
+        cur = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(cur)
+        for s in self._streams:
+            s.wait_event(start)                       # after everything already queued on the caller's stream
+        for idx, g in enumerate(self.groups):
+            with torch.cuda.stream(self._streams[idx % len(self._streams)]):
+                call(g)
+        for s in self._streams:                       # the caller's stream continues when all groups are done
+            done = torch.cuda.Event()
+            done.record(s)
+            cur.wait_event(done)
 
-    def evaluate(self):
-        for g in self.groups:
-            self.ctx.eval_layer(g["layer"], g["act"], g["table"], g["out"])
+    def garble(self, serial=False):
+        """serial: all groups on the caller's stream, one after the other (per-kernel timing)"""
+        self._each_group(lambda g: self.ctx.garble_layer(g["layer"], g["in0"], g["out0"], g["table"]), serial)
+
+    def evaluate(self, serial=False):
+        self._each_group(lambda g: self.ctx.eval_layer(g["layer"], g["act"], g["table"], g["out"]), serial)
