@@ -147,7 +147,7 @@ GateJob phi_job(int p, int q, LView in, const uint8_t* phi, uint32_t slot, LView
 // One sign gadget over E elements.  x[i]: input residues (i >= first_res).  seg: start of the gadget's
 // first segment inside the layer table (already offset for the element count), offsets per slot follow
 // the slot order.  On return w.bit holds [X >= P/2] (negate = 0) or its complement.
-// up (evaluator, optional): a second output wire, bit + up_coef * up_one.
+// up (optional): a second output wire, bit + up_coef * up_one.
 int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
               int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s, const LView* up = nullptr,
               const LView* up_one = nullptr, uint32_t up_coef = 0) {
@@ -220,6 +220,10 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     if (garble) {
         AffineBatcher ab(c, E, s);
         for (int j = n; j >= 1; j--) sum_digit(ab, j);
+        if (up) {       // the output wire's zero label is drawn, so its shifted copy can be formed here already
+            Term tu[2] = {Term{w.bit, 1}, Term{*up_one, up_coef}};
+            ab.add(2, *up, tu, 2);
+        }
         ab.flush();
         if (ab.status) return ab.status;
         for (int j = n; j >= 1; j--) chain_gate(j);
@@ -418,94 +422,36 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
     for (int i = 0; i < k; i++) one[i] = LView{garble ? c->d_one0[i] : c->d_one[i], 16, 0u};
     const uint64_t quarter = c->P / 4;
 
-    if (!garble) {
-        // Evaluator: per repetition a cast-and-halve launch (two-row gates and b_i = (x_i - cast_i) / 2 together), the
-        // sign gadget (whose last launch also writes the next repetition's shifted mod-2 wire), and nothing else: the
-        // ShiftDown of the odd residues is a constant that the next repetition's halving adds first; only the last
-        // repetition writes it out.
-        LView x[DASH_MAX_PRIMES];
-        for (int i = 0; i < k; i++) x[i] = view_of(in, i);
-        const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
-        {
-            AffineBatcher ab(c, E, s);
-            Term t[2] = {Term{x[0], 1}, Term{one[0], 1}};
-            ab.add(2, pl.up, t, 2);
-            ab.flush();
-            if (ab.status) return ab.status;
-        }
-        for (int rep = 0; rep < L->repeat; rep++) {
-            uint8_t* tb = tables + (size_t)rep * bpe * E;
-            const uint32_t sb = rep * slots_per_rep;
-            const bool last = rep == L->repeat - 1;
-            // b of this repetition alternates between two buffer sets (the halving reads the one before)
-            LView* bnew = rep & 1 ? pl.buf[0] : pl.b;
-            const LView* bold = rep & 1 ? pl.b : pl.buf[0];
-            CastLaunch CL;
-            memset(&CL, 0, sizeof(CL));
-            CL.n_elem = E; CL.layer = layer; CL.elem_base = eb; CL.y = pl.up;
-            size_t cum = 0;
-            int nj = 0;
-            for (int i = 1; i < k; i++) {
-                const uint32_t p = c->prime[i];
-                CastJob& J = CL.jobs[nj++];
-                J.p = p; J.slot = sb + (i - 1); J.table = tb + cum * E;
-                J.x = rep == 0 ? x[i] : bold[i];
-                J.one = one[i];
-                J.addc = rep == 0 ? 0u : (uint32_t)((p - quarter % p) % p);
-                J.out = bnew[i];
-                cum += 2 * pitch_of(c, p);
-                if (nj == kMaxJobs || i == k - 1) {
-                    const int st = launch_cast_halve(c, CL, nj, s);
-                    if (st) return st;
-                    nj = 0;
-                }
-            }
-            const uint32_t upc = (c0 + 1) % 2;
-            int st = sign_core(c, false, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
-                               last ? nullptr : &one[0], upc);
-            if (st) return st;
-            if (last) {
-                AffineBatcher ab(c, E, s);
-                Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};
-                ab.add(2, view_of(out, 0), t0, 2);
-                for (int i = 1; i < k; i++) {
-                    uint32_t p = c->prime[i];
-                    Term t[2] = {Term{bnew[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};
-                    ab.add(p, view_of(out, i), t, 2);
-                }
-                ab.flush();
-                if (ab.status) return ab.status;
-            }
-        }
-        return DASH_OK;
+    // Per repetition: the casts of the mod-2 wire into the odd primes and b_i = (x_i - cast_i) / 2 (evaluator: one
+    // cast-and-halve launch; garbler: the cast gates, then the halving of the zero labels as a free-gate launch), then the
+    // sign gadget, whose free-gate (garbler) or chain (evaluator) launch also writes the next repetition's shifted mod-2
+    // wire.  The ShiftDown of the odd residues is a constant that the next repetition's halving adds first; only the
+    // last repetition writes it out.
+    LView x[DASH_MAX_PRIMES];
+    for (int i = 0; i < k; i++) x[i] = view_of(in, i);
+    const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
+    {
+        AffineBatcher ab(c, E, s);
+        Term t[2] = {Term{x[0], 1}, Term{one[0], 1}};      // ShiftUp: + P/2, i.e. +1 on the mod-2 residue only
+        ab.add(2, pl.up, t, 2);
+        ab.flush();
+        if (ab.status) return ab.status;
     }
-
-    LView cur[DASH_MAX_PRIMES];
-    for (int i = 0; i < k; i++) cur[i] = view_of(in, i);
     for (int rep = 0; rep < L->repeat; rep++) {
         uint8_t* tb = tables + (size_t)rep * bpe * E;
         const uint32_t sb = rep * slots_per_rep;
-        LView nxt[DASH_MAX_PRIMES];
-        for (int i = 0; i < k; i++) nxt[i] = (rep == L->repeat - 1) ? view_of(out, i) : pl.buf[rep & 1][i];
-        // (1) ShiftUp: + P/2, i.e. +1 on the mod-2 residue only (after the first repetition it was
-        //     formed together with the previous ShiftDown)
-        if (rep == 0) {
-            AffineBatcher ab(c, E, s);
-            Term t[2] = {Term{cur[0], 1}, Term{one[0], 1}};
-            ab.add(2, pl.up, t, 2);
-            ab.flush();
-            if (ab.status) return ab.status;
-        }
-        // (2) cast the mod-2 residue into every odd prime, b_i = (x_i - cast_i) / 2
+        const bool last = rep == L->repeat - 1;
+        // b of this repetition alternates between two buffer sets (the halving reads the one before)
+        LView* bnew = rep & 1 ? pl.buf[0] : pl.b;
+        const LView* bold = rep & 1 ? pl.b : pl.buf[0];
+        auto addc_of = [&](uint32_t p) { return rep == 0 ? 0u : (uint32_t)((p - quarter % p) % p); };
+        size_t cum = 0;
         if (garble) {
             DrawBatcher db(c, E, layer, eb, s);
             for (int i = 1; i < k; i++) db.add(c->prime[i], DOM_GATE, sb + (i - 1), pl.cast[i]);
             db.flush();
             if (db.status) return db.status;
-        }
-        size_t cum = 0;
-        {
-            GateBatcher gb(c, garble, E, layer, eb, s, true);
+            GateBatcher gb(c, true, E, layer, eb, s, true);
             for (int i = 1; i < k; i++) {
                 gb.add(phi_job(2, c->prime[i], pl.up, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
                 cum += 2 * pitch_of(c, c->prime[i]);
@@ -514,35 +460,49 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
             if (gb.status) return gb.status;
             AffineBatcher ab(c, E, s);
             for (int i = 1; i < k; i++) {
-                uint32_t p = c->prime[i], inv2 = (p + 1) / 2;
-                Term t[2] = {Term{cur[i], inv2}, Term{pl.cast[i], p - inv2}};
-                ab.add(p, pl.b[i], t, 2);
+                const uint32_t p = c->prime[i], inv2 = (p + 1) / 2, addc = addc_of(p);
+                Term t[3] = {Term{rep == 0 ? x[i] : bold[i], inv2}, Term{pl.cast[i], p - inv2}, Term{one[i], (inv2 * addc) % p}};
+                ab.add(p, bnew[i], t, addc ? 3 : 2);
             }
             ab.flush();
             if (ab.status) return ab.status;
-        }
-        // (3) base extension: [value of (0, b_1..b_{k-1}) >= P/2] is the mod-2 residue of the halved value
-        int st = sign_core(c, garble, E, layer, eb, pl.b, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s);
-        if (st) return st;
-        // (4) ShiftDown: - floor(P/4)
-        {
-            AffineBatcher ab(c, E, s);
-            const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
-            Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};
-            ab.add(2, nxt[0], t0, 2);
-            if (rep + 1 < L->repeat) {      // the next repetition's ShiftUp of the same wire
-                Term tu[2] = {Term{pl.w.bit, 1}, Term{one[0], (c0 + 1) % 2}};
-                ab.add(2, pl.up, tu, 2);
+        } else {
+            CastLaunch CL;
+            memset(&CL, 0, sizeof(CL));
+            CL.n_elem = E; CL.layer = layer; CL.elem_base = eb; CL.y = pl.up;
+            int nj = 0;
+            for (int i = 1; i < k; i++) {
+                const uint32_t p = c->prime[i];
+                CastJob& J = CL.jobs[nj++];
+                J.p = p; J.slot = sb + (i - 1); J.table = tb + cum * E;
+                J.x = rep == 0 ? x[i] : bold[i];
+                J.one = one[i];
+                J.addc = addc_of(p);
+                J.out = bnew[i];
+                cum += 2 * pitch_of(c, p);
+                if (nj == kMaxJobs || i == k - 1) {
+                    const int st = launch_cast_halve(c, CL, nj, s);
+                    if (st) return st;
+                    nj = 0;
+                }
             }
+        }
+        const uint32_t upc = (c0 + 1) % 2;
+        int st = sign_core(c, garble, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
+                           last ? nullptr : &one[0], upc);
+        if (st) return st;
+        if (last) {
+            AffineBatcher ab(c, E, s);
+            Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};
+            ab.add(2, view_of(out, 0), t0, 2);
             for (int i = 1; i < k; i++) {
                 uint32_t p = c->prime[i];
-                Term t[2] = {Term{pl.b[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};
-                ab.add(p, nxt[i], t, 2);
+                Term t[2] = {Term{bnew[i], 1}, Term{one[i], (uint32_t)((p - quarter % p) % p)}};
+                ab.add(p, view_of(out, i), t, 2);
             }
             ab.flush();
             if (ab.status) return ab.status;
         }
-        for (int i = 0; i < k; i++) cur[i] = nxt[i];
     }
     return DASH_OK;
 }
