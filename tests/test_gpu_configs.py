@@ -197,3 +197,34 @@ def test_paper_cifar_model_shapes(name):
     """the CIFAR-sized models f and F of the paper's table (7-prime base, rescaling by 2^5 after every ReLU): one
     image, decoded outputs against the plain evaluation and the label invariant on every boundary"""
     vgg_check(workloads.paper_model(name, seed=6), 1, exact=False)
+
+
+def test_config4_dense_full_size_sampled():
+    """Config 4 at full size (dense 4096 x 4096, batch 128, 12 primes) in the launch configuration bench.py times (the
+    256 x 256 tile of the MFMA kernel).  The labels are uploaded from the host generator; the oracle recomputes sampled
+    outputs one by one: for a few batch elements, a few rows of every row block position, all digits of every prime."""
+    from paper_2302_06361_amd import Context, Labels, Layer, DENSE
+    mb = workloads.gemm_microbench(seed=4)
+    M, K, B = mb["M"], mb["K"], mb["batch"]
+    ctx, orc = both(12, seed=mb["seed"])
+    wp = ctx.weights_prepare(mb["W"])
+    x = Labels(ctx, B * K)
+    host = []
+    for i, p in enumerate(ctx.primes):
+        lab = workloads.uniform_labels(mb["gen"], B * K, ctx.lam(p), p)
+        host.append(lab)
+        x.from_numpy(i, lab)
+    y = Labels(ctx, B * M, zero=True)
+    lay = Layer(DENSE, 1, B, in_c=K, out_c=M, weights=wp)
+    print("inputs uploaded", flush=True)
+    ctx.eval_layer(lay, x, None, y)
+    torch.cuda.synchronize()
+    g = np.random.default_rng(44)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, M - 1], g.integers(0, M, 26)]))     # tile edges and random rows
+    for b in (0, 77, B - 1):
+        for i, p in enumerate(ctx.primes):
+            want = orc.dense(i, host[i][b * K:(b + 1) * K], 1, K, len(rows), mb["W"][rows])
+            got = y.slice(b * M, (b + 1) * M).to_numpy(i)[rows]
+            assert (got == want).all(), (b, p)
+    for i in range(ctx.k):
+        assert y.pad_is_zero(i)
