@@ -205,10 +205,14 @@ class Oracle:
     def signact_bytes_per_elem(self):
         return self.L.orc_signact_bytes_per_elem(self.h)
 
-    def relu_garble(self, layer, in0, elem_base=0, want_wires=False):
+    def relu_garble(self, layer, in0, elem_base=0, want_wires=False, zero_only=False):
+        """zero_only: the output zero labels alone (no ciphertexts are computed) -> out0"""
         in0 = [_u8(a) for a in in0]
         n = in0[0].shape[0]
         out0 = self._bundle_out(n)
+        if zero_only:
+            self.L.orc_relu_garble(self.h, int(layer), C.c_uint64(elem_base), C.c_long(n), _ptrs(in0), _ptrs(out0), None, None)
+            return out0
         tables = np.zeros(n * self.relu_bytes_per_elem(), np.uint8)
         wires = np.zeros((n, self.sign_nslots(), MAXLAM), np.uint8) if want_wires else None
         self.L.orc_relu_garble(self.h, int(layer), C.c_uint64(elem_base), C.c_long(n), _ptrs(in0), _ptrs(out0),
@@ -225,10 +229,15 @@ class Oracle:
                              _ptrs(out), _p(wires) if want_wires else None)
         return (out, wires) if want_wires else out
 
-    def scale_garble(self, layer, in0, repeat, elem_base=0):
+    def scale_garble(self, layer, in0, repeat, elem_base=0, zero_only=False):
+        """zero_only: the output zero labels alone (no ciphertexts are computed) -> out0"""
         in0 = [_u8(a) for a in in0]
         n = in0[0].shape[0]
         out0 = self._bundle_out(n)
+        if zero_only:
+            self.L.orc_scale_garble(self.h, int(layer), C.c_uint64(elem_base), C.c_long(n), int(repeat), _ptrs(in0), None,
+                                    _ptrs(out0))
+            return out0
         tables = np.zeros(n * repeat * self.scale_bytes_per_elem(), np.uint8)
         self.L.orc_scale_garble(self.h, int(layer), C.c_uint64(elem_base), C.c_long(n), int(repeat), _ptrs(in0),
                                 _p(tables), _ptrs(out0))

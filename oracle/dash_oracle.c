@@ -278,11 +278,14 @@ static void lab_zero(u8 *dst, int lam) { memset(dst, 0, (size_t)lam); }
 
 /* Garble one gate phi: Z_p -> Z_q on the wire with zero label in0.
  * out0 is the (already chosen) zero label of the output wire.
- * rows[colour(l^a)] = out0 + phi(a)*R_q + H_q(l^a, tweak),  l^a = in0 + a*R_p. */
+ * rows[colour(l^a)] = out0 + phi(a)*R_q + H_q(l^a, tweak),  l^a = in0 + a*R_p.
+ * rows == NULL: nothing is written (the zero labels of a circuit do not depend on its
+ * ciphertexts, so a caller that only needs zero labels skips them). */
 static void proj_garble_one(const octx *c, int p, int q, const u8 *in0, const u8 *phi, const u8 *out0,
                             int layer, uint32_t slot, u64 elem, u8 *rows) {
     int lp = c->lam[p], lq = c->lam[q], pitch = pitch_of(lq);
     u8 la[MAXLAM], h[MAXLAM], pay[MAXLAM];
+    if (!rows) return;      /* zero labels only: the caller wants no ciphertexts */
     for (int a = 0; a < p; a++) {
         lab_axpy(la, in0, a, c->delta[p], lp, p);
         hash(c, la, p, layer, slot, elem, q, h);
@@ -335,7 +338,7 @@ void orc_proj_eval(const octx *c, int p, int q, long n, u64 elem_base, int layer
  *   G[colour(lx^a)] = U0 + a*r*R_p             + H_p(lx^a)
  *   E[colour(ly^b)] = V0 - (b+r)*lx^0          + H_p(ly^b)
  *   S[colour(ly^b)] = (b + r + H_p(ly^b)[0]) mod p
- * zero label of z: V0 - U0. */
+ * zero label of z: V0 - U0.  G == NULL: only z0 is produced (no ciphertexts). */
 static void hg_garble_one(const octx *c, int p, const u8 *x0, const u8 *y0, int layer, uint32_t slotG,
                           u64 elem, u8 *z0, u8 *G, u8 *E, u8 *S) {
     int lp = c->lam[p], l2 = c->lam[2], pitch = pitch_of(lp);
@@ -344,7 +347,7 @@ static void hg_garble_one(const octx *c, int p, const u8 *x0, const u8 *y0, int 
     draw(c, DOM_GATE, layer, slotG + 1, elem, p, V0);
     draw(c, DOM_MASK, layer, slotG, elem, p, rl);
     int r = rl[0];
-    for (int a = 0; a < p; a++) {
+    for (int a = 0; a < p && G; a++) {
         lab_axpy(la, x0, a, c->delta[p], lp, p);
         hash(c, la, p, layer, slotG, elem, p, h);
         lab_axpy(pay, U0, (long)a * r, c->delta[p], lp, p);
@@ -352,7 +355,7 @@ static void hg_garble_one(const octx *c, int p, const u8 *x0, const u8 *y0, int 
         memset(row, 0, (size_t)pitch);
         for (int j = 0; j < lp; j++) row[j] = (u8)((pay[j] + h[j]) % p);
     }
-    for (int b = 0; b < 2; b++) {
+    for (int b = 0; b < 2 && G; b++) {
         lab_axpy(la, y0, b, c->delta[2], l2, 2);
         hash(c, la, 2, layer, slotG + 1, elem, p, h);
         lab_axpy(pay, V0, -(long)((b + r) % p), x0, lp, p);
@@ -541,7 +544,8 @@ int orc_sign_nslots(const octx *c) { return sign_nslots(c); }
 /* ------------------------------------------------------------------------- */
 
 /* in0[i], out0[i]: label tensors [n][lambda_{p_i}] of residue i.
- * tables: orc_relu_bytes_per_elem * n bytes.  wires (optional): [n][nsign][MAXLAM]. */
+ * tables: orc_relu_bytes_per_elem * n bytes, or NULL (garbler only): zero labels without
+ * ciphertexts.  wires (optional): [n][nsign][MAXLAM]. */
 void orc_relu_garble(const octx *c, int layer, u64 elem_base, long n, u8 *const in0[], u8 *const out0[],
                      u8 *tables, u8 *wires) {
     int k = c->k, ns = sign_nslots(c);
@@ -558,15 +562,16 @@ void orc_relu_garble(const octx *c, int layer, u64 elem_base, long n, u8 *const 
         u8 *x0[MAXK], *seg[MAXK * MAXN + MAXN];
         u8 bit0[MAXLAM];
         for (int i = 0; i < k; i++) x0[i] = in0[i] + e * c->lam[c->prime[i]];
-        for (int s = 0; s < ns; s++) seg[s] = tables + (size_t)n * off[s] + (size_t)e * sign_slot_bytes(c, s, 0);
+        for (int s = 0; s < ns; s++)
+            seg[s] = tables ? tables + (size_t)n * off[s] + (size_t)e * sign_slot_bytes(c, s, 0) : NULL;
         /* pos = [X < P/2]; ReLU keeps X when pos = 1 */
         sign_garble_one(c, 0, 1, x0, layer, 0, elem_base + (u64)e, seg, bit0,
                         wires ? wires + (size_t)e * ns * MAXLAM : NULL);
         for (int i = 0; i < k; i++) {
             int p = c->prime[i], pitch = pitch_of(c->lam[p]);
-            u8 *G = tables + (size_t)n * off[ns + 3 * i] + (size_t)e * p * pitch;
-            u8 *E = tables + (size_t)n * off[ns + 3 * i + 1] + (size_t)e * 2 * pitch;
-            u8 *S = tables + (size_t)n * off[ns + 3 * i + 2] + (size_t)e * 8;
+            u8 *G = tables ? tables + (size_t)n * off[ns + 3 * i] + (size_t)e * p * pitch : NULL;
+            u8 *E = tables ? tables + (size_t)n * off[ns + 3 * i + 1] + (size_t)e * 2 * pitch : NULL;
+            u8 *S = tables ? tables + (size_t)n * off[ns + 3 * i + 2] + (size_t)e * 8 : NULL;
             hg_garble_one(c, p, x0[i], bit0, layer, (uint32_t)(ns + 3 * i), elem_base + (u64)e,
                           out0[i] + e * c->lam[p], G, E, S);
         }
@@ -673,10 +678,11 @@ static void scale_layer(const octx *c, int garble, int layer, u64 elem_base, lon
         }
         for (int t = 0; t < repeat; t++) {
             u8 *castseg[MAXK], *signseg[MAXK * MAXN + MAXN];
-            u8 *rep = tables + (size_t)t * (size_t)n * bpe;
+            u8 *rep = tables ? tables + (size_t)t * (size_t)n * bpe : NULL;     /* NULL (garbler): no ciphertexts */
             for (int i = 1; i < k; i++)
-                castseg[i] = rep + (size_t)n * coff[i] + (size_t)e * 2 * pitch_of(c->lam[c->prime[i]]);
-            for (int s = 0; s < ns; s++) signseg[s] = rep + (size_t)n * soff[s] + (size_t)e * sign_slot_bytes(c, s, 1);
+                castseg[i] = rep ? rep + (size_t)n * coff[i] + (size_t)e * 2 * pitch_of(c->lam[c->prime[i]]) : NULL;
+            for (int s = 0; s < ns; s++)
+                signseg[s] = rep ? rep + (size_t)n * soff[s] + (size_t)e * sign_slot_bytes(c, s, 1) : NULL;
             scale_one(c, garble, curp, one, layer, (uint32_t)t * slots_per_rep, elem_base + (u64)e,
                       castseg, signseg, nxtp);
             for (int i = 0; i < k; i++) memcpy(cur[i], nxt[i], (size_t)c->lam[c->prime[i]]);

@@ -11,6 +11,7 @@ import workloads
 from gpu_util import both
 from oracle import capi, plain
 from oracle import net as onet
+from sampled import SampledOracle, segment_sizes, table_slices
 
 pytestmark = pytest.mark.gpu
 
@@ -32,32 +33,6 @@ def check_invariant(ctx, zero, act, ring_values, what):
         bad = (want != act.tensors[i][:, :n, :].to(torch.int16)).any(dim=2).any(dim=0)
         assert not bool(bad.any().item()), "%s residue %d: invariant broken at element %d" % (
             what, i, int(torch.nonzero(bad)[0].item()))
-
-
-def segment_sizes(orc, kind, repeat=1):
-    """bytes per element of every table segment of an activation layer, in slot order (the table format:
-    segment = [gate][row][pitch], rows = input modulus, pitch = 4 * ceil(lambda_out / 4))"""
-    k, n = orc.k, len(orc.digits)
-    m = [orc.mj(j) for j in range(1, n + 1)]
-    pitch = lambda q: 4 * ((orc.lam(q) + 3) // 4)
-
-    def sign(first):
-        out = [orc.primes[i] * pitch(m[j]) for i in range(first, k) for j in range(n)]
-        out += [m[j] * pitch(m[j - 1]) for j in range(1, n)]
-        out.append(m[0] * pitch(2))
-        return out
-    if kind == "relu":
-        out = sign(0)
-        for i in range(k):
-            p = orc.primes[i]
-            out += [p * pitch(p), 2 * pitch(p), 2 * 4]
-        assert sum(out) == orc.relu_bytes_per_elem()
-        return out
-    out = []
-    for _ in range(repeat):
-        out += [2 * pitch(orc.primes[i]) for i in range(1, k)] + sign(1)
-    assert sum(out) == repeat * orc.scale_bytes_per_elem()
-    return out
 
 
 def test_config2_lenet_batch16_full():
@@ -152,14 +127,40 @@ def test_config3_projection_microbenchmark_full():
         assert (G["table"][off * rb:(off + 40) * rb].cpu().numpy() == rtable.reshape(-1)).all(), gi
 
 
-def vgg_check(net, batch, exact):
+def vgg_check(net, batch, exact, batch_base=0, sample=None, runs=2, count=6):
+    """Gb, En, Ev, De layer by layer in the streamed mode (one table buffer, reused by every layer) over the batch
+    elements batch_base .. batch_base + batch - 1.  Always: decoded outputs against the plain evaluation and the
+    label invariant on every boundary.  exact: every byte against the oracle run over the same batch elements.
+    sample = b: in every activation layer, `runs` runs of `count` consecutive values of batch element b are
+    recomputed by the oracle from the seeds alone (tests/sampled.py); their zero and active labels on both sides of
+    the layer and their rows of every table segment must agree byte for byte."""
     from paper_2302_06361_amd import Context, StreamedNetwork
     ctx = Context(net["primes"], net["seed"], net["digits"])
-    g = StreamedNetwork(ctx, net, batch=batch)
+    g = StreamedNetwork(ctx, net, batch=batch, batch_base=batch_base)
     P = int(np.prod(net["primes"]))
-    x = net["x"][:batch * net["n_in"]]
+    x = net["x"][batch_base * net["n_in"]:(batch_base + batch) * net["n_in"]]
     pv = plain.run_network(net["layers"], x, P, batch)
-    ref = onet.run(net, batch, 0, 0, keep=True) if exact else None
+    ref = onet.run(net, batch, batch_base, 0, keep=True) if exact else None
+    samples = {}
+    if sample is not None:
+        so = SampledOracle(net, sample)
+        gen = np.random.default_rng(55)
+        for li, L in enumerate(net["layers"]):
+            if L["kind"] in ("relu", "scale", "sign"):
+                n = so.n[li]
+                c = min(count, n)
+                starts = {0, n - c}
+                while len(starts) < min(runs, n - c + 1):
+                    starts.add(int(gen.integers(0, n - c + 1)))
+                starts = sorted(starts)[:runs]
+                samples[li] = [(st, c, so.activation(li, st, c)) for st in starts]
+                print("oracle: layer %d (%s), values %s of batch element %d" % (L["id"], L["kind"], starts, sample), flush=True)
+    compared = [0]
+
+    def same(labels, first, cnt, want, what):
+        for r in range(ctx.k):
+            got = labels.slice(first, first + cnt).to_numpy(r)
+            assert (got == want[r]).all(), (what, "residue", r)
 
     def boundary(i, zero, act):
         check_invariant(ctx, zero, act, pv[i], "boundary %d" % i)
@@ -170,10 +171,23 @@ def vgg_check(net, batch, exact):
             if i and net["layers"][i - 1]["id"] in ref["gb"]["tables"]:
                 want = ref["gb"]["tables"][net["layers"][i - 1]["id"]]
                 assert (g.table[:want.size].cpu().numpy() == want).all(), ("tables", i)
+        n = g.sizes[i] // batch
+        base = (sample - batch_base) * n if sample is not None else 0
+        for st, c, r in samples.get(i, []):              # input side of layer i
+            same(zero, base + st, c, r["zero_in"], "layer %d zero labels in" % i)
+            same(act, base + st, c, r["act_in"], "layer %d active labels in" % i)
+        for st, c, r in samples.get(i - 1, []):          # output side of layer i - 1, and its tables
+            same(zero, base + st, c, r["zero_out"], "layer %d zero labels out" % (i - 1))
+            same(act, base + st, c, r["act_out"], "layer %d active labels out" % (i - 1))
+            for off_gpu, off_run, nbytes in table_slices(so.orc, net["layers"][i - 1], g.sizes[i], base + st, c):
+                got = g.table[off_gpu:off_gpu + nbytes].cpu().numpy()
+                assert (got == r["tables"][off_run:off_run + nbytes]).all(), ("layer %d tables" % (i - 1), off_gpu)
+            compared[0] += 1
     values, valid = g.run(torch.as_tensor(x).to(ctx.device), boundary)
     torch.cuda.synchronize()
     assert valid.cpu().numpy().all()
     assert (values.cpu().numpy() == plain.to_signed(pv[-1], P)).all()
+    assert compared[0] == sum(len(v) for v in samples.values())
     return g
 
 
@@ -184,19 +198,23 @@ def test_config5_vgg_shape_reduced_exact():
     vgg_check(workloads.vgg(seed=5, batch=2, width=(3, 4, 5), hw=8), 2, exact=True)
 
 
-def test_config5_vgg_full_width_one_image():
-    """Config 5 at its real layer shapes: one image of the batch of 64 (the tables of one image already
-    take tens of GB, so the batch is streamed image by image and layer by layer).  Decoded outputs against
-    the plain evaluation and the label invariant on every boundary."""
-    g = vgg_check(workloads.vgg(seed=5, batch=64), 1, exact=False)
-    print("config 5: %.1f GB of tables per image" % (g.table_bytes / 1e9))
+def test_config5_vgg_full_width_sampled():
+    """Config 5 at its real layer shapes: images 36 and 37 of the batch of 64 in one streamed call (the tables of one
+    image's largest layer already take 30 GB, so the batch is streamed in chunks and layer by layer; element and
+    wire indices of this call start at image 36, not at 0).  In each of the 14 activation layers three runs of values
+    of image 37 (first, last and a random position) are recomputed by the oracle: labels on both sides and every
+    table byte of those values.  All decoded outputs against the plain evaluation and the label invariant on every
+    boundary."""
+    g = vgg_check(workloads.vgg(seed=5, batch=64), 2, exact=False, batch_base=36, sample=37, runs=3)
+    print("config 5: %.1f GB of tables per image" % (g.table_bytes / 2 / 1e9))
 
 
 @pytest.mark.parametrize("name", ["f", "F"])
 def test_paper_cifar_model_shapes(name):
     """the CIFAR-sized models f and F of the paper's table (7-prime base, rescaling by 2^5 after every ReLU): one
-    image, decoded outputs against the plain evaluation and the label invariant on every boundary"""
-    vgg_check(workloads.paper_model(name, seed=6), 1, exact=False)
+    image; sampled values of every activation layer against the oracle (labels and table bytes), decoded outputs
+    against the plain evaluation and the label invariant on every boundary"""
+    vgg_check(workloads.paper_model(name, seed=6), 1, exact=False, sample=0, runs=3)
 
 
 def test_config4_dense_full_size_sampled():

@@ -85,6 +85,20 @@ def test_activation_one_gate_per_lane_digit_path(monkeypatch):
     run_activation(7, "scale", np.random.default_rng(78).integers(0, P7, 200), repeat=2, digits=workloads.DIGITS[7])
 
 
+@pytest.mark.parametrize("k", [8, 12])
+def test_activation_bank_replicated_tables_forced(monkeypatch, k):
+    """the instantiations with bank-replicated AES tables (taken by launches of 2^20 lanes and more: the wide layers
+    of configs 2 and 5) forced for small layers, for the gate kernels and for the fused digit garbler alike: every
+    byte of ReLU and scaling layers of the 8- and the 12-prime base against the oracle"""
+    monkeypatch.setenv("DASH_BANKED_MIN_LANES", "1")
+    monkeypatch.setenv("DASH_DIGITS_BANKED_MIN_LANES", "1")
+    P = int(np.prod(workloads.PRIMES[:k]))
+    g = np.random.default_rng(100 + k)
+    X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], g.integers(0, P, 1296)])     # 1301 values: ragged tiles of 1024 lanes
+    run_activation(k, "relu", X, elem_base=2 ** 31 + 3)
+    run_activation(k, "scale", X[:333], repeat=2, elem_base=77)
+
+
 def test_activation_floor_rule():
     P = int(np.prod(workloads.PRIMES[:5]))
     g = np.random.default_rng(5)
