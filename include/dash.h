@@ -137,6 +137,20 @@ int dash_garble_layer(dash_ctx *ctx, const dash_layer *layer, const dash_labels 
 int dash_eval_layer(dash_ctx *ctx, const dash_layer *layer, const dash_labels *in_act, const void *tables,
                     dash_labels *out_act, void *scratch, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops with a fixed memory
+ * budget, harnesses that forbid hipMalloc): dash_eval_layer with the scratch buffer taken from a fixed array of
+ * DASH_NOALLOC_SCRATCH_BYTES that lives inside the library (one copy per GPU, held until the process ends; its
+ * device address is resolved once per GPU by dash_ctx_create).  Same arguments, results and errors as
+ * dash_eval_layer otherwise; inputs, tables and outputs are still the caller's.  Returns DASH_ESIZE, and launches
+ * nothing, when the layer call needs more scratch than the array holds (dash_layer_sizes reports the need; split
+ * the layer into several calls over element ranges then).  The call allocates and frees nothing and does not
+ * synchronise.  Every kernel writes the scratch wires it reads, so nothing has to be cleared between calls, but all
+ * calls on one GPU share the one array: two calls that may overlap in time on the same GPU (different streams,
+ * different contexts) race; order them. */
+#define DASH_NOALLOC_SCRATCH_BYTES (32u << 20)
+int dash_eval_layer_noalloc(dash_ctx *ctx, const dash_layer *layer, const dash_labels *in_act, const void *tables,
+                            dash_labels *out_act, void *hip_stream);
+
 /* e: zero labels of circuit-input wires first_wire .. first_wire + zero->n_elem - 1, every residue. */
 int dash_input_labels(dash_ctx *ctx, int64_t first_wire, dash_labels *zero, void *hip_stream);
 /* En: out = zero + (value mod p) * R_p (Sec. Quantization and Encoding: Encode(x) = x mod P).

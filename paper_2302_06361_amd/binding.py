@@ -15,10 +15,11 @@ MAX_PRIMES = 16
 MAX_DIGITS = 16
 DENSE, CONV2D, SUMPOOL, RELU, SCALE, SIGN, PROJ = 1, 2, 3, 4, 5, 6, 7
 LAMBDA_CEIL, LAMBDA_FLOOR = 0, 1
+NOALLOC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
+           "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
 
 
 class DashError(RuntimeError):
@@ -248,6 +249,13 @@ class Context:
                                         C.c_void_p(tables.data_ptr() if tables is not None else 0),
                                         C.c_void_p(scratch.data_ptr() if scratch is not None else 0), _stream()),
                "dash_garble_layer")
+
+    def eval_layer_noalloc(self, layer, in_act, tables, out_act):
+        """dash_eval_layer with the library's own fixed scratch array (NOALLOC_SCRATCH_BYTES): allocates nothing"""
+        ci, co = in_act.c(), out_act.c()
+        _check(self.L.dash_eval_layer_noalloc(self.h, C.byref(layer.c), C.byref(ci),
+                                              C.c_void_p(tables.data_ptr() if tables is not None else 0), C.byref(co), _stream()),
+               "dash_eval_layer_noalloc")
 
     def eval_layer(self, layer, in_act, tables, out_act, scratch=None):
         ci, co = in_act.c(), out_act.c()

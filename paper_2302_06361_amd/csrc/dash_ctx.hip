@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "dash_hostconst.h"
@@ -151,6 +152,28 @@ static bool fits_128_bits(uint32_t m, uint32_t lam) {
 }  // namespace dash
 
 // ------------------------------------------------------------------------------------------------
+// Scratch memory of dash_eval_layer_noalloc: a fixed device array inside the library's code object (every GPU
+// that loads the library holds its own copy until the process ends).  In host code the array's name is only a
+// handle for hipGetSymbolAddress; the device address is resolved once per device, at context creation with that
+// device current, and only that pointer is ever handed to kernels.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) uint8_t scratch[DASH_NOALLOC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static uint8_t* g_scratch_ptr[kMaxDevices];      // per device; written under g_scratch_lock
+static std::mutex g_scratch_lock;
+
+// the calling thread's current device must be `device`
+static int resolve_scratch(int device) {
+    if (device < 0 || device >= kMaxDevices) return DASH_ESIZE;
+    std::lock_guard<std::mutex> lock(g_scratch_lock);
+    if (g_scratch_ptr[device]) return DASH_OK;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return DASH_EHIP;
+    g_scratch_ptr[device] = (uint8_t*)ptr;
+    return DASH_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
 extern "C" {
@@ -276,6 +299,8 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     int status = DASH_EHIP;
     do {
         if (hipSetDevice(hip_device) != hipSuccess) break;
+        if ((status = resolve_scratch(hip_device)) != DASH_OK) break;
+        status = DASH_EHIP;
         if (hipMalloc((void**)&c->d_pool, bytes) != hipSuccess) break;
         if (hipMalloc((void**)&c->d_mods, sizeof(ModInfo) * 256) != hipSuccess) break;
         if (hipMalloc((void**)&c->d_ttab, sizeof(T)) != hipSuccess) break;
@@ -520,6 +545,20 @@ int dash_garble_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_ze
 int dash_eval_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_act, const void* tables, dash_labels* out_act,
                     void* scratch, void* stream) {
     return run_layer(c, L, false, in_act, out_act, (uint8_t*)tables, (uint8_t*)scratch, (hipStream_t)stream);
+}
+
+
+int dash_eval_layer_noalloc(dash_ctx* c, const dash_layer* L, const dash_labels* in_act, const void* tables, dash_labels* out_act,
+                            void* stream) {
+    if (!c || !L) return DASH_EINVAL;
+    size_t need = 0;
+    const int st = layer_sizes(c, L, nullptr, nullptr, &need);
+    if (st) return st;
+    if (need > (size_t)DASH_NOALLOC_SCRATCH_BYTES) return DASH_ESIZE;
+    if (c->device < 0 || c->device >= kMaxDevices) return DASH_ESIZE;
+    uint8_t* ptr = g_scratch_ptr[c->device];       // resolved by dash_ctx_create on this device
+    if (!ptr) return DASH_EHIP;
+    return run_layer(c, L, false, in_act, out_act, (uint8_t*)tables, ptr, (hipStream_t)stream);
 }
 
 }  // extern "C"
