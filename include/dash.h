@@ -96,14 +96,22 @@ typedef struct {
 } dash_layer;
 
 /* Create a context on GPU `hip_device`: the CRT base (distinct primes, primes[0] must be 2 for
- * SCALE, every prime <= 127), the label-length rule, the 16-byte seed of the counter-based PRG
- * that replaces the paper's hardware RNG (Sec. Implementation) and the mixed-radix digits
- * d_1..d_n of the sign gadget (Appendix, Approximated Garbled Sign; d_1 most significant and
- * even, k * d_j <= 255; NULL = built-in set with prod(d) >= k * P, which makes the sign exact).
+ * SCALE, every prime <= 127, product of the primes below 2^62), the label lengths, the 16-byte seed of
+ * the counter-based PRG that replaces the paper's hardware RNG (Sec. Implementation) and the
+ * mixed-radix digits d_1..d_n of the sign gadget (Appendix, Approximated Garbled Sign; d_1 most
+ * significant and even, k * d_j <= 255; NULL = built-in set with prod(d) >= k * P, which makes the
+ * sign exact).
+ * Label lengths (Sec. LabelTensors): lambda_rule gives the length of every modulus; `lambda`, if not
+ * NULL, is a host array of k entries that overrides it for the CRT primes (lambda[i] digits for
+ * primes[i], 1..128; the accumulation moduli of the sign gadget keep the rule).
  * Draws the offset label R_m of every modulus in use (colour digit forced to 1) and the
- * constant-one wire of every prime.  Allocates a few hundred KB of device memory. */
-int dash_ctx_create(dash_ctx **out, const uint16_t *primes, int k, int lambda_rule, const uint8_t seed[16],
-                    const uint16_t *sign_digits, int n_digits, int hip_device);
+ * constant-one wire of every prime.  Allocates a few hundred KB of device memory.  Tuning variables of
+ * the environment (DASH_BANKED_MIN_LANES, DASH_DIGITS_BANKED_MIN_LANES, DASH_FUSED_MIN_ELEMS_GARBLE,
+ * DASH_FUSED_MIN_ELEMS_EVAL, DASH_GEMM_TILE) are read here, once per context, and nowhere else.
+ * Errors: DASH_EINVAL (NULL, non-prime or repeated modulus, bad digits or lambda), DASH_ESIZE (product
+ * of the primes too large), DASH_EUNSUPPORTED (no digit set found), DASH_EHIP. */
+int dash_ctx_create(dash_ctx **out, const uint16_t *primes, int k, int lambda_rule, const uint16_t *lambda,
+                    const uint8_t seed[16], const uint16_t *sign_digits, int n_digits, int hip_device);
 void dash_ctx_destroy(dash_ctx *ctx);
 
 /* Label length of modulus m (2..255) under the context's rule; 0 if m is out of range. */

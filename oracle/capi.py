@@ -80,7 +80,7 @@ def decompress(h, q, lam_):
 class Oracle:
     """One garbling context: CRT base, label-length rule, seed, mixed-radix digits."""
 
-    def __init__(self, primes, digits, seed, rule=0):
+    def __init__(self, primes, digits, seed, rule=0, lam=None):
         self.primes = [int(p) for p in primes]
         self.k = len(self.primes)
         self.digits = [int(d) for d in digits]
@@ -91,7 +91,8 @@ class Oracle:
         pr = (C.c_int * self.k)(*self.primes)
         dg = (C.c_int * self.n)(*self.digits)
         self.L = lib()
-        self.h = C.c_void_p(self.L.orc_ctx_create(pr, self.k, rule, _p(seed), dg, self.n))
+        la = None if lam is None else (C.c_int * self.k)(*[int(v) for v in lam])
+        self.h = C.c_void_p(self.L.orc_ctx_create(pr, self.k, rule, la, _p(seed), dg, self.n))
         assert self.h, "orc_ctx_create failed"
         self.P = 1
         for p in self.primes:

@@ -214,8 +214,12 @@ static void hash(const octx *c, const u8 *L, int p, int layer, uint32_t slot, u6
     decompress(load128(eb) ^ X, q, c->lam[q], out);
 }
 
-octx *orc_ctx_create(const int *primes, int k, int rule, const u8 seed[16], const int *digits, int n) {
+/* lam_primes: NULL, or k explicit label lengths (1..128) for the CRT primes in place of the rule
+ * (the label length is a parameter of the scheme, Sec. LabelTensors); the accumulation moduli of
+ * the sign gadget keep the rule. */
+octx *orc_ctx_create(const int *primes, int k, int rule, const int *lam_primes, const u8 seed[16], const int *digits, int n) {
     if (k < 1 || k > MAXK || n < 1 || n > MAXN) return NULL;
+    for (int i = 0; lam_primes && i < k; i++) if (lam_primes[i] < 1 || lam_primes[i] > MAXLAM) return NULL;
     octx *c = (octx *)calloc(1, sizeof(octx));
     c->k = k; c->rule = rule; c->n = n;
     c->P = 1;
@@ -232,6 +236,7 @@ octx *orc_ctx_create(const int *primes, int k, int rule, const u8 seed[16], cons
     aes_expand(seed, c->rk_seed);
     for (int m = 2; m < 256; m++) {
         c->lam[m] = orc_lambda(m, rule);
+        for (int i = 0; lam_primes && i < k; i++) if (primes[i] == m) c->lam[m] = lam_primes[i];
         /* offset label R_m: random, point-and-permute component fixed to 1
          * (Sec. Arithmetic Garbled Circuits).  Component 0 is the colour. */
         draw(c, DOM_DELTA, 0, 0, 0, m, c->delta[m]);

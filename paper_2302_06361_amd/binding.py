@@ -139,7 +139,7 @@ class Layer:
 
 
 class Context:
-    def __init__(self, primes, seed, digits=None, rule=LAMBDA_CEIL, device=0):
+    def __init__(self, primes, seed, digits=None, rule=LAMBDA_CEIL, device=0, lam=None):
         import torch
         if not torch.cuda.is_available():
             raise DashError("no GPU visible: libdash has no CPU path")
@@ -150,11 +150,9 @@ class Context:
         pr = (C.c_uint16 * self.k)(*self.primes)
         sd = (C.c_uint8 * 16)(*bytes(seed))
         h = C.c_void_p()
-        if digits is None:
-            st = self.L.dash_ctx_create(C.byref(h), pr, self.k, rule, sd, None, 0, device)
-        else:
-            dg = (C.c_uint16 * len(digits))(*[int(d) for d in digits])
-            st = self.L.dash_ctx_create(C.byref(h), pr, self.k, rule, sd, dg, len(digits), device)
+        la = None if lam is None else (C.c_uint16 * self.k)(*[int(v) for v in lam])
+        dg = None if digits is None else (C.c_uint16 * len(digits))(*[int(d) for d in digits])
+        st = self.L.dash_ctx_create(C.byref(h), pr, self.k, rule, la, sd, dg, 0 if digits is None else len(digits), device)
         _check(st, "dash_ctx_create")
         self.h = h
         buf = (C.c_uint16 * MAX_DIGITS)()

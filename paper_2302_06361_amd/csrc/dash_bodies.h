@@ -26,6 +26,15 @@ struct alignas(16) Dw4 { uint32_t w[4]; };
 DASH_HD Dw4 ld_chunk(const LView& v, uint32_t e, int ch) { return *(const Dw4*)(v.p + (int64_t)ch * v.cs + lane_off(v, e)); }
 DASH_HD void st_chunk(const LView& v, uint32_t e, int ch, const Dw4& d) { *(Dw4*)(v.p + (int64_t)ch * v.cs + lane_off(v, e)) = d; }
 
+// compressed label and colour of a wire of modulus 2 (a sign bit or a mod-2 residue): the 128-digit description
+// when that is the context's label length of modulus 2, the run-time record otherwise
+template <class LoadDw>
+DASH_HD U128 compress_mod2(const ModInfo* mods, LoadDw dw, uint32_t* colour) {
+    if (mods[2].lam == 128) return compress(CMod<2, 128>{nullptr}, dw, colour);
+    const ModInfo M2 = mods[2];
+    return compress(M2, dw, colour);
+}
+
 // PRG labels: one lane per (job, element)
 template <class Tab>
 DASH_HD void draw_body(const DrawLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
@@ -208,7 +217,8 @@ DASH_HD void chain_out(const ChainLaunch& L, uint32_t e, int i, uint32_t w) {
 }
 
 // Digit sets whose digits 2..n share one accumulation modulus (description MC) and whose first digit has
-// description M1, both fixed at compile time: the carry label stays in registers from gate to gate.
+// description M1, both fixed at compile time: the carry label stays in registers from gate to gate.  The output
+// wire has modulus 2 and 128 digits (the launcher takes the generic body for any other label length of modulus 2).
 template <class MC, class M1, class Tab>
 DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, const Tab& T) {
     const uint32_t e = bx * kThreads + tx;
@@ -272,9 +282,13 @@ DASH_HD void chain_eval_generic_body(const ChainLaunch& L, uint32_t bx, uint32_t
             const ModInfo Mo = L.mods[L.m[j - 1]];
             chain_gate(L, Mi, Mo, e, j, in_dw, [&](int i, uint32_t w) { st_dw(L.carry[j - 1], e, i, w); }, T);
             for (int i = (int)Mo.ndw; i < (int)Mo.nchunk * 4; i++) st_dw(L.carry[j - 1], e, i, 0);
-        } else {
+        } else if (L.mods[2].lam == 128) {
             const CMod<2, 128> M2{nullptr};
             chain_gate(L, Mi, M2, e, 1, in_dw, [&](int i, uint32_t w) { chain_out(L, e, i, w); }, T);
+        } else {                                // another label length of modulus 2: run-time constants
+            const ModInfo M2 = L.mods[2];
+            chain_gate(L, Mi, M2, e, 1, in_dw, [&](int i, uint32_t w) { chain_out(L, e, i, w); }, T);
+            for (int i = (int)M2.ndw; i < (int)M2.nchunk * 4; i++) chain_out(L, e, i, 0);
         }
     }
 }
@@ -381,7 +395,7 @@ DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint
     if (e >= L.n_elem) return;
     const ModInfo Mp = L.mods[J.p];
     uint32_t colour = 0;
-    U128 K = compress(CMod<2, 128>{nullptr}, [&](int i) { return ld_dw(L.y, e, i); }, &colour);
+    U128 K = compress_mod2(L.mods, [&](int i) { return ld_dw(L.y, e, i); }, &colour);
     U128 h = hash_block(K, L.elem_base + e, J.slot, L.layer, L.key.rk, T);
     const uint32_t inv2 = (J.p + 1) / 2;
     with_mod(Mp, [&](auto P) {
@@ -435,7 +449,7 @@ DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_
     uint32_t e = bx * kThreads + tx;
     if (e >= L.n_elem) return;
     uint32_t colour = 0;
-    U128 K = compress(CMod<2, 128>{nullptr}, [&](int i) { return ld_dw(J.y, e, i); }, &colour);
+    U128 K = compress_mod2(L.mods, [&](int i) { return ld_dw(J.y, e, i); }, &colour);
     U128 h = hash_block(K, L.elem_base + e, J.slot, L.layer, L.key.rk, T);
     uint32_t s = *(const uint32_t*)(J.S + ((size_t)e * 2 + colour) * 4);
     uint32_t beta = mod_m(s + Mp.m - mod_u128(h, Mp), Mp);

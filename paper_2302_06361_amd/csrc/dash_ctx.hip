@@ -189,14 +189,19 @@ const char* dash_strerror(int status) {
     return "unknown status";
 }
 
-int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_rule, const uint8_t seed[16],
-                    const uint16_t* sign_digits, int n_digits, int hip_device) {
+int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_rule, const uint16_t* lambda,
+                    const uint8_t seed[16], const uint16_t* sign_digits, int n_digits, int hip_device) {
     if (!out || !primes || !seed || k < 1 || k > DASH_MAX_PRIMES) return DASH_EINVAL;
     if (lambda_rule != DASH_LAMBDA_CEIL && lambda_rule != DASH_LAMBDA_FLOOR) return DASH_EINVAL;
+    uint64_t prod = 1;
     for (int i = 0; i < k; i++) {
         if (primes[i] < 2 || primes[i] > 127) return DASH_EINVAL;
         for (int j = 0; j < i; j++) if (primes[j] == primes[i]) return DASH_EINVAL;
         for (int t = 2; t * t <= primes[i]; t++) if (primes[i] % t == 0) return DASH_EINVAL;
+        if (lambda && (lambda[i] < 1 || lambda[i] > 128)) return DASH_EINVAL;
+        // P, 2 P (decode), k P (digit search) and the CRT coefficients are 64-bit numbers in this library
+        if (prod > (1ull << 62) / primes[i]) return DASH_ESIZE;
+        prod *= primes[i];
     }
     dash_ctx* c = new (std::nothrow) dash_ctx();
     if (!c) return DASH_EINVAL;
@@ -209,6 +214,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     if (const char* e = getenv("DASH_FUSED_MIN_ELEMS_GARBLE")) c->fused_min_elems[0] = strtoull(e, nullptr, 10);
     if (const char* e = getenv("DASH_FUSED_MIN_ELEMS_EVAL")) c->fused_min_elems[1] = strtoull(e, nullptr, 10);
     if (const char* e = getenv("DASH_DIGITS_BANKED_MIN_LANES")) c->digits_banked_min_lanes = strtoull(e, nullptr, 10);
+    if (const char* e = getenv("DASH_GEMM_TILE")) c->gemm_tile = e[0] == 'w' ? 2 : e[0] == 'b' ? 1 : 0;      // "wide" / "big"
     c->prof = new (std::nothrow) ProfState();
     c->P = 1;
     for (int i = 0; i < k; i++) { c->prime[i] = primes[i]; c->P *= primes[i]; }
@@ -251,6 +257,11 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     for (int i = 0; i < k; i++) used[c->prime[i]] = true;
     for (int j = 1; j <= c->n; j++) used[c->mj[j]] = true;
     for (int m = 2; m < 256; m++) fill_modinfo(c->mods[m], m, lambda_rule);
+    if (lambda)     // explicit label lengths of the CRT primes
+        for (int i = 0; i < k; i++) {
+            ModInfo& Mi = c->mods[c->prime[i]];
+            Mi.lam = lambda[i]; Mi.nchunk = (Mi.lam + 15) / 16; Mi.ndw = (Mi.lam + 3) / 4;
+        }
 
     // function tables of the sign gadget (Appendix, Approximated Garbled Sign)
     std::vector<uint8_t> phi;

@@ -138,9 +138,10 @@ int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
     auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
     dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
-    if (uniform && is(Mc, 96, 20) && is(M1, 26, 28))
+    const bool bit128 = c->mods[2].lam == 128;      // the fused bodies write the 128 digits of the sign wire
+    if (bit128 && uniform && is(Mc, 96, 20) && is(M1, 26, 28))
         hipLaunchKernelGGL((k_chain_eval<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, L);
-    else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24))
+    else if (bit128 && uniform && is(Mc, 204, 17) && is(M1, 46, 24))
         hipLaunchKernelGGL((k_chain_eval<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
     else
         hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);

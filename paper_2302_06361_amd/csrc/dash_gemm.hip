@@ -428,11 +428,10 @@ int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         macs += (double)batch * M * K * Mi.lam;
         bytes += (double)batch * (M + K) * Mi.lam + (double)M * K;
     }
-    (void)max_nchunk;
+    if ((int64_t)max_nchunk * batch >= (1ll << 31) - 64) return DASH_ESIZE;      // group indices are 32-bit in the kernel
     // tile shape.  Measured on 4096 x 4096, batch 128, 12 primes: 256 x 256 (one wave per SIMD) 1.30 ms, 128 x 512
     // (two waves per SIMD) 1.41 ms; the latter wastes half as many rows when there are at most 128 outputs.
-    const char* force = getenv("DASH_GEMM_TILE");       // tuning and test hook: "wide" or "big"
-    const bool wide = force ? force[0] == 'w' : M <= 128;
+    const bool wide = c->gemm_tile ? c->gemm_tile == 2 : M <= 128;
     auto launch = [&](auto tl) -> int {
         typedef decltype(tl) TL;
         const int gy = (M + TL::BM - 1) / TL::BM;

@@ -65,6 +65,7 @@ struct dash_ctx {
                                      // the fused kernels (a lane walks the n gates of a residue); smaller ones one gate per lane
     uint64_t digits_banked_min_lanes;   // the banked-table threshold of the fused garbling kernel (n hashes per lane)
     const uint8_t* phi_pm1[DASH_MAX_PRIMES];                         // {1, p-1}
+    int gemm_tile;                   // tile shape of the MFMA contraction: 0 by layer shape, 1 big, 2 wide (tuning and test hook)
 };
 
 namespace dash {

@@ -3,11 +3,11 @@
 // buffers under the sanitizers.  Test code, not part of libdash.
 //
 // usage: chain_emul <in.bin> <out.bin>
-//   in : int32 n n_elem rule layer variant(0 generic, 1 <96,26>, 2 <204,46>) pad pad pad; uint64 elem_base;
+//   in : int32 n n_elem rule layer variant(0 generic, 1 <96,26>, 2 <204,46>) lam2(0: by the rule) pad pad; uint64 elem_base;
 //        int32 m[n] (digit 1..n); int32 slot[n];
 //        for j = 1..n: u8 sum_j[n_elem][lam(m_j)];
 //        for j = 1..n: u8 table_j[n_elem][m_j][pitch(out modulus of gate j)]   (out modulus: m_{j-1}, or 2 for j = 1)
-//   out: u8 bit[n_elem][128]
+//   out: u8 bit[n_elem][lambda of modulus 2]
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -47,6 +47,8 @@ int main(int argc, char** argv) {
     if (fread(m.data() + 1, 4, n, f) != (size_t)n || fread(slot.data() + 1, 4, n, f) != (size_t)n) return 2;
     std::vector<ModInfo> mods(256);
     for (int q = 2; q < 256; q++) fill_modinfo(mods[q], q, rule);
+    if (hd[5]) { mods[2].lam = (uint32_t)hd[5]; mods[2].nchunk = (mods[2].lam + 15) / 16; mods[2].ndw = (mods[2].lam + 3) / 4; }
+    const uint32_t lam2 = mods[2].lam;
     uint8_t S[256];
     make_sbox(S);
     make_ttab(S, TT);
@@ -70,7 +72,7 @@ int main(int argc, char** argv) {
         if (fread(table[j].data(), 1, table[j].size(), f) != table[j].size()) return 2;
     }
     fclose(f);
-    std::vector<uint8_t> bit((size_t)8 * E * 16, 0xEE);
+    std::vector<uint8_t> bit((size_t)mods[2].nchunk * E * 16, 0xEE);
     for (int j = 1; j <= n; j++) {
         L.m[j] = (uint32_t)m[j]; L.slot[j] = (uint32_t)slot[j]; L.table[j] = table[j].data();
         L.sum[j] = LView{sum[j].data(), (int64_t)16 * E, 16u};
@@ -85,9 +87,9 @@ int main(int argc, char** argv) {
             else if (variant == 2) chain_eval_body<CMod<204, 17>, CMod<46, 24>>(L, bx, tx, T);
             else chain_eval_generic_body(L, bx, tx, T);
         }
-    std::vector<uint8_t> out((size_t)E * 128);
+    std::vector<uint8_t> out((size_t)E * lam2);
     for (uint32_t e = 0; e < E; e++)
-        for (uint32_t d = 0; d < 128; d++) out[(size_t)e * 128 + d] = bit[((size_t)(d / 16) * E + e) * 16 + d % 16];
+        for (uint32_t d = 0; d < lam2; d++) out[(size_t)e * lam2 + d] = bit[((size_t)(d / 16) * E + e) * 16 + d % 16];
     f = fopen(argv[2], "wb");
     if (!f) return 2;
     fwrite(out.data(), 1, out.size(), f);

@@ -8,12 +8,12 @@ from oracle import capi
 SEED = bytes(range(64, 80))
 
 
-def both(k, rule=0, seed=SEED, digits=None):
-    """(GPU context, oracle) for the first k primes"""
+def both(k, rule=0, seed=SEED, digits=None, lam=None):
+    """(GPU context, oracle) for the first k primes; lam: explicit label lengths of the primes"""
     from paper_2302_06361_amd import Context
     primes = workloads.PRIMES[:k]
     digits = list(digits or workloads.DIGITS[k])
-    return Context(primes, seed, digits, rule), capi.Oracle(primes, digits, seed, rule)
+    return Context(primes, seed, digits, rule, lam=lam), capi.Oracle(primes, digits, seed, rule, lam=lam)
 
 
 def upload_bundle(ctx, arrays):

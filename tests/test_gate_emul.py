@@ -72,11 +72,13 @@ def chain_emul():
     return CHAIN_EXE
 
 
-def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70):
+def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70, lam2=0):
     """m[0..n-1] = accumulation moduli of digits 1..n.  The tables are random bytes below the output modulus:
     the evaluator's result is defined by them alone, C_{j-1} = row[colour(S_j)] - H(S_j), S_j = sum_j + C_j
     (Appendix, Garbled Mixed-Radix Addition), recomputed here with the oracle's hash."""
     orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
+    if lam2:        # an explicit label length for modulus 2 (the output wire of the chain)
+        orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule, lam=[lam2] + [orc.lam(p) for p in workloads.PRIMES[1:8]])
     n = len(m)
     g = np.random.default_rng(sum(m) + n_elem)
     slots = [slot0 + n - 1] + [slot0 + (j - 2) for j in range(2, n + 1)]          # digit 1 feeds the final gate
@@ -89,14 +91,14 @@ def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 3
         t = np.zeros((n_elem, m[j], pitch), np.uint8)
         t[:, :, :lam_o] = g.integers(0, outm[j], (n_elem, m[j], lam_o))
         tabs.append(t)
-    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, 0, 0, 0, elem_base)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, lam2, 0, 0, elem_base)
     blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % n, *slots)
     blob += b"".join(s.tobytes() for s in sums) + b"".join(t.tobytes() for t in tabs)
     fin, fout = str(tmp_path / "cin.bin"), str(tmp_path / "cout.bin")
     open(fin, "wb").write(blob)
     r = subprocess.run([chain_emul, fin, fout], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
-    got = np.fromfile(fout, np.uint8).reshape(n_elem, 128)
+    got = np.fromfile(fout, np.uint8).reshape(n_elem, orc.lam(2))
     for e in range(n_elem):
         carry = None
         for j in range(n - 1, -1, -1):
@@ -119,6 +121,8 @@ def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
     run_chain(chain_emul, tmp_path, [2, 15, 27], 0, 65)
     run_chain(chain_emul, tmp_path, [4, 60, 56], 0, 33, rule=1)
     run_chain(chain_emul, tmp_path, [26, 96], 1, 5)                 # n = 2: no same-modulus step
+    run_chain(chain_emul, tmp_path, [26] + [96] * 6, 0, 70, lam2=64)    # label length of modulus 2 given explicitly
+    run_chain(chain_emul, tmp_path, [4, 60], 0, 300, lam2=100)
 
 
 # ---- the evaluator's fused digit gates --------------------------------------------------------------
@@ -215,3 +219,67 @@ def test_digit_row_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits_garble(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
     run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5)
+
+
+# ---- one evaluator launch that mixes output moduli -------------------------------------------------
+def test_mixed_output_moduli_in_one_eval_launch_under_sanitizers(tmp_path):
+    """the evaluator's any-modulus instantiation picks a compile-time description of the output modulus per job:
+    16 jobs with the 16 described moduli as outputs in ONE launch, exactly-sized buffers, address sanitizer; same
+    results as the single-modulus instantiations"""
+    exe = os.path.join(HERE, "mixed_emul.bin")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-o", exe, os.path.join(HERE, "mixed_emul.cpp")])
+    for n, seed in ((1, 1), (257, 2), (300, 3)):
+        r = subprocess.run([exe, str(n), str(seed)], capture_output=True, text=True)
+        assert r.returncode == 0 and r.stdout.strip() == "ok", r.stderr[-3000:]
+
+
+# ---- evaluator kernels that read a wire of modulus 2 ------------------------------------------------
+def run_cast(tmp_path, exe, p, n, addc, rule=0, lam2=0, lam_p=0, elem_base=2 ** 34 + 1, layer=12, slot=200):
+    """cast-and-halve of the scaling gadget, b = (x + addc one - cast) / 2 with cast = rows[colour(y)] - H_p(y)
+    (Sec. The Scaling Operation), and the evaluator's half-gate step z = V + beta x - U with
+    beta = S[colour(y)] - H_p(y)[0] (Appendix), from random tables, recomputed here with the oracle's hash"""
+    primes = workloads.PRIMES[:8]
+    base = capi.Oracle(primes, workloads.DIGITS[8], SEED, rule)
+    lam = [base.lam(q) for q in primes]
+    if lam2:
+        lam[0] = lam2
+    if lam_p:
+        lam[primes.index(p)] = lam_p
+    orc = capi.Oracle(primes, workloads.DIGITS[8], SEED, rule, lam=lam)
+    l2, lp = orc.lam(2), orc.lam(p)
+    pitch = capi.pitch(lp)
+    g = np.random.default_rng(p * 100 + n + lam2)
+    y = g.integers(0, 2, (n, l2)).astype(np.uint8)
+    x, U, V = (g.integers(0, p, (n, lp)).astype(np.uint8) for _ in range(3))
+    one = g.integers(0, p, lp).astype(np.uint8)
+    table = np.zeros((n, 2, pitch), np.uint8)
+    table[:, :, :lp] = g.integers(0, p, (n, 2, lp))
+    S = np.zeros((n, 2, 4), np.uint8)
+    S[:, :, 0] = g.integers(0, p, (n, 2))
+    blob = struct.pack("<8iQ", p, n, rule, layer, slot, addc, lam2, lam_p, elem_base)
+    blob += b"".join(a.tobytes() for a in (y, x, one, table, U, V, S))
+    fin, fout = str(tmp_path / "kin.bin"), str(tmp_path / "kout.bin")
+    open(fin, "wb").write(blob)
+    r = subprocess.run([exe, fin, fout], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    b, z = np.split(np.fromfile(fout, np.uint8), 2)
+    b, z = b.reshape(n, lp), z.reshape(n, lp)
+    inv2 = (p + 1) // 2
+    for e in range(n):
+        colour = int(y[e, 0])
+        cast = (table[e, colour, :lp].astype(np.int64) - orc.hash(y[e], 2, layer, slot, elem_base + e, p)) % p
+        assert (b[e] == ((x[e].astype(np.int64) + addc * one.astype(np.int64) - cast) * inv2) % p).all(), ("cast", e)
+        beta = (int(S[e, colour, 0]) - int(orc.hash(y[e], 2, layer, slot + 2, elem_base + e, p)[0])) % p
+        assert (z[e] == (V[e].astype(np.int64) + beta * x[e].astype(np.int64) - U[e]) % p).all(), ("half gate", e)
+
+
+def test_cast_and_half_gate_bodies_under_sanitizers(tmp_path):
+    exe = os.path.join(HERE, "cast_emul.bin")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-o", exe, os.path.join(HERE, "cast_emul.cpp")])
+    run_cast(tmp_path, exe, 3, 300, 0)
+    run_cast(tmp_path, exe, 19, 257, 7)
+    run_cast(tmp_path, exe, 7, 40, 3, rule=1)
+    run_cast(tmp_path, exe, 5, 70, 2, lam2=64)                   # label lengths given explicitly: modulus 2 shorter than 128
+    run_cast(tmp_path, exe, 13, 33, 0, lam2=100, lam_p=9)

@@ -63,6 +63,21 @@ def test_projection_gates_floor_rule_and_shared_table():
     run_proj(ctx, orc, 1, 5, 300, seed=2, shared_phi=True)
 
 
+def test_projection_gates_explicit_label_lengths():
+    ctx, orc = both(5, lam=(100, 20, 56, 7, 128))
+    for pi, qi in [(0, 1), (1, 0), (2, 3), (3, 4), (4, 2), (4, 4), (0, 0)]:
+        run_proj(ctx, orc, pi, qi, 300, seed=70 + pi * 6 + qi)
+
+
+def test_context_refuses_bases_whose_product_overflows():
+    from paper_2302_06361_amd import Context, DashError
+    primes = [2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37, 41, 43, 47, 53]       # product 3.3e19 > 2^62
+    with pytest.raises(DashError, match="size not supported"):
+        Context(primes, bytes(16), digits=(2, 3))
+    with pytest.raises(DashError, match="invalid argument"):
+        Context([2, 3, 5], bytes(16), digits=(2, 5, 9), lam=(128, 0, 56))
+
+
 def test_projection_gates_empty_batch():
     from paper_2302_06361_amd import Labels, Layer, PROJ
     ctx, orc = both(12)

@@ -11,9 +11,17 @@ from oracle import plain
 pytestmark = pytest.mark.gpu
 
 
-def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500, digits=None, exact=True):
+def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500, digits=None, exact=True, lam=None,
+                   default_digits=False):
     from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN
-    ctx, orc = both(k, rule, digits=digits)
+    if default_digits:      # the library picks the digit set; the oracle is built from what it reports
+        from paper_2302_06361_amd import Context
+        from oracle import capi
+        from gpu_util import SEED
+        ctx = Context(workloads.PRIMES[:k], SEED, None, rule)
+        orc = capi.Oracle(workloads.PRIMES[:k], ctx.digits, SEED, rule)
+    else:
+        ctx, orc = both(k, rule, digits=digits, lam=lam)
     n = len(X)
     zero = [orc.input_labels(first_wire, n, i) for i in range(k)]
     act = [orc.encode(i, np.asarray(X), zero[i]) for i in range(k)]
@@ -104,6 +112,27 @@ def test_activation_floor_rule():
     g = np.random.default_rng(5)
     run_activation(5, "relu", g.integers(0, P, 130), rule=1)
     run_activation(5, "scale", g.integers(0, P, 130), repeat=2, rule=1)
+
+
+def test_activation_explicit_label_lengths():
+    """label lengths passed per prime to dash_ctx_create (shorter and longer than either rule gives)"""
+    P = int(np.prod(workloads.PRIMES[:5]))
+    X = np.random.default_rng(31).integers(0, P, 140)
+    lam = (64, 90, 17, 46, 3)
+    run_activation(5, "relu", X, lam=lam)
+    run_activation(5, "scale", X, repeat=2, lam=lam)
+    run_activation(5, "sign", X, lam=lam)
+
+
+@pytest.mark.parametrize("k", [5, 7, 9, 10])
+def test_activation_default_digit_sets(k):
+    """no digit set given: the library searches one (prod(d) >= k P, smallest tables); the oracle, built from the
+    digits the library reports, must agree on every byte, and the sign must be exact (decoded values checked)"""
+    P = int(np.prod(workloads.PRIMES[:k]))
+    g = np.random.default_rng(40 + k)
+    X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P // 2 + 1, P - 1], g.integers(0, P, 194)])
+    run_activation(k, "relu", X, default_digits=True)
+    run_activation(k, "scale", X, repeat=2, default_digits=True)
 
 
 def test_activation_single_element():

@@ -141,3 +141,32 @@ def test_offsets_have_colour_one_and_inputs_differ():
     b = orc.input_labels(4, 4, 1)
     assert (a[4:] == b).all()                      # counter based: any wire alone
     assert len({r.tobytes() for r in a}) == 8      # and distinct
+
+
+def test_explicit_label_lengths_per_prime():
+    """label lengths given per prime (instead of the rule): lengths, hash and PRG recomputed from big integers and
+    openssl; digits past the 128-bit hash are zero; every projection-gate input still evaluates to its payload"""
+    primes, lam = (2, 3, 5, 7), (64, 90, 17, 46)
+    orc = capi.Oracle(primes, (4, 15, 14), bytes(range(16, 32)), 0, lam=lam)
+    ref = capi.Oracle(primes, (4, 15, 14), bytes(range(16, 32)), 0)
+    for p, l in zip(primes, lam):
+        assert orc.lam(p) == l and len(orc.delta(p)) == l and orc.delta(p)[0] == 1
+    assert orc.lam(60) == ref.lam(60)            # the accumulation moduli keep the rule
+    g = np.random.default_rng(6)
+    fixed_key = bytes(range(16))
+    for p, q in [(2, 3), (3, 5), (5, 2), (7, 3)]:
+        lp, lq = orc.lam(p), orc.lam(q)
+        lab = g.integers(0, p, lp, dtype=np.uint8)
+        K = sum(int(lab[j]) * p ** j for j in range(lp)) % (1 << 128)
+        X = K ^ (9 | (3 << 64) | (5 << 96))
+        h = int.from_bytes(_openssl_ecb(fixed_key, X.to_bytes(16, "little")), "little") ^ X
+        assert orc.hash(lab, p, 5, 3, 9, q).tolist() == [(h // q ** j) % q for j in range(lq)]
+    assert (orc.hash(np.zeros(64, np.uint8), 2, 1, 1, 1, 3)[81:] == 0).all()      # 3^81 > 2^128
+    for p, q in [(3, 5), (5, 2), (2, 7), (7, 3)]:
+        in0 = g.integers(0, p, (1, orc.lam(p)), dtype=np.uint8)
+        phi = g.integers(0, q, p, dtype=np.uint8)
+        out0, table = orc.proj_garble(p, q, in0, phi, 2, 4, 77)
+        for a in range(p):
+            act = ((in0.astype(np.int64) + a * orc.delta(p)) % p).astype(np.uint8)
+            out = orc.proj_eval(p, q, act, table, 2, 4, 77)
+            assert (out == (out0.astype(np.int64) + int(phi[a]) * orc.delta(q)) % q).all()
