@@ -1,12 +1,16 @@
 #!/usr/bin/env python3
-"""bench.py -- one GPU, the whole hot path on config 2 of the benchmark spec.
+"""bench.py -- one GPU, the whole hot path.
 
-A "step" is one pass of the whole path over one batch of synthetic input: garble the LeNet-5-shaped
-network (batch 16, 8-prime CRT base, 128-bit labels), encode the inputs, evaluate the garbled
-network, decode.  Inputs, weights and every buffer are resident in HBM before the timed region.
-Prints ONE JSON line (Measurement).
+A "step" is one pass of the whole path over one batch of synthetic input on config 2 of the benchmark spec, the
+configuration the metric is quoted on: garble the LeNet-5-shaped network (batch 16, 8-prime CRT base, 128-bit
+labels), encode the inputs, evaluate the garbled network, decode.  Inputs, weights and every buffer are resident
+in HBM before the timed region.  The other four configurations are measured after the timed steps and reported
+in `configs` of the same JSON line (config 1: batch-1 latency; config 3: projection gates/s; config 4:
+label-MAC/s; config 5: streamed over `--images` images of its batch of 64, never extrapolated).
+Prints ONE JSON line.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -23,27 +27,121 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
 # permute, three-operand forms and all multiplies issue at half of that.)
 ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
-# Figures taken from the rocprofv3 --pmc runs of this same command (profiles/k_proj_garble_lenet_b16_pmc.txt):
-# vector instructions per ciphertext row of k_proj_garble and of k_digits_garble / per gate of the evaluator's gate kernels, averaged over
-# the launches of one config-2 step (SQ_INSTS_VALU * 64 lanes / rows), and the HBM bytes per row (FETCH_SIZE,
-# WRITE_SIZE, scaled by what the same counters read for the 1 GiB copy issued in warm-up: 2.0 and 1.0).
-PMC = dict(garble_valu_per_row=792.5, digits_valu_per_row=636.8, eval_valu_per_gate=625.1,
-           garble_fetch_bytes_per_row=4.27, garble_write_bytes_per_row=29.83,
-           digits_fetch_bytes_per_row=4.62, digits_write_bytes_per_row=21.47)
+PMC_FILE = os.path.join(ROOT, "profiles", "gate_kernels_lenet_b16_pmc_per_unit.txt")
+GATE_SOURCES = ["dash_core.h", "dash_bodies.h", "dash_tabs.h", "dash_launch.h", "dash_gates.hip", "dash_gates_eval.hip", "dash_layers.hip"]
 
 
-def gate_counts(net, k, n_digits):
-    """projection-gate tables per step (the garbler builds each once, the evaluator hashes once per table)"""
-    sign = k * n_digits + n_digits
-    gates = 0
+def gate_source_hash():
+    """identifies the gate-kernel sources a counter file was taken with"""
+    h = hashlib.sha256()
+    for name in GATE_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2302_06361_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_pmc():
+    """Per-unit counter figures of the gate kernels (executed vector instructions per ciphertext row / per gate, HBM
+    bytes per row) from the committed summary of the rocprofv3 --pmc runs of this same command: `key = value` lines.
+    Returns (dict or None, note).  The file names the commit and the hash of the gate-kernel sources it was taken with;
+    figures taken with other sources are flagged stale (and still printed: they are counters, not timings)."""
+    if not os.path.exists(PMC_FILE):
+        return None, "profiles/%s is missing: no executed-instruction or traffic figures" % os.path.basename(PMC_FILE)
+    vals = {}
+    for line in open(PMC_FILE):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = [t.strip() for t in line.split("=", 1)]
+            try:
+                vals[k] = float(v)
+            except ValueError:
+                vals[k] = v
+    stale = vals.get("gate_source_hash") != gate_source_hash()
+    return vals, "taken at commit %s%s" % (vals.get("commit", "?"), "; STALE: the gate-kernel sources have changed since" if stale else "")
+
+
+# ---- algorithmic work of one hash, in 32-bit lane operations (derivation: DESIGN.md, Measurement) ----------------
+def _lam_ceil(m):
+    lam, v = 0, 1
+    while v < (1 << 128):
+        v *= m
+        lam += 1
+    return lam
+
+
+AES_LANE_OPS = 160 + 72 + 4 + 16 + 4      # 160 table indices, 2 three-input xors per column and round (9 rounds), key, last round, feed-forward
+
+
+def _compress_ops(m, lam):
+    dw = (lam + 3) // 4
+    return dw if m == 2 else 3 * dw + 16          # bits: one packing per dword; else 2 dot products + 1 fold per dword, 4 x 4 wide multiply-adds
+
+
+def _decompress_ops(m, lam):
+    dw = (lam + 3) // 4
+    return 2 * dw if m == 2 else 3 * lam + 132    # bits: one spread per dword; else 3 per digit + the long division of the 128-bit number
+
+
+def _modadd_ops(m, lam, count):
+    dw = (lam + 3) // 4
+    return count * dw * (1 if m == 2 else 4)      # packed modular addition of 4 digits: add, compare mask, and, subtract
+
+
+def alg_ops_garble_row(p, q, lam_p, lam_q, short=False, share=1):
+    """one ciphertext row: form the label of a, compress, AES, base-q digits, add payload (zero label + phi(a) R_q).
+    share: gates that hash the same input label under different tweaks (the n digit gates of a residue): the label is
+    formed and compressed once for all of them."""
+    head = (_modadd_ops(p, lam_p, 1) + _compress_ops(p, lam_p)) / share
+    if short:
+        return head + AES_LANE_OPS + 24 + 4
+    return head + AES_LANE_OPS + _decompress_ops(q, lam_q) + _modadd_ops(q, lam_q, 2)
+
+
+def alg_ops_eval_gate(p, q, lam_p, lam_q, share=1):
+    """one evaluated gate: compress, AES, base-q digits, subtract from the row"""
+    return _compress_ops(p, lam_p) / share + AES_LANE_OPS + _decompress_ops(q, lam_q) + _modadd_ops(q, lam_q, 1)
+
+
+def gadget_gates(primes, digits, kind, repeat=1):
+    """(p, q, class) of every projection-gate table of one value of an activation layer; class: 'digits' (the fused digit
+    kernels), 'gate' (general gate kernels), 'short' (one-digit rows of the half gate)"""
+    k, n = len(primes), len(digits)
+    m = [digits[0]] + [k * d for d in digits[1:]]
+
+    def sign(first):
+        out = [(primes[i], m[j], "digits") for i in range(first, k) for j in range(n)]
+        out += [(m[j], m[j - 1], "gate") for j in range(1, n)] + [(m[0], 2, "gate")]
+        return out
+    if kind == "relu":
+        out = sign(0)
+        for p in primes:
+            out += [(p, p, "gate"), (2, p, "gate"), (2, p, "short")]
+        return out
+    if kind == "sign":
+        return sign(0) + [(2, p, "gate") for p in primes]
+    out = []
+    for _ in range(repeat):
+        out += [(2, p, "gate") for p in primes[1:]] + sign(1)
+    return out
+
+
+def network_work(net):
+    """gates, rows and algorithmic lane operations of one pass over `batch` batch elements, split by kernel class"""
+    primes, digits = net["primes"], net["digits"]
+    w = dict(gates=0, rows=dict(digits=0, gate=0), ops_garble=dict(digits=0.0, gate=0.0), ops_eval=0.0)
     for L in net["layers"]:
-        if L["kind"] == "relu":
-            gates += L["n"] * (sign + 3 * k)
-        elif L["kind"] == "sign":
-            gates += L["n"] * (sign + k)
-        elif L["kind"] == "scale":
-            gates += L["n"] * L["repeat"] * ((k - 1) + (sign - n_digits))
-    return gates * net["batch"]
+        if L["kind"] not in ("relu", "scale", "sign"):
+            continue
+        per = gadget_gates(primes, digits, L["kind"], L.get("repeat", 1))
+        nval = L["n"] * net["batch"]
+        for p, q, cls in per:
+            lp, lq = _lam_ceil(p), _lam_ceil(q)
+            c = "digits" if cls == "digits" else "gate"
+            w["gates"] += nval
+            w["rows"][c] += nval * p
+            share = len(digits) if cls == "digits" else 1
+            w["ops_garble"][c] += nval * p * alg_ops_garble_row(p, q, lp, lq, cls == "short", share)
+            w["ops_eval"] += nval * alg_ops_eval_gate(p, q, lp, lq, share)
+    return w
 
 
 def mac_counts(net, lam_sum):
@@ -54,19 +152,24 @@ def mac_counts(net, lam_sum):
     return macs * net["batch"] * lam_sum
 
 
-def cpu_baseline(net, seconds_target=12.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload: the ReLU +
-    scale-by-2^6 activation pipeline (garble and evaluate) over `per_thread` values per thread."""
+# ---- the oracle on the host cores ------------------------------------------------------------------------
+def cpu_baseline(net, seconds_target=10.0):
+    """The oracle as it stands, on the host cores, on bounded samples of the same workloads:
+    (1) the ReLU + scale-by-2^6 activation pipeline of config 2 (garble and evaluate), values split over the threads;
+    (2) the dense contraction of config 4 on a subset of output rows and batch elements;
+    (3) one whole config-1 inference (garble, encode, evaluate, decode) on one thread."""
     from concurrent.futures import ThreadPoolExecutor
 
     import numpy as np
 
+    import workloads
     from oracle import capi
+    from oracle import net as onet
 
     cores = min(16, os.cpu_count() or 1)
     repeat = next(L["repeat"] for L in net["layers"] if L["kind"] == "scale")
-    k, n = len(net["primes"]), len(net["digits"])
-    per_value = (k * n + n + 3 * k) + repeat * ((k - 1) + (k - 1) * n + n)
+    k = len(net["primes"])
+    per_value = len(gadget_gates(net["primes"], net["digits"], "relu")) + len(gadget_gates(net["primes"], net["digits"], "scale", repeat))
 
     def work(t, count):
         orc = capi.Oracle(net["primes"], net["digits"], net["seed"], 0)
@@ -88,12 +191,46 @@ def cpu_baseline(net, seconds_target=12.0):
     with ThreadPoolExecutor(cores) as ex:
         done = sum(ex.map(lambda t: work(t, count), range(cores)))
     dt = time.time() - t0
-    return dict(value=2 * done * per_value / dt, unit="projection gates/s (garble+eval)", cores=cores, kind="oracle",
-                sample="ReLU + scale-by-2^%d pipeline of config 2 on %d values (%d per thread), garble + evaluate, %.1f s"
-                       % (repeat, done, count, dt))
+    out = dict(value=2 * done * per_value / dt, unit="projection gates/s (garble+eval)", cores=cores, kind="oracle",
+               sample="ReLU + scale-by-2^%d pipeline of config 2 on %d values (%d per thread), garble + evaluate, %.1f s"
+                      % (repeat, done, count, dt))
+
+    # (2) config 4: R output rows of the 4096 x 4096 layer for one batch element per thread, all 12 primes
+    mb = workloads.gemm_microbench(seed=4)
+    K, rows = mb["K"], 2048
+    orc12 = capi.Oracle(mb["primes"], workloads.DIGITS[12], mb["seed"], 0)
+    lam12 = [orc12.lam(p) for p in mb["primes"]]
+
+    def macs(t):
+        g = np.random.default_rng(100 + t)
+        r0 = (t * rows) % (mb["M"] - rows)
+        for i, p in enumerate(mb["primes"]):
+            x = workloads.uniform_labels(g, K, lam12[i], p)
+            orc12.dense(i, x, 1, K, rows, mb["W"][r0:r0 + rows])
+        return rows * K * sum(lam12)
+    t0 = time.time()
+    with ThreadPoolExecutor(cores) as ex:
+        total = sum(ex.map(macs, range(cores)))
+    dt = time.time() - t0
+    out["label_mac_per_s"] = dict(value=total / dt, cores=cores,
+                                  sample="config 4: %d output rows x 4096 inputs x 12 primes for %d batch elements (one per thread), %.1f s" % (rows, cores, dt))
+
+    # (3) config 1: one inference, single thread
+    net1 = workloads.mlp(seed=1, batch=1)
+    orc1 = onet.make_oracle(net1)
+    t0 = time.time()
+    gb = onet.garble(orc1, net1)
+    t1 = time.time()
+    act = onet.encode(orc1, net1, gb["e"], np.asarray(net1["x"]))
+    outl = onet.evaluate(orc1, net1, act, gb["tables"])
+    orc1.decode(outl, gb["d"])
+    t2 = time.time()
+    out["config1_inference"] = dict(garble_ms=(t1 - t0) * 1e3, eval_ms=(t2 - t1) * 1e3, cores=1,
+                                    sample="config 1 whole (MLP 784-128-10, batch 1): garble; encode + evaluate + decode")
+    return out
 
 
-def kernel_line(pr, steps, bytes_per_unit_note=None):
+def kernel_line(pr, steps):
     """per-kernel figures from the library's own HIP-event instrumentation (events recorded around every
     launch on the stream the kernel runs on)"""
     if not pr["ms"]:
@@ -109,24 +246,33 @@ def read_profiles(ctx):
     return {name: ctx.profile_read(kind) for name, kind in (("garble", 0), ("eval", 1), ("linear", 2), ("garble_digits", 3))}
 
 
+def zero_pad_digits(ctx, labels, i):
+    """digits past lambda in the last chunk are zero in a LabelTensor (the layout contract)"""
+    lam = ctx.lam(ctx.primes[i])
+    if lam % 16:
+        labels.tensors[i][-1, :, lam % 16:] = 0
+
+
+# ---- config 3 --------------------------------------------------------------------------------------------
 def micro_projection(torch, workloads, reps=2):
     """Config 3: 2^24 independent gates Z_p -> Z_q over the 12-prime base, grouped by (p, q)."""
     from paper_2302_06361_amd import Context, ProjectionBatch
     mb = workloads.proj_microbench(seed=3)
     ctx = Context(mb["primes"], mb["seed"], workloads.DIGITS[12])
     pb = ProjectionBatch(ctx, mb["pi"], mb["qi"])
-    a_all = torch.as_tensor(mb["a"][pb.order].astype("int16")).to(ctx.device)
+    a_all = torch.as_tensor(mb["a"][pb.order].astype("int64")).to(ctx.device)
     gen = torch.Generator(device=ctx.device)
     gen.manual_seed(3)
+    ops_g = ops_e = 0.0
     for G in pb.groups:
-        i, p, n = G["pi"], ctx.primes[G["pi"]], G["count"]
+        i, p, q, n = G["pi"], ctx.primes[G["pi"]], ctx.primes[G["qi"]], G["count"]
         t = G["in0"].tensors[i]
         t.copy_(torch.randint(0, p, t.shape, dtype=torch.uint8, device=ctx.device, generator=gen))
-        R = torch.zeros(t.shape[0] * 16, dtype=torch.int16)
-        R[:ctx.lam(p)] = torch.as_tensor(ctx.offset(p).astype("int16"))
-        a = a_all[G["start"]:G["start"] + n].view(1, n, 1)
-        G["act"].tensors[i].copy_(((t.to(torch.int16) + a * R.to(ctx.device).view(-1, 1, 16)) % p).to(torch.uint8))
-        G["phi"].copy_(torch.randint(0, ctx.primes[G["qi"]], G["phi"].shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+        zero_pad_digits(ctx, G["in0"], i)
+        ctx.encode(a_all[G["start"]:G["start"] + n], G["in0"], G["act"])           # active label = zero + a R_p
+        G["phi"].copy_(torch.randint(0, q, G["phi"].shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+        ops_g += n * p * alg_ops_garble_row(p, q, ctx.lam(p), ctx.lam(q))
+        ops_e += n * alg_ops_eval_gate(p, q, ctx.lam(p), ctx.lam(q))
     pb.garble(); pb.evaluate()
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -149,18 +295,25 @@ def micro_projection(torch, workloads, reps=2):
     torch.cuda.synchronize()
     ctx.profile_enable(False)
     pr = read_profiles(ctx)
-    out = dict(workload="config 3: 2^24 gates Z_p->Z_q, (p,q) uniform over the 12-prime base, 144 grouped launches on 4 streams",
-               gates=pb.n, rows=pb.rows, table_bytes=pb.table_bytes,
+    kg, ke = kernel_line(pr["garble"], reps), kernel_line(pr["eval"], reps)
+    eval_bytes = pr["eval"]["bytes"] / reps
+    out = dict(workload="config 3: 2^24 gates Z_p->Z_q, (p,q) uniform over the 12-prime base, grouped by (p,q)",
+               gates=pb.n, rows=pb.rows, table_bytes=pb.table_bytes, launches_garble=kg["launches_per_step"], launches_eval=ke["launches_per_step"],
                garble_ms=gms, eval_ms=ems, garble_gates_per_s=pb.n / (gms * 1e-3), eval_gates_per_s=pb.n / (ems * 1e-3),
-               garble_rows_per_s=pb.rows / (gms * 1e-3), garble_table_GBps=pb.table_bytes / (gms * 1e-3) / 1e9,
-               garble_frac_of_hbm=pb.table_bytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_proj_eval=kernel_line(pr["eval"], reps)))
+               garble_rows_per_s=pb.rows / (gms * 1e-3),
+               garble=dict(hbm_algorithmic_GBps=pr["garble"]["bytes"] / reps / (gms * 1e-3) / 1e9,
+                           hbm_frac=pr["garble"]["bytes"] / reps / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           alu_frac_algorithmic=ops_g / (gms * 1e-3) / 1e12 / ALU_PEAK_TOPS),
+               eval=dict(hbm_algorithmic_GBps=eval_bytes / (ems * 1e-3) / 1e9, hbm_frac=eval_bytes / (ems * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         alu_frac_algorithmic=ops_e / (ems * 1e-3) / 1e12 / ALU_PEAK_TOPS),
+               kernels_one_stream=dict(k_proj_garble=kg, k_proj_eval=ke))
     del pb
     ctx.close()
     torch.cuda.empty_cache()
     return out
 
 
+# ---- config 4 --------------------------------------------------------------------------------------------
 def micro_contraction(torch, workloads, reps=5):
     """Config 4: dense 4096 x 4096 on label tensors at batch 128, every prime of the 12-prime base."""
     from paper_2302_06361_amd import DENSE, Context, Labels, Layer
@@ -174,6 +327,7 @@ def micro_contraction(torch, workloads, reps=5):
     for i, p in enumerate(ctx.primes):
         t = x.tensors[i]
         t.copy_(torch.randint(0, p, t.shape, dtype=torch.uint8, device=ctx.device, generator=gen))
+        zero_pad_digits(ctx, x, i)
     lay = Layer(DENSE, 1, Bn, in_c=K, out_c=M, weights=wp)
     lam = sum(ctx.lam(p) for p in ctx.primes)
     macs = M * K * Bn * lam
@@ -192,86 +346,123 @@ def micro_contraction(torch, workloads, reps=5):
     pr = read_profiles(ctx)["linear"]
     ms = e0.elapsed_time(e1) / reps
     kms = pr["ms"] / max(pr["launches"], 1)
+    traffic, note = gemm_traffic()
     out = dict(workload="config 4: dense 4096x4096, weights in [-64,63], batch 128, 12 primes (%d label digits per value)" % lam,
                ms=ms, label_mac_per_s=macs / (ms * 1e-3),
                roofline=dict(bound="mfma", kernel="k_dense_mfma", unit="TOP/s", peak=INT8_MFMA_PEAK_TOPS,
                              achieved=2 * macs / (kms * 1e-3) / 1e12, frac=2 * macs / (kms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
-                             avg_launch_ms=kms, ops_per_launch=2 * macs,
-                             # HBM bytes per launch from the rocprofv3 --pmc runs in profiles/k_dense_mfma_dense4096_b128_pmc.txt
-                             traffic=1.965e9 + 0.327e9, algorithmic_bytes_per_launch=float(M) * K * len(ctx.primes) + 2.0 * Bn * (M + K) / 2 * 16 * sum((ctx.lam(p) + 15) // 16 for p in ctx.primes)))
+                             avg_launch_ms=kms, ops_per_launch=2 * macs, traffic=traffic, traffic_note=note,
+                             algorithmic_bytes_per_launch=float(M) * K * len(ctx.primes) + 2.0 * Bn * (M + K) / 2 * 16 * sum((ctx.lam(p) + 15) // 16 for p in ctx.primes)))
     ctx.close()
     torch.cuda.empty_cache()
     return out
 
 
-def micro_vgg(torch, workloads, images=1, reps=2):
-    """Config 5, streamed: garble + evaluate layer by layer, `images` images of the batch of 64 at a time."""
+def gemm_traffic():
+    """HBM bytes per launch of k_dense_mfma on config 4 from the committed counter summary (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy kernel), or None"""
+    path = os.path.join(ROOT, "profiles", "k_dense_mfma_dense4096_b128_pmc.txt")
+    if not os.path.exists(path):
+        return None, "profiles/k_dense_mfma_dense4096_b128_pmc.txt is missing"
+    for line in open(path):
+        if line.startswith("hbm_bytes_per_launch"):
+            return float(line.split("=")[1].split("#")[0]), "from profiles/k_dense_mfma_dense4096_b128_pmc.txt"
+    return None, "no hbm_bytes_per_launch line in profiles/k_dense_mfma_dense4096_b128_pmc.txt"
+
+
+# ---- config 5 --------------------------------------------------------------------------------------------
+def micro_vgg(torch, workloads, images=2, chunk=2, reps=1):
+    """Config 5, streamed: garble + encode + evaluate + decode layer by layer, `chunk` images of the batch of 64 at a
+    time (the tables of one image's largest layer take 30 GB), `images` images in all."""
     from paper_2302_06361_amd import Context, StreamedNetwork
     net = workloads.vgg(seed=5, batch=64)
+    images = min(images, 64)
+    chunk = min(chunk, images)
     ctx = Context(net["primes"], net["seed"], net["digits"])
-    g = StreamedNetwork(ctx, net, batch=images)
-    x = torch.as_tensor(net["x"][:images * net["n_in"]]).to(ctx.device)
-    k, n = ctx.k, len(ctx.digits)
+    g = StreamedNetwork(ctx, net, batch=chunk)
+    n_in = net["n_in"]
+    xs = [torch.as_tensor(net["x"][b * n_in:(b + chunk) * n_in]).to(ctx.device) for b in range(0, images, chunk) if b + chunk <= images]
     lam_sum = sum(ctx.lam(p) for p in ctx.primes)
-    sub = dict(net, batch=images)
-    gates, macs = gate_counts(sub, k, n), mac_counts(sub, lam_sum)
-    g.run(x)
+    sub = dict(net, batch=len(xs) * chunk)
+    work, macs = network_work(sub), mac_counts(sub, lam_sum)
+    g.run(xs[0])
     torch.cuda.synchronize()
-    ctx.profile_enable(True)
-    read_profiles(ctx)
+    valid = True
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        g.run(x)
+        for ci, x in enumerate(xs):
+            g.batch_base = ci * chunk
+            g.rebase()
+            g.run(x)
+            valid = valid and bool(g.valid.all().item())
     e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    # per-kernel figures from one more chunk with the library's events (not timed above)
+    ctx.profile_enable(True)
+    read_profiles(ctx)
+    g.run(xs[0])
     torch.cuda.synchronize()
     ctx.profile_enable(False)
     pr = read_profiles(ctx)
-    ms = e0.elapsed_time(e1) / reps
-    out = dict(workload="config 5: VGG shape (12 primes, scale 2^5), %d image(s) of the batch of 64 streamed layer by layer, "
-                        "garble + evaluate + decode" % images,
-               images=images, ms=ms, ms_per_image=ms / images, outputs_valid=bool(g.valid.all().item()),
-               table_bytes_per_image=g.table_bytes // images, gates_per_image=gates // images,
-               gates_per_s=2 * gates / (ms * 1e-3), label_macs_per_image=2 * macs // images,
-               kernels=dict(k_proj_garble=kernel_line(pr["garble"], reps), k_digits_garble=kernel_line(pr["garble_digits"], reps),
-                            eval_kernels=kernel_line(pr["eval"], reps), linear=kernel_line(pr["linear"], reps)))
+    n_img = len(xs) * chunk
+    out = dict(workload="config 5: VGG shape (12 primes, scale 2^5), %d image(s) of the batch of 64, streamed layer by layer in chunks "
+                        "of %d images, garble + encode + evaluate + decode" % (n_img, chunk),
+               images=n_img, chunk=chunk, ms=ms, ms_per_image=ms / n_img, outputs_valid=valid,
+               table_bytes_per_image=g.table_bytes // chunk, gates_per_image=work["gates"] // n_img,
+               gates_per_s=2 * work["gates"] / (ms * 1e-3), label_macs_per_image=2 * macs // n_img,
+               kernels_per_chunk=dict(k_proj_garble=kernel_line(pr["garble"], 1), k_digits_garble=kernel_line(pr["garble_digits"], 1),
+                                      eval_kernels=kernel_line(pr["eval"], 1), linear=kernel_line(pr["linear"], 1)))
     ctx.close()
     torch.cuda.empty_cache()
     return out
 
 
-def micro_paper_models(torch, workloads, reps=5):
+# ---- config 1 and the paper's model shapes: batch-1 latency ---------------------------------------------------
+def latency(torch, net, reps=5):
+    from paper_2302_06361_amd import Context, GarbledNetwork
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    g = GarbledNetwork(ctx, net)
+    x = torch.as_tensor(net["x"]).to(ctx.device)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for r in range(reps + 1):
+        if r == 1:
+            torch.cuda.synchronize()
+            ev[0].record()
+        g.garble()
+    ev[1].record()
+    for _ in range(reps):
+        g.encode(x)
+        g.evaluate()
+        g.decode()
+    ev[2].record()
+    torch.cuda.synchronize()
+    work = network_work(net)
+    out = dict(primes=len(net["primes"]), activation_values=sum(L["n"] for L in net["layers"] if L["kind"] == "relu") * net["batch"],
+               gates=work["gates"], table_bytes=g.table_bytes, garble_ms=ev[0].elapsed_time(ev[1]) / reps,
+               eval_ms=ev[1].elapsed_time(ev[2]) / reps, outputs_valid=bool(g.valid.all().item()))
+    del g
+    ctx.close()
+    torch.cuda.empty_cache()
+    return out
+
+
+def micro_mlp(torch, workloads):
+    """Config 1: MLP 784-128-10, batch 1, 8 primes, ReLU + scale 2^6: latency of one inference."""
+    out = latency(torch, workloads.mlp(seed=1, batch=1), reps=10)
+    out["workload"] = "config 1: MLP 784-128-10, batch 1, 8 primes, ReLU + scale 2^6; eval_ms = encode + evaluate + decode of one inference"
+    out["ms_per_inference"] = out["eval_ms"]
+    return out
+
+
+def micro_paper_models(torch, workloads):
     """The shapes of the paper's models A-F (Sec. Model architectures), batch 1, random weights: garbling time
     (offline in the paper) and evaluation time (its online figure, there including a modelled network cost)."""
-    from paper_2302_06361_amd import Context, GarbledNetwork
-    out = {}
-    for name in "ABCDfF":
-        net = workloads.paper_model(name, seed=6)
-        ctx = Context(net["primes"], net["seed"], net["digits"])
-        g = GarbledNetwork(ctx, net)
-        x = torch.as_tensor(net["x"]).to(ctx.device)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        for r in range(reps + 1):
-            if r == 1:
-                torch.cuda.synchronize()
-                ev[0].record()
-            g.garble()
-        ev[1].record()
-        g.encode(x)
-        for _ in range(reps):
-            g.evaluate()
-            g.decode()
-        ev[2].record()
-        torch.cuda.synchronize()
-        out[name] = dict(primes=len(net["primes"]), relu_values=sum(L["n"] for L in net["layers"] if L["kind"] == "relu"),
-                         table_bytes=g.table_bytes, garble_ms=ev[0].elapsed_time(ev[1]) / reps,
-                         eval_ms=ev[1].elapsed_time(ev[2]) / reps, outputs_valid=bool(g.valid.all().item()))
-        del g
-        ctx.close()
-        torch.cuda.empty_cache()
+    out = {name: latency(torch, workloads.paper_model(name, seed=6)) for name in "ABCDfF"}
     return dict(workload="paper model shapes A-F, batch 1, random integer weights and biases", models=out,
                 paper_online_ms_gpu=dict(A=10, B=32, C=16, D=42, f=1332, F=1443),
-                note="the paper's figures (its Table of online runtimes, other hardware) include a modelled 1 Gbit/s transfer; context only")
+                note="the paper's figures (its table of online runtimes, other hardware) include a modelled 1 Gbit/s transfer; context only")
 
 
 def main():
@@ -280,9 +471,11 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--batch", type=int, default=16, help="batch elements of config 2 (16 = the config)")
+    ap.add_argument("--images", type=int, default=2, help="images of config 5's batch of 64 to stream (64 = the whole config, about 11 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-micro", action="store_true", help="skip the config-3 and config-4 microbenchmarks")
-    ap.add_argument("--only", choices=["config3", "config4", "config5", "paper_models"], help="run one microbenchmark alone (for profiling); prints its JSON object")
+    ap.add_argument("--no-micro", action="store_true", help="the config-2 step alone")
+    ap.add_argument("--only", choices=["config1", "config3", "config4", "config5", "paper_models"],
+                    help="run one of the other configurations alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures ONE GPU (every box has one); --gpus %d is not supported" % a.gpus, file=sys.stderr)
@@ -294,7 +487,8 @@ def main():
     from paper_2302_06361_amd import Context, GarbledNetwork
 
     if a.only:
-        fn = dict(config3=micro_projection, config4=micro_contraction, config5=micro_vgg, paper_models=micro_paper_models)[a.only]
+        fn = dict(config1=micro_mlp, config3=micro_projection, config4=micro_contraction,
+                  config5=lambda t, w: micro_vgg(t, w, images=a.images), paper_models=micro_paper_models)[a.only]
         print(json.dumps(fn(torch, workloads)))
         return
 
@@ -302,9 +496,9 @@ def main():
     ctx = Context(net["primes"], net["seed"], net["digits"])
     g = GarbledNetwork(ctx, net)
     x = torch.as_tensor(net["x"]).to(ctx.device)
-    k, n = ctx.k, len(ctx.digits)
     lam_sum = sum(ctx.lam(p) for p in ctx.primes)
-    gates = gate_counts(net, k, n)
+    work = network_work(net)
+    gates = work["gates"]
     macs = mac_counts(net, lam_sum)
 
     # a plain copy of known size, for scaling the HBM counters of a rocprofv3 --pmc run of this command
@@ -352,59 +546,77 @@ def main():
     torch.cuda.synchronize()
     ctx.profile_enable(False)
     prof = read_profiles(ctx)
-
     kg, ke, kl, kd = (kernel_line(prof[n_], a.steps) for n_ in ("garble", "eval", "linear", "garble_digits"))
+    pmc, pmc_note = load_pmc()
 
-    def garble_roofline(kernel, kk, valu, traffic_per_row):
-        r = dict(kernel=kernel, bound="alu", unit="Tlane-instr/s (32-bit integer vector instructions)", peak=ALU_PEAK_TOPS,
-                 achieved=kk["units_per_s"] * valu / 1e12, ms_per_step=kk["ms_per_step"],
+    def garble_roofline(kernel, kk, cls, key):
+        """ALU roofline of a garbling kernel.  achieved = ALGORITHMIC lane operations per launch / average launch duration
+        (frac = frac_algorithmic); frac_issue = executed vector instructions (counter SQ_INSTS_VALU of the committed --pmc
+        summary) on the same clock; hbm_frac = algorithmic bytes against the HBM peak."""
+        alg_per_row = work["ops_garble"][cls] / max(work["rows"][cls], 1)
+        r = dict(kernel=kernel, bound="alu", unit="Tlane-op/s (32-bit integer vector operations)", peak=ALU_PEAK_TOPS,
+                 achieved=kk["units_per_s"] * alg_per_row / 1e12, ms_per_step=kk["ms_per_step"],
                  avg_launch_ms=kk["avg_launch_ms"], launches_per_step=kk["launches_per_step"],
-                 rows_per_launch=kk["units_per_launch"], rows_per_s=kk["units_per_s"], lane_ops_per_row=valu,
+                 rows_per_launch=kk["units_per_launch"], rows_per_s=kk["units_per_s"], algorithmic_lane_ops_per_row=alg_per_row,
                  hbm_algorithmic_GBps=kk["gbytes_per_s"], hbm_frac=kk["gbytes_per_s"] / HBM_PEAK_GBS,
-                 algorithmic_bytes_per_launch=kk["bytes_per_launch"], traffic=traffic_per_row * kk["units_per_launch"])
-        r["frac"] = r["achieved"] / ALU_PEAK_TOPS
+                 algorithmic_bytes_per_launch=kk["bytes_per_launch"], counters=pmc_note)
+        r["frac"] = r["frac_algorithmic"] = r["achieved"] / ALU_PEAK_TOPS
+        if pmc and key + "_valu_per_row" in pmc:
+            r["executed_lane_instr_per_row"] = pmc[key + "_valu_per_row"]
+            r["frac_issue"] = kk["units_per_s"] * pmc[key + "_valu_per_row"] / 1e12 / ALU_PEAK_TOPS
+            r["traffic"] = (pmc[key + "_fetch_bytes_per_row"] + pmc[key + "_write_bytes_per_row"]) * kk["units_per_launch"]
+        else:
+            r["frac_issue"] = r["traffic"] = None
         return r
     # the dominant kernel of the step: the general projection-gate garbler (carry chains, half gates, casts); the
     # digit gates of the sign gadgets run in the fused kernel, reported beside it
-    roofline = garble_roofline("k_proj_garble", kg, PMC["garble_valu_per_row"],
-                               PMC["garble_fetch_bytes_per_row"] + PMC["garble_write_bytes_per_row"])
-    roofline_digits = garble_roofline("k_digits_garble", kd, PMC["digits_valu_per_row"],
-                                      PMC["digits_fetch_bytes_per_row"] + PMC["digits_write_bytes_per_row"]) if kd else None
-    ev_valu = PMC["eval_valu_per_gate"]
+    roofline = garble_roofline("k_proj_garble", kg, "gate", "garble")
+    roofline_digits = garble_roofline("k_digits_garble", kd, "digits", "digits") if kd else None
+    alg_eval = work["ops_eval"] / gates
     roofline_eval = dict(kernel="k_digits_eval + k_chain_eval + k_cast_halve + k_proj_eval", bound="alu", unit=roofline["unit"], peak=ALU_PEAK_TOPS,
-                         achieved=ke["units_per_s"] * ev_valu / 1e12 if ev_valu else None,
-                         avg_launch_ms=ke["avg_launch_ms"], launches_per_step=ke["launches_per_step"],
+                         achieved=ke["units_per_s"] * alg_eval / 1e12, algorithmic_lane_ops_per_gate=alg_eval,
+                         ms_per_step=ke["ms_per_step"], avg_launch_ms=ke["avg_launch_ms"], launches_per_step=ke["launches_per_step"],
                          gates_per_s=ke["units_per_s"], hbm_algorithmic_GBps=ke["gbytes_per_s"],
                          hbm_frac=ke["gbytes_per_s"] / HBM_PEAK_GBS)
-    roofline_eval["frac"] = roofline_eval["achieved"] / ALU_PEAK_TOPS if roofline_eval["achieved"] else None
+    roofline_eval["frac"] = roofline_eval["frac_algorithmic"] = roofline_eval["achieved"] / ALU_PEAK_TOPS
+    roofline_eval["frac_issue"] = (ke["units_per_s"] * pmc["eval_valu_per_gate"] / 1e12 / ALU_PEAK_TOPS) if pmc and "eval_valu_per_gate" in pmc else None
 
+    config2 = dict(
+        workload="config 2: LeNet-5 shape, batch %d, 8-prime CRT base, 128-bit labels (ceil rule), "
+                 "ReLU + scale 2^6 after every conv/dense but the last" % a.batch,
+        ms_per_step=ms_step, outputs_valid=ok,
+        gates_per_s=2 * gates / (ms_step * 1e-3), garble_gates_per_s=gates / (phase[0] * 1e-3), eval_gates_per_s=gates / (phase[2] * 1e-3),
+        ms_per_inference=ms_step / a.batch, ms_per_inference_eval=(phase[1] + phase[2] + phase[3]) / a.batch,
+        ms_per_inference_garble=phase[0] / a.batch,
+        phase_ms=dict(garble=phase[0], encode=phase[1], eval=phase[2], decode=phase[3]),
+        gates_per_step=gates, label_macs_per_step=2 * macs, table_bytes=g.table_bytes,
+        linear_kernels=dict(ms_per_step=kl["ms_per_step"], label_mac_per_s=kl["units_per_s"],
+                            note="config-2 linear layers are tiny (launch-bound); config 4 is the contraction figure"))
     out = dict(
         metric="label-MAC/s + projection gates/s (garble & eval); ms/inference, 1 GPU",
         value=2 * gates / (ms_step * 1e-3),
         unit="projection gates/s (garbled + evaluated, whole step: garble+encode+eval+decode)",
         n_gpus=1, steps=a.steps, warmup=a.warmup, ms_per_step=ms_step, higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="u8 digits, i32 accumulate", data="synthetic",
-        config=dict(workload="config 2: LeNet-5 shape, batch %d, 8-prime CRT base, 128-bit labels (ceil rule), "
-                             "ReLU + scale 2^6 after every conv/dense but the last" % a.batch,
+        config=dict(workload=config2["workload"] + "; the other four configurations are in `configs`",
                     batch=a.batch, primes=ctx.primes, sign_digits=ctx.digits, table_bytes=g.table_bytes),
         outputs_valid=ok,
-        garble_gates_per_s=gates / (phase[0] * 1e-3),
-        eval_gates_per_s=gates / (phase[2] * 1e-3),
-        ms_per_inference=ms_step / a.batch,
-        ms_per_inference_eval=phase[2] / a.batch,
-        ms_per_inference_garble=phase[0] / a.batch,
-        phase_ms=dict(garble=phase[0], encode=phase[1], eval=phase[2], decode=phase[3]),
-        gates_per_step=gates, label_macs_per_step=2 * macs,
+        garble_gates_per_s=config2["garble_gates_per_s"], eval_gates_per_s=config2["eval_gates_per_s"],
+        ms_per_inference=config2["ms_per_inference"], ms_per_inference_eval=config2["ms_per_inference_eval"],
+        ms_per_inference_garble=config2["ms_per_inference_garble"],
         roofline=roofline, roofline_digits_kernel=roofline_digits, roofline_eval_kernel=roofline_eval,
-        linear_kernels_config2=dict(ms_per_step=kl["ms_per_step"], label_mac_per_s=kl["units_per_s"],
-                                    note="config-2 linear layers are tiny (launch-bound); config 4 below is the contraction figure"),
     )
     del g
     ctx.close()
     torch.cuda.empty_cache()
+    configs = dict(config2=config2)
     if not a.no_micro:
-        out["config3_projection_gates"] = micro_projection(torch, workloads)
-        out["config4_contraction"] = micro_contraction(torch, workloads)
+        configs["config1"] = micro_mlp(torch, workloads)
+        configs["config3"] = micro_projection(torch, workloads)
+        configs["config4"] = micro_contraction(torch, workloads)
+        configs["config5"] = micro_vgg(torch, workloads, images=a.images)
+        configs["paper_models"] = micro_paper_models(torch, workloads)
+    out["configs"] = {k: configs[k] for k in sorted(configs)}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(net)
     print(json.dumps(out))

@@ -162,7 +162,8 @@ int dash_eval_layer_noalloc(dash_ctx *ctx, const dash_layer *layer, const dash_l
 /* e: zero labels of circuit-input wires first_wire .. first_wire + zero->n_elem - 1, every residue. */
 int dash_input_labels(dash_ctx *ctx, int64_t first_wire, dash_labels *zero, void *hip_stream);
 /* En: out = zero + (value mod p) * R_p (Sec. Quantization and Encoding: Encode(x) = x mod P).
- * values: device int64 [n]. */
+ * values: device int64 [n].  A residue whose data pointer is NULL in both bundles is skipped (bundles that carry
+ * a single residue, as the inputs of PROJ gates do); NULL in only one of them is DASH_EINVAL. */
 int dash_encode(dash_ctx *ctx, const int64_t *values, int64_t n, const dash_labels *zero, dash_labels *out,
                 void *hip_stream);
 /* De: per element, the residue a_i with act = zero + a_i * R_p on every digit, CRT-reconstructed and

@@ -457,13 +457,18 @@ int dash_input_labels(dash_ctx* c, int64_t first_wire, dash_labels* zero, void* 
 }
 
 int dash_encode(dash_ctx* c, const int64_t* values, int64_t n, const dash_labels* zero, dash_labels* out, void* stream) {
-    if (!c || (!values && n > 0) || n < 0) return DASH_EINVAL;
+    if (!c || !zero || !out || (!values && n > 0) || n < 0) return DASH_EINVAL;
     if (n > 0x7fffffff) return DASH_ESIZE;
-    int st = check_labels(c, zero, n);
-    if (!st) st = check_labels(c, out, n);
-    if (st) return st;
+    if (zero->n_elem < n || out->n_elem < n) return DASH_EINVAL;
+    for (int i = 0; i < c->k; i++) {
+        if (!zero->data[i] && !out->data[i]) continue;      // residue not present in either bundle: skipped
+        int st = check_labels(c, zero, n, i);
+        if (!st) st = check_labels(c, out, n, i);
+        if (st) return st;
+    }
     if (n == 0) return DASH_OK;
     for (int i = 0; i < c->k; i++) {
+        if (!zero->data[i] && !out->data[i]) continue;
         hipLaunchKernelGGL(k_encode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream,
                            c->d_mods, (uint32_t)c->prime[i], values, (uint32_t)n, view_of(zero, i), view_of(out, i));
     }

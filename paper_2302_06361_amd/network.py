@@ -27,8 +27,10 @@ def build_layers(ctx, net, b, batch_base):
             lay = B.Layer(B.SUMPOOL, L["id"], b, in_h=L["in_h"], in_w=L["in_w"], in_c=L["ch"])
         elif kind in ("relu", "sign"):
             lay = B.Layer(B.RELU if kind == "relu" else B.SIGN, L["id"], n * b, elem_base=batch_base * n)
+            lay.per_batch_element = n
         elif kind == "scale":
             lay = B.Layer(B.SCALE, L["id"], n * b, elem_base=batch_base * n, repeat=L["repeat"])
+            lay.per_batch_element = n
         else:
             raise ValueError(kind)
         oe, tb, sb = ctx.layer_sizes(lay)
@@ -101,6 +103,14 @@ class StreamedNetwork:
         self.values = torch.empty(self.sizes[-1], dtype=torch.int64, device=ctx.device)
         self.valid = torch.empty(self.sizes[-1], dtype=torch.uint8, device=ctx.device)
         self.table_bytes = sum(self.layer_table_bytes)
+
+    def rebase(self):
+        """after a change of self.batch_base: the same buffers and descriptors serve the next chunk of the batch (element
+        and wire indices of a chunk start at its first batch element)"""
+        for lay in self.layers:
+            n = getattr(lay, "per_batch_element", None)
+            if n is not None:
+                lay.c.elem_base = self.batch_base * n
 
     def run(self, x_dev, on_boundary=None):
         """Gb, En, Ev, De over the whole network.  on_boundary(b, zero, act) sees the label bundles of
