@@ -145,6 +145,20 @@ int dash_garble_layer(dash_ctx *ctx, const dash_layer *layer, const dash_labels 
 int dash_eval_layer(dash_ctx *ctx, const dash_layer *layer, const dash_labels *in_act, const void *tables,
                     dash_labels *out_act, void *scratch, void *hip_stream);
 
+/* n independent layer calls in one (Sec. LabelTensors: gates of the same kind are processed together as tensors): the
+ * result is that of dash_garble_layer (dash_eval_layer) on (layers[i], in[i], out[i], tables[i], scratch[i]) for
+ * i = 0 .. n-1, and no call of the list may read what another one writes.  The library may serve several calls with
+ * one kernel launch: PROJ calls with the same layer_id and the same output modulus share launches of up to 16 calls
+ * (the 144 (p, q) groups of a mixed batch of independent gates take 12 gate launches instead of 144); other kinds are
+ * run in turn.  layers, in, out: host arrays of n entries; tables, scratch: host arrays of n device pointers (an entry
+ * may be NULL where dash_layer_sizes gives 0; scratch itself may be NULL if no call needs scratch).  If the list holds
+ * PROJ calls only, nothing is launched when the argument check of any call fails; otherwise the calls before the
+ * failing one have been enqueued. */
+int dash_garble_layers(dash_ctx *ctx, int n, const dash_layer *layers, const dash_labels *in_zero, dash_labels *out_zero,
+                       void *const *tables, void *const *scratch, void *hip_stream);
+int dash_eval_layers(dash_ctx *ctx, int n, const dash_layer *layers, const dash_labels *in_act, const void *const *tables,
+                     dash_labels *out_act, void *const *scratch, void *hip_stream);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, serving loops with a fixed memory
  * budget, harnesses that forbid hipMalloc): dash_eval_layer with the scratch buffer taken from a fixed array of
  * DASH_NOALLOC_SCRATCH_BYTES that lives inside the library (one copy per GPU, held until the process ends; its

@@ -19,7 +19,7 @@ NOALLOC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
+           "dash_garble_layers", "dash_eval_layers", "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
 
 
 class DashError(RuntimeError):
@@ -247,6 +247,24 @@ class Context:
                                         C.c_void_p(tables.data_ptr() if tables is not None else 0),
                                         C.c_void_p(scratch.data_ptr() if scratch is not None else 0), _stream()),
                "dash_garble_layer")
+
+    def _layer_lists(self, layers, ins, outs, tables, scratch):
+        n = len(layers)
+        cl = (CLayer * n)(*[l.c for l in layers])
+        ci = (CLabels * n)(*[t.c() for t in ins])
+        co = (CLabels * n)(*[t.c() for t in outs])
+        ct = (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in tables])
+        cs = None if scratch is None else (C.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in scratch])
+        return n, cl, ci, co, ct, cs
+
+    def garble_layers(self, layers, in_zero, out_zero, tables, scratch=None):
+        """n independent layer calls in one ABI call (lists of equal length)"""
+        n, cl, ci, co, ct, cs = self._layer_lists(layers, in_zero, out_zero, tables, scratch)
+        _check(self.L.dash_garble_layers(self.h, n, cl, ci, co, ct, cs, _stream()), "dash_garble_layers")
+
+    def eval_layers(self, layers, in_act, tables, out_act, scratch=None):
+        n, cl, ci, co, ct, cs = self._layer_lists(layers, in_act, out_act, tables, scratch)
+        _check(self.L.dash_eval_layers(self.h, n, cl, ci, ct, co, cs, _stream()), "dash_eval_layers")
 
     def eval_layer_noalloc(self, layer, in_act, tables, out_act):
         """dash_eval_layer with the library's own fixed scratch array (NOALLOC_SCRATCH_BYTES): allocates nothing"""

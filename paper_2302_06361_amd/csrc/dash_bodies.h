@@ -40,9 +40,9 @@ template <class Tab>
 DASH_HD void draw_body(const DrawLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
     const DrawJob& J = L.jobs[by];
     uint32_t e = bx * kThreads + tx;
-    if (e >= L.n_elem) return;
+    if (e >= J.n_elem) return;
     const ModInfo M = L.mods[J.m];
-    U128 h = prg_block(L.elem_base + e, J.slot, L.layer, J.domain, J.m, L.key.rk, T);
+    U128 h = prg_block(J.elem_base + e, J.slot, L.layer, J.domain, J.m, L.key.rk, T);
     if (J.digit0_only) { J.out.p[e] = (uint8_t)mod_u128(h, M); return; }
     with_mod(M, [&](auto Q) {
         decompress(Q, h, [&](int i, uint32_t w) { st_dw(J.out, e, i, w); });
@@ -101,12 +101,12 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
     // The block's first row is divided once (scalar unit); the lane's offset from it is small enough
     // for the 24-bit magic division.
     const uint64_t r0 = (uint64_t)bx * kThreads;
-    if (r0 >= (uint64_t)L.n_elem * Mp.m) return;
+    if (r0 >= (uint64_t)J.n_elem * Mp.m) return;
     const uint32_t g0 = (uint32_t)(r0 / Mp.m);
     const uint32_t off = (uint32_t)(r0 - (uint64_t)g0 * Mp.m) + tx;
     const uint32_t dg = div_m(off, Mp);
     const uint32_t g = g0 + dg, a = off - dg * Mp.m;
-    if (g >= L.n_elem) return;
+    if (g >= J.n_elem) return;
 
     // label of value a on the input wire: zero label + a * R_p (row a of the table of offset multiples)
     uint32_t colour = 0;
@@ -115,7 +115,7 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
         const uint32_t* da = P.dtab + a * P.ndw;
         K = compress(P, [&](int i) { return addmod4(ld_dw(J.in, g, i), gload32(da + i), P); }, &colour);
     });
-    U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
+    U128 h = hash_block(K, J.elem_base + g, J.slot, L.layer, L.key.rk, T);
 
     // the output modulus: the kernel's compile-time description, or the run-time record (the instantiation for any
     // modulus, which also serves launches that mix output moduli; choosing a compile-time description per job inside
@@ -163,7 +163,7 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
     const GateJob& J = L.jobs[by];
     const ModInfo Mp = L.mods[J.p], Mq = L.mods[J.q];
     uint32_t g = bx * kThreads + tx;
-    if (g >= L.n_elem) return;
+    if (g >= J.n_elem) return;
     uint32_t colour = ld_dw(J.in, g, 0) & 0xffu;
     U128 K = {{0, 0, 0, 0}};
     with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(J.in, g, i); }, &colour); });
@@ -177,7 +177,7 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
 #pragma unroll
             for (int i = 0; i < (int)QT::ndw; i++) rw[i] = row[i];
         }
-        U128 h = hash_block(K, L.elem_base + g, J.slot, L.layer, L.key.rk, T);
+        U128 h = hash_block(K, J.elem_base + g, J.slot, L.layer, L.key.rk, T);
         if constexpr (cmod_m<QT>::value != 0) {
             decompress(Q, h, [&](int i, uint32_t hd) { st_dw(J.out, g, i, submod4(rw[i], hd, Q)); });
         } else {

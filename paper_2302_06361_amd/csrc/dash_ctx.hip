@@ -340,8 +340,8 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
         for (int m = 2; m < 256 && !fail; m++) if (used[m]) {
             DrawLaunch L;
             memset(&L, 0, sizeof(L));
-            L.elem_base = 0; L.layer = 0; L.n_elem = 1;
-            L.jobs[0] = DrawJob{(uint32_t)m, DOM_DELTA, 0, 0, LView{c->d_delta[m], 16, 16}};
+            L.layer = 0;
+            L.jobs[0] = DrawJob{(uint32_t)m, DOM_DELTA, 0, 0, LView{c->d_delta[m], 16, 16}, 0, 1u, 0u};
             if (launch_draw(c, L, 1, 0) != DASH_OK) { fail = true; break; }
             hipLaunchKernelGGL(k_delta_tab, dim3((m + 63) / 64), dim3(64), 0, 0, c->mods[m], c->d_delta[m],
                                (uint32_t*)(c->d_pool + off_dtab[m]));
@@ -353,8 +353,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
             int p = c->prime[i];
             DrawLaunch L;
             memset(&L, 0, sizeof(L));
-            L.n_elem = 1;
-            L.jobs[0] = DrawJob{(uint32_t)p, DOM_ONE, 0, 0, LView{c->d_one0[i], 16, 16}};
+            L.jobs[0] = DrawJob{(uint32_t)p, DOM_ONE, 0, 0, LView{c->d_one0[i], 16, 16}, 0, 1u, 0u};
             if (launch_draw(c, L, 1, 0) != DASH_OK) { fail = true; break; }
             AffineLaunch A;
             memset(&A, 0, sizeof(A));
@@ -451,8 +450,8 @@ int dash_input_labels(dash_ctx* c, int64_t first_wire, dash_labels* zero, void* 
     if (st) return st;
     DrawLaunch L;
     memset(&L, 0, sizeof(L));
-    L.elem_base = (uint64_t)first_wire; L.layer = 0; L.n_elem = (uint32_t)n;
-    for (int i = 0; i < c->k; i++) L.jobs[i] = DrawJob{(uint32_t)c->prime[i], DOM_INPUT, 0, 0, view_of(zero, i)};
+    L.layer = 0;
+    for (int i = 0; i < c->k; i++) L.jobs[i] = DrawJob{(uint32_t)c->prime[i], DOM_INPUT, 0, 0, view_of(zero, i), (uint64_t)first_wire, (uint32_t)n, 0u};
     return launch_draw(c, L, c->k, (hipStream_t)stream);
 }
 
@@ -563,6 +562,29 @@ int dash_eval_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_act,
     return run_layer(c, L, false, in_act, out_act, (uint8_t*)tables, (uint8_t*)scratch, (hipStream_t)stream);
 }
 
+
+// n independent layer calls: lists of PROJ calls go to the launcher that merges them, anything else is run in turn
+static int run_layers(dash_ctx* c, bool garble, int n, const dash_layer* Ls, const dash_labels* ins, dash_labels* outs, void* const* tables,
+                      void* const* scratch, hipStream_t s) {
+    if (!c || n < 0 || (n > 0 && (!Ls || !ins || !outs))) return DASH_EINVAL;
+    bool all_proj = n > 0;
+    for (int i = 0; i < n; i++) if (Ls[i].kind != DASH_PROJ) all_proj = false;
+    if (all_proj) return proj_layers(c, garble, n, Ls, ins, outs, (uint8_t* const*)tables, s);
+    for (int i = 0; i < n; i++) {
+        const int st = run_layer(c, Ls + i, garble, ins + i, outs + i, tables ? (uint8_t*)tables[i] : nullptr,
+                                 scratch ? (uint8_t*)scratch[i] : nullptr, s);
+        if (st) return st;
+    }
+    return DASH_OK;
+}
+int dash_garble_layers(dash_ctx* c, int n, const dash_layer* layers, const dash_labels* in_zero, dash_labels* out_zero, void* const* tables,
+                       void* const* scratch, void* stream) {
+    return run_layers(c, true, n, layers, in_zero, out_zero, tables, scratch, (hipStream_t)stream);
+}
+int dash_eval_layers(dash_ctx* c, int n, const dash_layer* layers, const dash_labels* in_act, const void* const* tables, dash_labels* out_act,
+                     void* const* scratch, void* stream) {
+    return run_layers(c, false, n, layers, in_act, out_act, (void* const*)tables, scratch, (hipStream_t)stream);
+}
 
 int dash_eval_layer_noalloc(dash_ctx* c, const dash_layer* L, const dash_labels* in_act, const void* tables, dash_labels* out_act,
                             void* stream) {

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_draw(const DrawLa
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     __shared__ uint32_t tt[gate_tab<Banked>::words];
     const auto T = gate_tab<Banked>::load(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    const uint32_t tiles = (L.jobs[blockIdx.y].n_elem + kThreads - 1) / kThreads;
     const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
     for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) draw_body(L, tile, blockIdx.y, tx, T);
 }
@@ -31,11 +31,17 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_draw(const DrawLa
 int launch_draw(const dash_ctx* c, DrawLaunch& L, int njobs, hipStream_t s) {
     static_assert(sizeof(DrawLaunch) <= 4096, "kernel argument block");
     if (njobs < 1 || njobs > kMaxDrawJobs) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    uint64_t lanes = 0;
+    uint32_t nmax = 0;
+    for (int j = 0; j < njobs; j++) {
+        if (L.jobs[j].n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+        lanes += L.jobs[j].n_elem;
+        nmax = L.jobs[j].n_elem > nmax ? L.jobs[j].n_elem : nmax;
+    }
+    if (nmax == 0) return DASH_OK;
     L.key = c->seed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
-    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
+    const bool banked = lanes >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((nmax + kThreads - 1) / kThreads, njobs, banked), njobs);
     if (banked) hipLaunchKernelGGL(k_draw<true>, grid, dim3(kBigThreads), 0, s, L);
     else hipLaunchKernelGGL(k_draw<false>, grid, dim3(kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
@@ -89,7 +95,7 @@ template <class QD, bool Banked>
 __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const GateLaunch L) {
     static_assert(!(stage_rows<QD>::value && Banked), "staged rows use the shared tables");
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
-    const uint64_t rows = (uint64_t)L.n_elem * L.jobs[blockIdx.y].p;
+    const uint64_t rows = (uint64_t)L.jobs[blockIdx.y].n_elem * L.jobs[blockIdx.y].p;      // (unused by the one-dimensional banked form)
     const uint32_t tiles = (uint32_t)((rows + kThreads - 1) / kThreads);
     if constexpr (stage_rows<QD>::value) {
         __shared__ uint32_t tt[kTabWords];
@@ -122,7 +128,7 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const
         if constexpr (Banked) {
             // one-dimensional grid: the jobs differ in length (n_elem * p rows), so the blocks share the
             // concatenation of all jobs' tiles evenly.  job, base and next are the same in all lanes of a wave.
-            auto tiles_of = [&](uint32_t j) { return (uint32_t)(((uint64_t)L.n_elem * L.jobs[j].p + kThreads - 1) / kThreads); };
+            auto tiles_of = [&](uint32_t j) { return (uint32_t)(((uint64_t)L.jobs[j].n_elem * L.jobs[j].p + kThreads - 1) / kThreads); };
             uint32_t total = 0;
             for (uint32_t j = 0; j < L.njobs; j++) total += tiles_of(j);
             uint32_t job = 0, base = 0, next = tiles_of(0);
@@ -218,26 +224,25 @@ int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
 
 int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
-    uint32_t pmax = 0;
-    for (int j = 0; j < njobs; j++) {
-        const GateJob& J = L.jobs[j];
-        if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
-        if (!J.in.p || !J.table) return DASH_EINVAL;
-        pmax = J.p > pmax ? J.p : pmax;
-    }
-    uint64_t rows = (uint64_t)L.n_elem * pmax;
-    uint64_t blocks = (rows + kThreads - 1) / kThreads;
-    if (blocks > 0x7fffffffull) return DASH_ESIZE;
+    uint64_t rows = 0, tiles_sum = 0;      // rows of the largest job; tiles of all jobs
     double units = 0, bytes = 0;
     for (int j = 0; j < njobs; j++) {
         const GateJob& J = L.jobs[j];
-        double lp = c->mods[J.p].lam, lq = J.mode == PAY_SHORT ? 1 : c->mods[J.q].lam;
-        units += (double)L.n_elem * J.p;
-        bytes += (double)L.n_elem * (lp + (J.phi_stride ? J.p : 0) + lq + J.p * lq + (J.mode == PAY_EHALF ? lq : 0));
+        if (J.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+        if (J.n_elem == 0) continue;
+        if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
+        if (!J.in.p || !J.table) return DASH_EINVAL;
+        const uint64_t r = (uint64_t)J.n_elem * J.p;
+        rows = r > rows ? r : rows;
+        tiles_sum += (r + kThreads - 1) / kThreads;
+        const double lp = c->mods[J.p].lam, lq = J.mode == PAY_SHORT ? 1 : c->mods[J.q].lam;
+        units += (double)r;
+        bytes += (double)J.n_elem * (lp + (J.phi_stride ? J.p : 0) + lq + J.p * lq + (J.mode == PAY_EHALF ? lq : 0));
     }
+    if (rows == 0) return DASH_OK;
+    const uint64_t blocks = (rows + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffull || tiles_sum > 0x7fffffffull) return DASH_ESIZE;
     // jobs with one output modulus run its instantiation; a mix of output moduli (many small batches
     // in one launch) runs the instantiation with run-time constants
     const uint32_t q = common_q(L, njobs);
@@ -248,9 +253,7 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     L.njobs = (uint32_t)njobs;
     dim3 grid(gate_grid_x_for(blocks, njobs, banked), njobs);
     if (banked) {       // one-dimensional: all jobs' tiles, 1024 lanes (4 tiles) per block at a time, two blocks per CU
-        uint64_t tiles = 0;
-        for (int j = 0; j < njobs; j++) tiles += ((uint64_t)L.n_elem * L.jobs[j].p + kThreads - 1) / kThreads;
-        const uint64_t nb = (tiles + 3) / 4;
+        const uint64_t nb = (tiles_sum + 3) / 4;
         grid = dim3((uint32_t)(nb < 512 ? nb : 512));
     }
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_eval(const G
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     __shared__ uint32_t tt[gate_tab<Banked>::words];
     const auto T = gate_tab<Banked>::load(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    const uint32_t tiles = (L.jobs[blockIdx.y].n_elem + kThreads - 1) / kThreads;
     const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
     for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles) eval_body<QD>(L, tile, blockIdx.y, tx, T);
 }
@@ -32,20 +32,26 @@ static const GateKernel kEvalKernelsBanked[] = {k_proj_eval<ModInfo, true>, DASH
 
 int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
-    if (L.n_elem == 0) return DASH_OK;
-    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
     L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    uint64_t lanes = 0;
+    uint32_t nmax = 0;
+    double bytes = 0;
     for (int j = 0; j < njobs; j++) {
         const GateJob& J = L.jobs[j];
+        if (J.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+        if (J.n_elem == 0) continue;
         if (J.p < 2 || J.p > 255 || J.q < 2 || J.q > 255 || !c->mods[J.p].dtab || !c->mods[J.q].dtab) return DASH_EINVAL;
         if (!J.in.p || !J.table || !J.out.p) return DASH_EINVAL;
+        lanes += J.n_elem;
+        nmax = J.n_elem > nmax ? J.n_elem : nmax;
+        bytes += (double)J.n_elem * (c->mods[J.p].lam + 2.0 * c->mods[J.q].lam);
     }
-    const bool banked = (uint64_t)L.n_elem * njobs >= c->banked_min_lanes;
-    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, njobs, banked), njobs);
-    double bytes = 0;
-    for (int j = 0; j < njobs; j++) bytes += (double)L.n_elem * (c->mods[L.jobs[j].p].lam + 2.0 * c->mods[L.jobs[j].q].lam);
+    if (nmax == 0) return DASH_OK;
+    const bool banked = lanes >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((nmax + kThreads - 1) / kThreads, njobs, banked), njobs);
     const uint32_t q = common_q(L, njobs);
-    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs, bytes);
+    L.njobs = (uint32_t)njobs;
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)lanes, bytes);
     const int ki = q ? hot_mod_index(c->mods[q]) : 0;
     hipLaunchKernelGGL(banked ? kEvalKernelsBanked[ki] : kEvalKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());

@@ -89,6 +89,8 @@ int activation_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_l
                      uint8_t* tables, uint8_t* scratch, hipStream_t s);
 int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out,
                uint8_t* tables, hipStream_t s);
+int proj_layers(dash_ctx* c, bool garble, int n, const dash_layer* Ls, const dash_labels* ins, dash_labels* outs, uint8_t* const* tables,
+                hipStream_t s);
 
 // linear layers (dash_linear.hip)
 int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s);

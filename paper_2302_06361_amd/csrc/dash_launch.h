@@ -8,7 +8,7 @@
 namespace dash {
 
 constexpr int kMaxJobs = 16;    // gate batches per launch (blockIdx.y)
-constexpr int kMaxDrawJobs = 80;   // label draws per launch: all fresh zero labels of a sign gadget (their jobs are small)
+constexpr int kMaxDrawJobs = 64;   // label draws per launch: all fresh zero labels of a base-8 sign gadget (their jobs are small)
 constexpr int kMaxTerms = 64;   // label terms per launch, shared by its jobs
 constexpr int kThreads = 256;
 constexpr int kMaxChain = 16;   // mixed-radix digits of the sign gadget
@@ -45,6 +45,9 @@ struct GateJob {
     uint8_t* table;           // segment base
     const uint8_t* r;         // PAY_MULR / EHALF / SHORT: mask per element
     LView x0;                 // PAY_EHALF: zero labels of the x wire
+    uint64_t elem_base;       // index of the job's gate 0 inside its layer (hash tweaks)
+    uint32_t n_elem;          // gates of this job (the jobs of one launch may differ in size)
+    uint32_t pad2_;
 };
 
 struct AesKey { uint32_t rk[44]; };
@@ -53,25 +56,24 @@ struct GateLaunch {
     AesKey key;
     const uint32_t* ttab;       // device [4][256]
     const ModInfo* mods;        // device [256]
-    uint64_t elem_base;
     uint32_t layer;
-    uint32_t n_elem;
     uint32_t njobs;             // set by the launcher
-    uint32_t pad_;
     GateJob jobs[kMaxJobs];
 };
 
 struct DrawJob {
     uint32_t m, domain, slot, digit0_only;
     LView out;       // digit0_only: out.p is a byte array [n_elem]
+    uint64_t elem_base;   // PRG counter of the job's element 0
+    uint32_t n_elem;      // labels of this job (the jobs of one launch may differ in size)
+    uint32_t pad_;
 };
 struct DrawLaunch {
     AesKey key;
     const uint32_t* ttab;
     const ModInfo* mods;
-    uint64_t elem_base;
     uint32_t layer;
-    uint32_t n_elem;
+    uint32_t pad_;
     DrawJob jobs[kMaxDrawJobs];
 };
 

@@ -6,6 +6,9 @@
 // over all elements of the layer; gates at the same depth of the gadget share one launch.
 #include <string.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "dash_internal.h"
 
 namespace dash {
@@ -90,17 +93,19 @@ void plan_sign(const dash_ctx* c, Arena& ar, int64_t E, int first_res, SignWires
 struct GateBatcher {
     static constexpr int kSlots = 4;
     const dash_ctx* c; bool garble; hipStream_t s; bool mixed = false;
+    uint32_t E; uint64_t elem_base;      // of the jobs that do not bring their own
     GateLaunch L[kSlots]; int nj[kSlots]; int status = DASH_OK;
-    GateBatcher(const dash_ctx* c_, bool g, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_, bool mixed_ = false)
-        : c(c_), garble(g), s(s_), mixed(mixed_) {
+    GateBatcher(const dash_ctx* c_, bool g, uint32_t E_, uint32_t layer, uint64_t elem_base_, hipStream_t s_, bool mixed_ = false)
+        : c(c_), garble(g), s(s_), mixed(mixed_), E(E_), elem_base(elem_base_) {
         memset(L, 0, sizeof(L));
-        for (int t = 0; t < kSlots; t++) { L[t].n_elem = E; L[t].layer = layer; L[t].elem_base = elem_base; nj[t] = 0; }
+        for (int t = 0; t < kSlots; t++) { L[t].layer = layer; nj[t] = 0; }
     }
     void launch(int t) {
         if (nj[t] && status == DASH_OK) status = garble ? launch_garble(c, L[t], nj[t], s) : launch_eval(c, L[t], nj[t], s);
         nj[t] = 0;
     }
-    void add(const GateJob& J) {
+    void add(GateJob J, bool own_range = false) {      // own_range: J.n_elem and J.elem_base are set by the caller
+        if (!own_range) { J.n_elem = E; J.elem_base = elem_base; }
         int t = -1, free_slot = -1;
         for (int u = 0; u < kSlots; u++) {
             if (nj[u] && (mixed || L[u].jobs[0].q == J.q)) t = u;
@@ -116,13 +121,15 @@ struct GateBatcher {
 };
 struct DrawBatcher {
     const dash_ctx* c; hipStream_t s; DrawLaunch L; int nj = 0, status = DASH_OK;
-    DrawBatcher(const dash_ctx* c_, uint32_t E, uint32_t layer, uint64_t elem_base, hipStream_t s_) : c(c_), s(s_) {
+    uint32_t E; uint64_t elem_base;
+    DrawBatcher(const dash_ctx* c_, uint32_t E_, uint32_t layer, uint64_t elem_base_, hipStream_t s_) : c(c_), s(s_), E(E_), elem_base(elem_base_) {
         memset(&L, 0, sizeof(L));
-        L.n_elem = E; L.layer = layer; L.elem_base = elem_base;
+        L.layer = layer;
     }
-    void add(int m, int domain, uint32_t slot, LView out, bool digit0 = false) {
+    void add(int m, int domain, uint32_t slot, LView out, bool digit0 = false) { add_range(m, domain, slot, out, E, elem_base, digit0); }
+    void add_range(int m, int domain, uint32_t slot, LView out, uint32_t n, uint64_t base, bool digit0 = false) {
         if (nj == kMaxDrawJobs) flush();
-        L.jobs[nj++] = DrawJob{(uint32_t)m, (uint32_t)domain, slot, digit0 ? 1u : 0u, out};
+        L.jobs[nj++] = DrawJob{(uint32_t)m, (uint32_t)domain, slot, digit0 ? 1u : 0u, out, base, n, 0u};
     }
     void flush() { if (nj && status == DASH_OK) status = launch_draw(c, L, nj, s); nj = 0; }
 };
@@ -564,29 +571,68 @@ int activation_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_l
 }
 
 // n independent gates Z_p -> Z_q with per-gate function tables (the projection-gate microbenchmark)
-int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables, hipStream_t s) {
+static int check_proj(const dash_ctx* c, const dash_layer* L, const dash_labels* in, const dash_labels* out, const uint8_t* tables) {
+    if (!L || !in || !out || L->kind != DASH_PROJ) return DASH_EINVAL;
+    if (L->layer_id < 0 || L->layer_id > 65535 || L->elem_base < 0 || L->n_elem < 0) return DASH_EINVAL;
     if (L->n_elem > 0x7fffffff) return DASH_ESIZE;
     if (L->n_elem == 0) return DASH_OK;
     if (L->p_index < 0 || L->p_index >= c->k || L->q_index < 0 || L->q_index >= c->k) return DASH_EINVAL;
     if (!L->phi || !tables || ((uintptr_t)tables & 3)) return DASH_EINVAL;
-    const int pi = L->p_index, qi = L->q_index, p = c->prime[pi], q = c->prime[qi];
+    const int pi = L->p_index, qi = L->q_index, p = c->prime[pi];
     if (L->phi_stride != 0 && L->phi_stride != p) return DASH_EINVAL;
     if (!in->data[pi] || !out->data[qi] || in->n_elem < L->n_elem || out->n_elem < L->n_elem) return DASH_EINVAL;
     if (((uintptr_t)in->data[pi] & 15) || ((uintptr_t)out->data[qi] & 15) || (in->chunk_stride[pi] & 15) || (out->chunk_stride[qi] & 15) ||
         in->chunk_stride[pi] < 16 * L->n_elem || out->chunk_stride[qi] < 16 * L->n_elem) return DASH_EINVAL;
-    const uint32_t E = (uint32_t)L->n_elem;
-    if (garble) {
-        DrawBatcher db(c, E, L->layer_id, L->elem_base, s);
-        db.add(q, DOM_GATE, 0, view_of(out, qi));
-        db.flush();
-        if (db.status) return db.status;
+    return DASH_OK;
+}
+
+// Several independent PROJ calls at once: calls with the same layer id and output modulus share gate launches (up to
+// kMaxJobs per launch, each job with its own gate count and element base), and all fresh zero labels of a layer id
+// are drawn in shared launches.
+int proj_layers(dash_ctx* c, bool garble, int n, const dash_layer* Ls, const dash_labels* ins, dash_labels* outs, uint8_t* const* tables,
+                hipStream_t s) {
+    for (int i = 0; i < n; i++) {
+        const int st = check_proj(c, Ls + i, ins + i, outs + i, tables ? tables[i] : nullptr);
+        if (st) return st;
     }
-    GateBatcher gb(c, garble, E, L->layer_id, L->elem_base, s);
-    GateJob J = phi_job(p, q, view_of(in, pi), L->phi, 0, view_of(out, qi), tables);
-    J.phi_stride = (uint32_t)L->phi_stride;
-    gb.add(J);
-    gb.flush();
-    return gb.status;
+    std::vector<int> order;
+    for (int i = 0; i < n; i++) if (Ls[i].n_elem > 0) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        if (Ls[a].layer_id != Ls[b].layer_id) return Ls[a].layer_id < Ls[b].layer_id;
+        return Ls[a].q_index < Ls[b].q_index;
+    });
+    for (size_t r0 = 0; r0 < order.size();) {
+        size_t r1 = r0;
+        while (r1 < order.size() && Ls[order[r1]].layer_id == Ls[order[r0]].layer_id) r1++;
+        const uint32_t layer = (uint32_t)Ls[order[r0]].layer_id;
+        if (garble) {
+            DrawBatcher db(c, 0, layer, 0, s);
+            for (size_t r = r0; r < r1; r++) {
+                const dash_layer& L = Ls[order[r]];
+                db.add_range(c->prime[L.q_index], DOM_GATE, 0, view_of(outs + order[r], L.q_index), (uint32_t)L.n_elem, (uint64_t)L.elem_base);
+            }
+            db.flush();
+            if (db.status) return db.status;
+        }
+        GateBatcher gb(c, garble, 0, layer, 0, s);
+        for (size_t r = r0; r < r1; r++) {
+            const dash_layer& L = Ls[order[r]];
+            GateJob J = phi_job(c->prime[L.p_index], c->prime[L.q_index], view_of(ins + order[r], L.p_index), L.phi, 0,
+                                view_of(outs + order[r], L.q_index), tables[order[r]]);
+            J.phi_stride = (uint32_t)L.phi_stride;
+            J.n_elem = (uint32_t)L.n_elem; J.elem_base = (uint64_t)L.elem_base;
+            gb.add(J, true);
+        }
+        gb.flush();
+        if (gb.status) return gb.status;
+        r0 = r1;
+    }
+    return DASH_OK;
+}
+
+int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables, hipStream_t s) {
+    uint8_t* const tb[1] = {tables};
+    return proj_layers(c, garble, 1, L, in, out, tb, s);
 }
 
 }  // namespace dash

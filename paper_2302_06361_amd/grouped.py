@@ -1,6 +1,7 @@
 """Independent projection gates with mixed moduli (Sec. Arithmetic Garbled Circuits, projection gates):
-the gates are grouped by their (input modulus, output modulus) pair and every group is one PROJ layer
-call.  Buffer allocation, grouping and call order only; the gates themselves run in the library."""
+the gates are grouped by their (input modulus, output modulus) pair, every group is one PROJ layer
+descriptor, and all descriptors go to the library in one call.  Buffer allocation and grouping only; the gates
+themselves run in the library."""
 import numpy as np
 
 from . import binding as B
@@ -11,14 +12,13 @@ class ProjectionBatch:
 
     Gates are renumbered in grouped order: `order[j]` is the caller's index of the gate at position j,
     and position j is the gate's element index (its tweak).  Per group the buffers are
-    in0 / act (input zero and active labels), out0 / out (output labels), phi [count][p], table."""
+    in0 / act (input zero and active labels), out0 / out (output labels), phi [count][p], table.
+    garble() and evaluate() hand all groups to the library in ONE call (dash_garble_layers / dash_eval_layers),
+    which serves the groups that share an output modulus with one kernel launch."""
 
-    def __init__(self, ctx, pi, qi, layer_id=1, streams=4):
+    def __init__(self, ctx, pi, qi, layer_id=1):
         import torch
         self.ctx = ctx
-        # the groups are independent: their calls go round-robin to a few streams (default priority), so that the
-        # ramp-up and tail of one group's kernels overlap with its neighbours'
-        self._streams = [torch.cuda.Stream(device=ctx.device) for _ in range(max(1, streams))] if streams > 1 else []
         k = ctx.k
         key = np.asarray(pi, np.int64) * k + np.asarray(qi, np.int64)
         self.order = np.argsort(key, kind="stable")
@@ -44,28 +44,23 @@ class ProjectionBatch:
         self.table_bytes = sum(g["table"].numel() for g in self.groups)
         self.rows = sum(g["count"] * ctx.primes[g["pi"]] for g in self.groups)
 
-    def _each_group(self, call, serial=False):
-        import torch
-        if serial or not self._streams:
+    def _lists(self, a, b):
+        G = self.groups
+        return [g["layer"] for g in G], [g[a] for g in G], [g[b] for g in G], [g["table"] for g in G]
+
+    def garble(self, one_call_per_group=False):
+        """one_call_per_group: a dash_garble_layer call (and its own kernel launches) per (p, q) group instead"""
+        if one_call_per_group:
             for g in self.groups:
-                call(g)
+                self.ctx.garble_layer(g["layer"], g["in0"], g["out0"], g["table"])
             return
-        cur = torch.cuda.current_stream()
-        start = torch.cuda.Event()
-        start.record(cur)
-        for s in self._streams:
-            s.wait_event(start)                       # after everything already queued on the caller's stream
-        for idx, g in enumerate(self.groups):
-            with torch.cuda.stream(self._streams[idx % len(self._streams)]):
-                call(g)
-        for s in self._streams:                       # the caller's stream continues when all groups are done
-            done = torch.cuda.Event()
-            done.record(s)
-            cur.wait_event(done)
+        layers, ins, outs, tables = self._lists("in0", "out0")
+        self.ctx.garble_layers(layers, ins, outs, tables)
 
-    def garble(self, serial=False):
-        """serial: all groups on the caller's stream, one after the other (per-kernel timing)"""
-        self._each_group(lambda g: self.ctx.garble_layer(g["layer"], g["in0"], g["out0"], g["table"]), serial)
-
-    def evaluate(self, serial=False):
-        self._each_group(lambda g: self.ctx.eval_layer(g["layer"], g["act"], g["table"], g["out"]), serial)
+    def evaluate(self, one_call_per_group=False):
+        if one_call_per_group:
+            for g in self.groups:
+                self.ctx.eval_layer(g["layer"], g["act"], g["table"], g["out"])
+            return
+        layers, ins, outs, tables = self._lists("act", "out")
+        self.ctx.eval_layers(layers, ins, tables, outs)

@@ -78,16 +78,17 @@ int main(int argc, char** argv) {
     DrawLaunch D;
     memset(&D, 0, sizeof(D));
     expand_key(seed, S, D.key.rk);
-    D.mods = mods.data(); D.elem_base = elem_base; D.layer = layer; D.n_elem = n;
-    D.jobs[0] = DrawJob{(uint32_t)q, DOM_GATE, (uint32_t)slot, 0, LView{cout0.data(), (int64_t)16 * n, 16u}};
+    D.mods = mods.data(); D.layer = layer;
+    D.jobs[0] = DrawJob{(uint32_t)q, DOM_GATE, (uint32_t)slot, 0, LView{cout0.data(), (int64_t)16 * n, 16u}, elem_base, n, 0u};
     for (uint32_t bx = 0; bx < nb_e; bx++)
         for (uint32_t tx = 0; tx < kThreads; tx++) draw_body(D, bx, 0, tx, HostTab());
 
     GateLaunch G;
     memset(&G, 0, sizeof(G));
     expand_key(fixed, S, G.key.rk);
-    G.mods = mods.data(); G.elem_base = elem_base; G.layer = layer; G.n_elem = n;
+    G.mods = mods.data(); G.layer = layer;
     GateJob& J = G.jobs[0];
+    J.elem_base = elem_base; J.n_elem = n;
     J.p = p; J.q = q; J.in = LView{cin0.data(), (int64_t)16 * n, 16u}; J.phi = phi.data(); J.phi_stride = phi_stride;
     J.slot = slot; J.mode = PAY_PHI; J.out = LView{cout0.data(), (int64_t)16 * n, 16u}; J.table = table.data();
     const uint64_t rows = (uint64_t)n * p;

@@ -37,7 +37,7 @@ int main(int argc, char** argv) {
     GateLaunch G;
     memset(&G, 0, sizeof(G));
     expand_key(fixed, S, G.key.rk);
-    G.mods = mods.data(); G.elem_base = (1ull << 35) + 3; G.layer = 11; G.n_elem = n; G.njobs = 16;
+    G.mods = mods.data(); G.layer = 11; G.njobs = 16;
     std::vector<std::vector<uint8_t>> in(16), table(16), out(16), out_typed(16);
     for (int j = 0; j < 16; j++) {
         const int q = hot[j], p = hot[(j * 7 + 3) % 16];            // every hot modulus once as output, inputs mixed
@@ -52,6 +52,7 @@ int main(int argc, char** argv) {
         out_typed[j].assign((size_t)Mq.nchunk * n * 16, 0xDD);
         GateJob& J = G.jobs[j];
         J.p = p; J.q = q; J.slot = 100 + j; J.mode = PAY_PHI;
+        J.elem_base = (1ull << 35) + 3 + 1000 * j; J.n_elem = n;
         J.in = LView{in[j].data(), (int64_t)16 * n, 16u};
         J.table = table[j].data();
         J.out = LView{out[j].data(), (int64_t)16 * n, 16u};

@@ -106,3 +106,49 @@ def test_both_table_layouts_of_the_gate_kernels(monkeypatch):
         for pi, qi in [(0, 0), (0, 11), (11, 0), (5, 7), (3, 1), (9, 9)]:
             run_proj(ctx, orc, pi, qi, 1500, seed=50 + pi * 12 + qi)
         run_proj(ctx, orc, 6, 2, 1, seed=3)
+
+
+@pytest.mark.parametrize("threshold", ["1", "1000000000000"])
+def test_projection_groups_in_one_call(monkeypatch, threshold):
+    """dash_garble_layers / dash_eval_layers: independent PROJ calls of different sizes, element bases and layer ids in
+    ONE call (groups with the same layer id and output modulus share kernel launches, each job with its own gate count),
+    an empty group among them; both table layouts of the kernels forced in turn; every group against the oracle"""
+    from paper_2302_06361_amd import Labels, Layer, PROJ
+    monkeypatch.setenv("DASH_BANKED_MIN_LANES", threshold)
+    ctx, orc = both(12)
+    g = np.random.default_rng(99)
+    spec = [(0, 3, 700, 5, 10), (4, 3, 1, 5, 2 ** 33), (11, 3, 257, 5, 999), (3, 3, 0, 5, 0), (2, 0, 300, 5, 4000), (7, 0, 513, 5, 70000),
+            (1, 9, 64, 6, 123), (9, 9, 1500, 6, 2 ** 32 + 1), (5, 3, 300, 6, 5), (0, 0, 333, 5, 1), (10, 11, 100, 5, 0)]
+    spec += [(int(g.integers(0, 12)), 7, int(g.integers(1, 400)), 5, int(g.integers(0, 10 ** 6))) for _ in range(20)]    # more than 16 jobs of one modulus
+    layers, in0s, acts, out0s, outs, tables, host = [], [], [], [], [], [], []
+    for pi, qi, n, lid, base in spec:
+        p, q = orc.primes[pi], orc.primes[qi]
+        in0 = workloads.uniform_labels(g, n, orc.lam(p), p)
+        phi = workloads.proj_phi(g, max(n, 1), p, q)[:n]
+        a = g.integers(0, p, n)
+        act = ((in0.astype(np.int64) + a[:, None] * orc.delta(p).astype(np.int64)[None, :]) % p).astype(np.uint8)
+        tin0, tact = Labels(ctx, n, only=[pi]), Labels(ctx, n, only=[pi])
+        if n:
+            tin0.from_numpy(pi, in0)
+            tact.from_numpy(pi, act)
+        phid = torch.as_tensor(phi.reshape(-1, p) if n else np.zeros((1, p), np.uint8)).to(ctx.device)
+        lay = Layer(PROJ, lid, n, elem_base=base, p_index=pi, q_index=qi, phi=phid, phi_stride=p)
+        oe, tb, sb = ctx.layer_sizes(lay)
+        layers.append(lay); in0s.append(tin0); acts.append(tact)
+        out0s.append(Labels(ctx, n, only=[qi], zero=True)); outs.append(Labels(ctx, n, only=[qi], zero=True))
+        tables.append(torch.zeros(max(tb, 4), dtype=torch.uint8, device=ctx.device)[:tb])
+        host.append((in0, phi, act))
+    ctx.garble_layers(layers, in0s, out0s, tables)
+    ctx.eval_layers(layers, acts, tables, outs)
+    torch.cuda.synchronize()
+    for i, (pi, qi, n, lid, base) in enumerate(spec):
+        if n == 0:
+            continue
+        p, q = orc.primes[pi], orc.primes[qi]
+        in0, phi, act = host[i]
+        rout0, rtable = orc.proj_garble(p, q, in0, phi, lid, 0, base)
+        rout = orc.proj_eval(p, q, act, rtable, lid, 0, base)
+        assert (out0s[i].to_numpy(qi) == rout0).all(), ("zero labels", i)
+        assert_tables_equal(tables[i], rtable.reshape(-1), "group %d" % i)
+        assert (outs[i].to_numpy(qi) == rout).all(), ("evaluated labels", i)
+        assert outs[i].pad_is_zero(qi) and out0s[i].pad_is_zero(qi)
