@@ -408,10 +408,20 @@ def micro_vgg(torch, workloads, images=2, chunk=2, reps=1):
     ctx.profile_enable(False)
     pr = read_profiles(ctx)
     n_img = len(xs) * chunk
+    # table bytes of one image in the working format and in the packed storage format (dash_tables_pack; defined for
+    # label lengths by the floor rule, so both are given for a floor-rule context; sizes only, nothing is run)
+    from paper_2302_06361_amd import LAMBDA_FLOOR
+    from paper_2302_06361_amd.network import build_layers
+    fctx = Context(net["primes"], net["seed"], net["digits"], LAMBDA_FLOOR)
+    flayers, _, ftb, _ = build_layers(fctx, net, 1, 0)
+    floor_bytes = sum(ftb)
+    floor_packed = sum(fctx.tables_packed_bytes(l) for l, tb in zip(flayers, ftb) if tb)
+    fctx.close()
     out = dict(workload="config 5: VGG shape (12 primes, scale 2^5), %d image(s) of the batch of 64, streamed layer by layer in chunks "
                         "of %d images, garble + encode + evaluate + decode" % (n_img, chunk),
                images=n_img, chunk=chunk, ms=ms, ms_per_image=ms / n_img, outputs_valid=valid,
                table_bytes_per_image=g.table_bytes // chunk, gates_per_image=work["gates"] // n_img,
+               table_bytes_per_image_floor_rule=dict(working_format=floor_bytes, packed_format=floor_packed),
                gates_per_s=2 * work["gates"] / (ms * 1e-3), label_macs_per_image=2 * macs // n_img,
                kernels_per_chunk=dict(k_proj_garble=kernel_line(pr["garble"], 1), k_digits_garble=kernel_line(pr["garble_digits"], 1),
                                       eval_kernels=kernel_line(pr["eval"], 1), linear=kernel_line(pr["linear"], 1)))

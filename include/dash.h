@@ -197,6 +197,23 @@ int dash_decode(dash_ctx *ctx, const dash_labels *act, const dash_labels *zero, 
 int dash_labels_pack(dash_ctx *ctx, const dash_labels *labels, int64_t n, void *packed, void *hip_stream);
 int dash_labels_unpack(dash_ctx *ctx, const void *packed, int64_t n, dash_labels *labels, void *hip_stream);
 
+/* The packed storage format of a layer's ciphertext tables, for keeping garbled layers and for shipping them from the
+ * garbling device to the inference device (Sec. System-level Architecture, offline phase).  A ciphertext is an
+ * encrypted label, a vector in Z_q^lambda, and is compressed exactly like a label (Sec. Implementation, compress;
+ * Sec. Evaluation: labels travel as 128 bits): row r of a segment becomes the little-endian 128-bit integer
+ * sum_j row[j] q^j, 16 bytes instead of pitch_q = 4 ceil(lambda_q / 4); the one-digit rows of a half gate become one
+ * byte each.  Packed layout: the layer's segments in the same order, segment [gate][row][16] (one-digit segments
+ * [gate][row][1], padded to a multiple of 16 bytes).  `layer` is the descriptor the tables were garbled with (kind,
+ * n_elem, repeat, p_index / q_index).  Lossless only if q^lambda_q <= 2^128 for every output modulus of the layer,
+ * i.e. for contexts with the floor rule; otherwise dash_tables_packed_bytes returns 0 and the two calls return
+ * DASH_EUNSUPPORTED and touch nothing.  The garbling and evaluating kernels work on the unpacked format: unpack before
+ * dash_eval_layer.  tables: device, 4-byte aligned; packed: device, 16-byte aligned, dash_tables_packed_bytes bytes.
+ * Asynchronous on the stream, no allocation.  (Garbled row reduction, which would drop one row per gate, is not part
+ * of the scheme: Sec. Arithmetic Garbled Circuits, projection gates, leaves it out.) */
+size_t dash_tables_packed_bytes(const dash_ctx *ctx, const dash_layer *layer);
+int dash_tables_pack(dash_ctx *ctx, const dash_layer *layer, const void *tables, void *packed, void *hip_stream);
+int dash_tables_unpack(dash_ctx *ctx, const dash_layer *layer, const void *packed, void *tables, void *hip_stream);
+
 /* Benchmark instrumentation (not part of the scheme): while enabled, every launch of the kernel
  * classes below is bracketed by two HIP events on its stream.  dash_profile_read synchronises,
  * returns the summed kernel time, the number of launches, the units processed (ciphertext rows for

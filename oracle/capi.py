@@ -34,6 +34,7 @@ def lib():
         _lib.orc_relu_bytes_per_elem.restype = C.c_size_t
         _lib.orc_scale_bytes_per_elem.restype = C.c_size_t
         _lib.orc_signact_bytes_per_elem.restype = C.c_size_t
+        _lib.orc_tables_packed_bytes.restype = C.c_size_t
     return _lib
 
 
@@ -269,6 +270,27 @@ class Oracle:
         out = self._bundle_out(n)
         self.L.orc_signact_eval(self.h, int(layer), C.c_uint64(elem_base), C.c_long(n), _ptrs(act), _p(tables),
                                 _ptrs(out))
+        return out
+
+    # -- packed storage format of the tables ----------------------------------------
+    KIND = dict(relu=4, scale=5, sign=6, proj=7)
+
+    def tables_packed_bytes(self, kind, n, repeat=1, p=0, q=0):
+        return self.L.orc_tables_packed_bytes(self.h, self.KIND[kind], C.c_long(n), int(repeat), int(p), int(q))
+
+    def tables_pack(self, kind, n, tables, repeat=1, p=0, q=0):
+        """tables of a layer over n elements (working format) -> packed format (uint8 array)"""
+        tables = _u8(tables).copy()
+        out = np.zeros(self.tables_packed_bytes(kind, n, repeat, p, q), np.uint8)
+        ok = self.L.orc_tables_repack(self.h, self.KIND[kind], C.c_long(n), int(repeat), int(p), int(q), 1, _p(tables), _p(out))
+        assert ok, "packed format not defined for these label lengths"
+        return out
+
+    def tables_unpack(self, kind, n, packed, nbytes, repeat=1, p=0, q=0):
+        packed = _u8(packed).copy()
+        out = np.full(nbytes, 0xEE, np.uint8)
+        ok = self.L.orc_tables_repack(self.h, self.KIND[kind], C.c_long(n), int(repeat), int(p), int(q), 0, _p(out), _p(packed))
+        assert ok
         return out
 
     # -- linear layers ----------------------------------------------------------

@@ -746,6 +746,82 @@ void orc_signact_eval(const octx *c, int layer, u64 elem_base, long n, u8 *const
                       u8 *const out[]) { signact_layer(c, 0, layer, elem_base, n, in, (u8 *)tables, out); }
 
 /* ------------------------------------------------------------------------- */
+/* Packed storage format of the ciphertext tables                            */
+/* ------------------------------------------------------------------------- */
+
+/* A ciphertext is an encrypted label, a vector in Z_q^lambda_q; for storage and transfer it is
+ * compressed like a label (Sec. Implementation, compress; Sec. Evaluation, Communication: labels
+ * travel as 128 bits): 16 bytes per row, little endian, in place of pitch_q.  The one-digit rows of
+ * a half gate (4 bytes in the working format) take one byte.  Segments keep their order; a
+ * one-digit segment is padded to a multiple of 16 bytes.  Only defined when q^lambda_q <= 2^128 for
+ * every row modulus of the layer (the floor rule); returns 0 otherwise.
+ * kind: 4 ReLU, 5 scaling (repeat), 6 sign activation, 7 one segment of gates p -> q. */
+typedef struct { int rows, q; } oseg;      /* rows per element, modulus of the rows (0: one-digit rows) */
+static int table_segments(const octx *c, int kind, int repeat, int p, int q, oseg *out) {
+    int n = 0, k = c->k, ns = sign_nslots(c);
+    int reps = kind == 5 ? repeat : 1;
+    for (int t = 0; t < reps; t++) {
+        if (kind == 5) for (int i = 1; i < k; i++) out[n++] = (oseg){2, c->prime[i]};
+        if (kind == 4 || kind == 5 || kind == 6)
+            for (int s = 0; s < ns; s++)
+                if (sign_slot_bytes(c, s, kind == 5)) out[n++] = (oseg){sign_slot_in(c, s), sign_slot_out(c, s)};
+        if (kind == 4) for (int i = 0; i < k; i++) {
+            out[n++] = (oseg){c->prime[i], c->prime[i]};
+            out[n++] = (oseg){2, c->prime[i]};
+            out[n++] = (oseg){2, 0};
+        }
+        if (kind == 6) for (int i = 0; i < k; i++) out[n++] = (oseg){2, c->prime[i]};
+        if (kind == 7) out[n++] = (oseg){p, q};
+    }
+    return n;
+}
+static int row_fits_128(const octx *c, int q) {
+    u128 v = 1;
+    for (int j = 0; j < c->lam[q]; j++) {
+        if (v > (~(u128)0) / (u128)q) return (q == 2 || q == 4 || q == 16) && j == c->lam[q] - 1;   /* q^lambda = 2^128 exactly */
+        v *= (u128)q;
+    }
+    return 1;
+}
+#define MAXSEG (MAXN * (MAXK * MAXN + MAXN + MAXK) + 4 * MAXK + 8)
+size_t orc_tables_packed_bytes(const octx *c, int kind, long n, int repeat, int p, int q) {
+    oseg seg[MAXSEG];
+    int ns = table_segments(c, kind, repeat, p, q, seg);
+    size_t b = 0;
+    for (int s = 0; s < ns; s++) {
+        if (seg[s].q && !row_fits_128(c, seg[s].q)) return 0;
+        b += seg[s].q ? (size_t)n * seg[s].rows * 16 : (((size_t)n * seg[s].rows + 15) / 16) * 16;
+    }
+    return b;
+}
+/* pack = 1: tables -> packed; pack = 0: packed -> tables.  Returns 0 if the format is not defined. */
+int orc_tables_repack(const octx *c, int kind, long n, int repeat, int p, int q, int pack, u8 *tables, u8 *packed) {
+    oseg seg[MAXSEG];
+    int ns = table_segments(c, kind, repeat, p, q, seg);
+    if (!orc_tables_packed_bytes(c, kind, n, repeat, p, q) && ns && n) return 0;
+    for (int s = 0; s < ns; s++) {
+        size_t rows = (size_t)n * seg[s].rows;
+        if (!seg[s].q) {
+            for (size_t r = 0; r < rows; r++) {
+                if (pack) packed[r] = tables[4 * r];
+                else { memset(tables + 4 * r, 0, 4); tables[4 * r] = packed[r]; }
+            }
+            if (pack) memset(packed + rows, 0, ((rows + 15) / 16) * 16 - rows);
+            tables += 4 * rows; packed += ((rows + 15) / 16) * 16;
+            continue;
+        }
+        int lq = c->lam[seg[s].q], pitch = pitch_of(lq);
+        for (size_t r = 0; r < rows; r++) {
+            u8 *row = tables + r * pitch, *pk = packed + r * 16;
+            if (pack) store128(compress(row, lq, seg[s].q), pk);
+            else { memset(row, 0, (size_t)pitch); decompress(load128(pk), seg[s].q, lq, row); }
+        }
+        tables += rows * pitch; packed += rows * 16;
+    }
+    return 1;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Linear layers: free additions and multiplications by public constants     */
 /* (Sec. Arithmetic Garbled Circuits; System-level Architecture; LabelTensors */
 /* figure of the Conv2D operation)                                           */

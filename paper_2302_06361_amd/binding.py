@@ -19,7 +19,7 @@ NOALLOC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_garble_layers", "dash_eval_layers", "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
+           "dash_garble_layers", "dash_eval_layers", "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_tables_packed_bytes", "dash_tables_pack", "dash_tables_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
 
 
 class DashError(RuntimeError):
@@ -55,6 +55,7 @@ def lib():
         L = C.CDLL(_SO)
         L.dash_strerror.restype = C.c_char_p
         L.dash_weights_bytes.restype = C.c_size_t
+        L.dash_tables_packed_bytes.restype = C.c_size_t
         L.dash_ctx_destroy.restype = None
         _lib = L
     return _lib
@@ -240,6 +241,18 @@ class Context:
         cl = labels.c()
         _check(self.L.dash_labels_unpack(self.h, C.c_void_p(packed.data_ptr()), C.c_int64(labels.n_elem), C.byref(cl), _stream()),
                "dash_labels_unpack")
+
+    def tables_packed_bytes(self, layer):
+        """bytes of the layer's tables in the packed storage format (0: not available under this context's label lengths)"""
+        return self.L.dash_tables_packed_bytes(self.h, C.byref(layer.c))
+
+    def tables_pack(self, layer, tables, packed):
+        _check(self.L.dash_tables_pack(self.h, C.byref(layer.c), C.c_void_p(tables.data_ptr()), C.c_void_p(packed.data_ptr()), _stream()),
+               "dash_tables_pack")
+
+    def tables_unpack(self, layer, packed, tables):
+        _check(self.L.dash_tables_unpack(self.h, C.byref(layer.c), C.c_void_p(packed.data_ptr()), C.c_void_p(tables.data_ptr()), _stream()),
+               "dash_tables_unpack")
 
     def garble_layer(self, layer, in_zero, out_zero, tables=None, scratch=None):
         ci, co = in_zero.c(), out_zero.c()

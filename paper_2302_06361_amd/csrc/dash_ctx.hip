@@ -138,17 +138,6 @@ __global__ __launch_bounds__(kThreads) void k_unpack(const ModInfo* mods, uint32
     for (uint32_t i = M.ndw; i < M.nchunk * 4; i++) put((int)i, 0u);      // digits past lambda are zero in a LabelTensor
 }
 
-// true if every label of modulus m with lam digits is below 2^128 as a base-m number (m^lam <= 2^128)
-static bool fits_128_bits(uint32_t m, uint32_t lam) {
-    if ((m & (m - 1)) == 0) { uint32_t t = 0; while ((1u << t) < m) t++; return t * lam <= 128; }
-    u128 r = 1;
-    for (uint32_t j = 0; j < lam; j++) {
-        if (r > ~(u128)0 / m) return false;
-        r *= m;
-    }
-    return true;
-}
-
 }  // namespace dash
 
 // ------------------------------------------------------------------------------------------------
@@ -562,6 +551,20 @@ int dash_eval_layer(dash_ctx* c, const dash_layer* L, const dash_labels* in_act,
     return run_layer(c, L, false, in_act, out_act, (uint8_t*)tables, (uint8_t*)scratch, (hipStream_t)stream);
 }
 
+
+size_t dash_tables_packed_bytes(const dash_ctx* c, const dash_layer* L) {
+    size_t b = 0;
+    if (!c || !L || tables_packed_bytes(c, L, &b) != DASH_OK) return 0;
+    return b;
+}
+int dash_tables_pack(dash_ctx* c, const dash_layer* L, const void* tables, void* packed, void* stream) {
+    if (!c || !L) return DASH_EINVAL;
+    return tables_repack(c, L, true, (uint8_t*)tables, (uint8_t*)packed, (hipStream_t)stream);
+}
+int dash_tables_unpack(dash_ctx* c, const dash_layer* L, const void* packed, void* tables, void* stream) {
+    if (!c || !L) return DASH_EINVAL;
+    return tables_repack(c, L, false, (uint8_t*)tables, (uint8_t*)packed, (hipStream_t)stream);
+}
 
 // n independent layer calls: lists of PROJ calls go to the launcher that merges them, anything else is run in turn
 static int run_layers(dash_ctx* c, bool garble, int n, const dash_layer* Ls, const dash_labels* ins, dash_labels* outs, void* const* tables,

@@ -72,6 +72,54 @@ int launch_affine(const dash_ctx* c, AffineLaunch& L, int njobs, hipStream_t s) 
     return DASH_OK;
 }
 
+// ------------------------------------------------------------------------------- packed table rows
+// one lane per row: working format [pitch_q bytes, one digit each] <-> 16-byte integer sum_j row[j] q^j
+template <bool Pack>
+__global__ __launch_bounds__(kThreads) void k_rows_repack(const PackLaunch L) {
+    const PackSeg& S = L.seg[blockIdx.y];
+    const uint64_t rows = (uint64_t)L.n_elem * S.rows_per_gate;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    if (S.q == 0) {                     // one-digit rows; the packed segment is padded with zeros to a multiple of 16 bytes
+        const uint64_t padded = (rows + 15) & ~(uint64_t)15;
+        for (uint64_t r = (uint64_t)blockIdx.x * kThreads + threadIdx.x; r < padded; r += (uint64_t)gridDim.x * kThreads) {
+            if (Pack) S.packed[r] = r < rows ? S.rows[r * 4] : 0;
+            else if (r < rows) *(uint32_t*)(const_cast<uint8_t*>(S.rows) + r * 4) = S.packed[r];
+        }
+        return;
+    }
+    for (uint64_t r = (uint64_t)blockIdx.x * kThreads + threadIdx.x; r < rows; r += (uint64_t)gridDim.x * kThreads) {
+        const ModInfo M = L.mods[S.q];
+        uint32_t* row = (uint32_t*)(const_cast<uint8_t*>(S.rows) + r * (M.ndw * 4));
+        if (Pack) {
+            uint32_t colour;
+            const U128 x = compress(M, [&](int i) { return row[i]; }, &colour);
+            *(u32x4*)(S.packed + r * 16) = u32x4{x.w[0], x.w[1], x.w[2], x.w[3]};
+        } else {
+            const u32x4 v = *(const u32x4*)(S.packed + r * 16);
+            const U128 x = {{v.x, v.y, v.z, v.w}};
+            decompress(M, x, [&](int i, uint32_t w) { row[i] = w; });
+        }
+    }
+}
+
+int launch_pack(const dash_ctx* c, PackLaunch& L, bool pack, hipStream_t s) {
+    static_assert(sizeof(PackLaunch) <= 4096, "kernel argument block");
+    if (L.nseg < 1 || L.nseg > (uint32_t)kMaxPackSegs) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    L.mods = c->d_mods;
+    uint64_t rows = 0;
+    for (uint32_t i = 0; i < L.nseg; i++) {
+        const uint64_t r = (uint64_t)L.n_elem * L.seg[i].rows_per_gate + 15;      // (+ the padding of a one-digit segment)
+        rows = r > rows ? r : rows;
+    }
+    const uint64_t tiles = (rows + kThreads - 1) / kThreads;
+    dim3 grid(grid_x_for(tiles, (int)L.nseg), L.nseg);
+    if (pack) hipLaunchKernelGGL(k_rows_repack<true>, grid, dim3(kThreads), 0, s, L);
+    else hipLaunchKernelGGL(k_rows_repack<false>, grid, dim3(kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
 // ---------------------------------------------------------------------------------------- garble
 // One instantiation per output-modulus description: QD = ModInfo (any modulus, run-time constants) or
 // CMod<m, lam> for the hot moduli.  The input modulus is dispatched inside (its code is small).

@@ -92,11 +92,27 @@ int proj_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
 int proj_layers(dash_ctx* c, bool garble, int n, const dash_layer* Ls, const dash_labels* ins, dash_labels* outs, uint8_t* const* tables,
                 hipStream_t s);
 
+// packed table format (dash_layers.hip)
+int tables_packed_bytes(const dash_ctx* c, const dash_layer* L, size_t* bytes);
+int tables_repack(dash_ctx* c, const dash_layer* L, bool pack, uint8_t* tables, uint8_t* packed, hipStream_t s);
+int launch_pack(const dash_ctx* c, PackLaunch& L, bool pack, hipStream_t s);
+
 // linear layers (dash_linear.hip)
 int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s);
 // dense layers on the matrix cores (dash_gemm.hip)
 bool dense_mfma_wanted(const dash_layer* L, int64_t batch);
 int dense_mfma(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, hipStream_t s);
+
+// true if every vector of lam digits below m is below 2^128 as a base-m number (m^lam <= 2^128)
+inline bool fits_128_bits(uint32_t m, uint32_t lam) {
+    if ((m & (m - 1)) == 0) { uint32_t t = 0; while ((1u << t) < m) t++; return t * lam <= 128; }
+    unsigned __int128 r = 1;
+    for (uint32_t j = 0; j < lam; j++) {
+        if (r > ~(unsigned __int128)0 / m) return false;
+        r *= m;
+    }
+    return true;
+}
 
 inline LView view_of(const dash_labels* t, int i) { return LView{(uint8_t*)t->data[i], t->chunk_stride[i], 16u}; }
 

@@ -145,6 +145,21 @@ struct CastLaunch {
     CastJob jobs[kMaxJobs];
 };
 
+// packed storage format of ciphertext tables: every row of a segment, a vector in Z_q^lambda, as the 128-bit integer
+// sum_j row[j] q^j (Sec. Implementation, compress), 16 bytes per row; the one-digit rows of a half gate as one byte
+struct PackSeg {
+    const uint8_t* rows;     // the segment in the working format: [gate][row][pitch_q]  (pack: read; unpack: written)
+    uint8_t* packed;         // the segment in the packed format: [gate][row][16]        (pack: written; unpack: read)
+    uint32_t q;              // modulus of the rows; 0 = one-digit rows (4 bytes <-> 1 byte)
+    uint32_t rows_per_gate;
+};
+constexpr int kMaxPackSegs = 96;
+struct PackLaunch {
+    const ModInfo* mods;
+    uint32_t n_elem, nseg;
+    PackSeg seg[kMaxPackSegs];
+};
+
 // the digit gates of one sign gadget (Appendix, approximated sign: residue i -> digit j of its
 // rounded CRT fraction): the n gates of a residue share their input label, so one lane takes (element, residue),
 // compresses the label once and evaluates its n gates (the garbler: one lane per (element, value a, residue)).  Output wire (i, j) and table segment (i, j) are at fixed

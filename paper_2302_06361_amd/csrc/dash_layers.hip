@@ -553,6 +553,90 @@ int layer_sizes(const dash_ctx* c, const dash_layer* L, int64_t* out_elems, size
     return DASH_OK;
 }
 
+// ---- packed storage format of the tables ------------------------------------------------------
+// Segments of a layer's table buffer in order: (rows per gate, modulus of the rows; 0 = one-digit rows of 4 bytes)
+struct SegDesc { uint32_t rows, q; };
+static int table_segments(const dash_ctx* c, const dash_layer* L, std::vector<SegDesc>& out) {
+    const int k = c->k, ns = sign_nslots(c);
+    auto sign = [&](int first_res) {
+        for (int s = 0; s < ns; s++)
+            if (sign_slot_bytes(c, s, first_res)) out.push_back(SegDesc{(uint32_t)sign_slot_in(c, s), (uint32_t)sign_slot_out(c, s)});
+    };
+    switch (L->kind) {
+        case DASH_RELU:
+            sign(0);
+            for (int i = 0; i < k; i++) {
+                out.push_back(SegDesc{(uint32_t)c->prime[i], (uint32_t)c->prime[i]});
+                out.push_back(SegDesc{2u, (uint32_t)c->prime[i]});
+                out.push_back(SegDesc{2u, 0u});
+            }
+            return DASH_OK;
+        case DASH_SIGN:
+            sign(0);
+            for (int i = 0; i < k; i++) out.push_back(SegDesc{2u, (uint32_t)c->prime[i]});
+            return DASH_OK;
+        case DASH_SCALE:
+            if (L->repeat < 1) return DASH_EINVAL;
+            for (int r = 0; r < L->repeat; r++) {
+                for (int i = 1; i < k; i++) out.push_back(SegDesc{2u, (uint32_t)c->prime[i]});
+                sign(1);
+            }
+            return DASH_OK;
+        case DASH_PROJ:
+            if (L->p_index < 0 || L->p_index >= k || L->q_index < 0 || L->q_index >= k) return DASH_EINVAL;
+            out.push_back(SegDesc{(uint32_t)c->prime[L->p_index], (uint32_t)c->prime[L->q_index]});
+            return DASH_OK;
+        case DASH_DENSE: case DASH_CONV2D: case DASH_SUMPOOL: return DASH_OK;       // free gates: no tables
+    }
+    return DASH_EINVAL;
+}
+// every row must be below 2^128 as a base-q number
+static bool rows_fit_128_bits(const dash_ctx* c, const std::vector<SegDesc>& segs) {
+    for (const SegDesc& sd : segs)
+        if (sd.q && !fits_128_bits(sd.q, c->mods[sd.q].lam)) return false;
+    return true;
+}
+static inline size_t packed_seg_bytes(const SegDesc& sd, size_t E) { return sd.q ? E * sd.rows * 16 : (E * sd.rows + 15) & ~(size_t)15; }
+
+int tables_packed_bytes(const dash_ctx* c, const dash_layer* L, size_t* bytes) {
+    if (L->n_elem < 0) return DASH_EINVAL;
+    std::vector<SegDesc> segs;
+    const int st = table_segments(c, L, segs);
+    if (st) return st;
+    if (!rows_fit_128_bits(c, segs)) return DASH_EUNSUPPORTED;
+    size_t b = 0;
+    for (const SegDesc& sd : segs) b += packed_seg_bytes(sd, (size_t)L->n_elem);
+    *bytes = b;
+    return DASH_OK;
+}
+
+int tables_repack(dash_ctx* c, const dash_layer* L, bool pack, uint8_t* tables, uint8_t* packed, hipStream_t s) {
+    if (L->n_elem < 0) return DASH_EINVAL;
+    if (L->n_elem > 0x7fffffff) return DASH_ESIZE;
+    std::vector<SegDesc> segs;
+    int st = table_segments(c, L, segs);
+    if (st) return st;
+    if (!rows_fit_128_bits(c, segs)) return DASH_EUNSUPPORTED;
+    if (L->n_elem == 0 || segs.empty()) return DASH_OK;
+    if (!tables || !packed || ((uintptr_t)tables & 3) || ((uintptr_t)packed & 15)) return DASH_EINVAL;
+    const size_t E = (size_t)L->n_elem;
+    PackLaunch PL;
+    memset(&PL, 0, sizeof(PL));
+    PL.n_elem = (uint32_t)E;
+    size_t toff = 0, poff = 0;
+    for (const SegDesc& sd : segs) {
+        if (PL.nseg == (uint32_t)kMaxPackSegs) {
+            st = launch_pack(c, PL, pack, s);
+            if (st) return st;
+            PL.nseg = 0;
+        }
+        PL.seg[PL.nseg++] = PackSeg{tables + toff, packed + poff, sd.q, sd.rows};
+        toff += E * sd.rows * (sd.q ? pitch_of(c, (int)sd.q) : 4);
+        poff += packed_seg_bytes(sd, E);
+    }
+    return launch_pack(c, PL, pack, s);
+}
+
 int activation_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels* in, dash_labels* out, uint8_t* tables,
                      uint8_t* scratch, hipStream_t s) {
     if (L->n_elem > 0x7fffffff) return DASH_ESIZE;

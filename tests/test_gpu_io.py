@@ -136,3 +136,57 @@ def test_labels_pack_needs_the_floor_rule():
         ctx.labels_unpack(packed, t)
     torch.cuda.synchronize()
     assert bool((packed == 7).all().item())
+
+
+@pytest.mark.parametrize("k,kind,repeat", [(8, "relu", 1), (8, "scale", 2), (5, "sign", 1), (12, "relu", 1)])
+def test_tables_pack_unpack(k, kind, repeat):
+    """the packed storage format of a layer's ciphertext tables (16 bytes per row, the row compressed like a label;
+    floor-rule contexts): packed bytes against the oracle's packing of the oracle's tables, unpacking gives the
+    tables back, and the layer evaluates from the unpacked copy"""
+    from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN
+    ctx, orc = both(k, rule=1)
+    P = orc.P
+    n = 333
+    X = np.random.default_rng(k).integers(0, P, n)
+    zero = [orc.input_labels(9, n, i) for i in range(k)]
+    act = [orc.encode(i, X, zero[i]) for i in range(k)]
+    lay = Layer(dict(relu=RELU, scale=SCALE, sign=SIGN)[kind], 3, n, elem_base=50, repeat=repeat)
+    if kind == "relu":
+        r0, rt = orc.relu_garble(3, zero, 50)
+        r = orc.relu_eval(3, act, rt, 50)
+    elif kind == "scale":
+        r0, rt = orc.scale_garble(3, zero, repeat, 50)
+        r = orc.scale_eval(3, act, rt, repeat, 50)
+    else:
+        r0, rt = orc.signact_garble(3, zero, 50)
+        r = orc.signact_eval(3, act, rt, 50)
+    want_packed = orc.tables_pack(kind, n, rt, repeat)
+    oe, tb, sb = ctx.layer_sizes(lay)
+    pb = ctx.tables_packed_bytes(lay)
+    assert tb == rt.size and pb == want_packed.size and pb < tb
+    tz, ta = upload_bundle(ctx, zero), upload_bundle(ctx, act)
+    oz, oa = Labels(ctx, n, zero=True), Labels(ctx, n, zero=True)
+    tables = torch.zeros(tb, dtype=torch.uint8, device=ctx.device)
+    scratch = torch.zeros(sb + 256, dtype=torch.uint8, device=ctx.device)
+    ctx.garble_layer(lay, tz, oz, tables, scratch)
+    packed = torch.full((pb,), 0xEE, dtype=torch.uint8, device=ctx.device)
+    ctx.tables_pack(lay, tables, packed)
+    back = torch.full((tb,), 0xEE, dtype=torch.uint8, device=ctx.device)
+    ctx.tables_unpack(lay, packed, back)
+    ctx.eval_layer(lay, ta, back, oa, scratch)
+    torch.cuda.synchronize()
+    assert (packed.cpu().numpy() == want_packed).all(), "packed bytes"
+    assert (back.cpu().numpy() == rt).all(), "unpacked tables"
+    assert_bundle_equal(oa, r, "evaluated from the unpacked tables")
+    print("%s, %d primes: %.1f KB per value unpacked, %.1f KB packed" % (kind, k, tb / n / 1e3, pb / n / 1e3))
+
+
+def test_tables_pack_needs_rows_below_128_bits():
+    from paper_2302_06361_amd import Layer, RELU, DashError
+    ctx, orc = both(8)                       # ceil rule: 3^81 > 2^128
+    lay = Layer(RELU, 3, 10)
+    assert ctx.tables_packed_bytes(lay) == 0
+    t = torch.zeros(1 << 20, dtype=torch.uint8, device=ctx.device)
+    with pytest.raises(DashError, match="not implemented"):
+        ctx.tables_pack(lay, t, t)
+    torch.cuda.synchronize()

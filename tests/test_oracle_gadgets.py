@@ -350,3 +350,51 @@ def test_reduced_accuracy_relu_garbled_equals_its_plain_approximation():
     pos = np.array([orc.sign_plain(residues(int(x), orc.primes), 0, 1) for x in X])
     assert (vals == plain.to_signed(np.where(pos == 1, X, 0), P)).all()
     assert (pos != (2 * X < P)).any()
+
+
+def test_packed_tables_are_horner_integers_and_unpack_back():
+    """the packed storage format of the tables: every row of every segment is the integer sum_j row[j] q^j (big
+    integers here) in 16 little-endian bytes; one-digit rows one byte; unpacking gives the tables back; sizes;
+    not defined under the ceil rule (rows can exceed 128 bits)"""
+    orc = orc_for(4, rule=1)
+    P = orc.P
+    X = np.arange(0, P, 7)
+    n = len(X)
+    zero = [orc.input_labels(0, n, i) for i in range(orc.k)]
+    nd, k = len(orc.digits), orc.k
+    m = [orc.mj(j) for j in range(1, nd + 1)]
+    sign_segs = lambda first: [(orc.primes[i], m[j]) for i in range(first, k) for j in range(nd)] + \
+        [(m[j], m[j - 1]) for j in range(1, nd)] + [(m[0], 2)]
+    cases = []
+    r0, rt = orc.relu_garble(3, zero)
+    cases.append(("relu", 1, rt, sign_segs(0) + [s for p in orc.primes for s in ((p, p), (2, p), (2, 0))]))
+    s0, st = orc.scale_garble(4, zero, 2)
+    cases.append(("scale", 2, st, ([(2, p) for p in orc.primes[1:]] + sign_segs(1)) * 2))
+    a0, at = orc.signact_garble(5, zero)
+    cases.append(("sign", 1, at, sign_segs(0) + [(2, p) for p in orc.primes]))
+    for kind, rep, tab, segs in cases:
+        packed = orc.tables_pack(kind, n, tab, rep)
+        assert packed.size == orc.tables_packed_bytes(kind, n, rep) == sum(n * r * 16 if q else -(-n * r // 16) * 16 for r, q in segs)
+        t_at = p_at = 0
+        for rows, q in segs:
+            if q == 0:
+                assert (packed[p_at:p_at + n * rows] == tab[t_at:t_at + 4 * n * rows:4]).all()
+                t_at += 4 * n * rows
+                p_at += -(-n * rows // 16) * 16
+                continue
+            lq = orc.lam(q)
+            pitch = capi.pitch(lq)
+            for r in (0, 1, n * rows // 2, n * rows - 1):
+                row = tab[t_at + r * pitch:t_at + r * pitch + lq]
+                want = sum(int(d) * q ** j for j, d in enumerate(row))
+                assert want < 1 << 128
+                assert int.from_bytes(packed[p_at + 16 * r:p_at + 16 * r + 16].tobytes(), "little") == want, (kind, q, r)
+            t_at += n * rows * pitch
+            p_at += n * rows * 16
+        assert t_at == tab.size and p_at == packed.size
+        assert (orc.tables_unpack(kind, n, packed, tab.size, rep) == tab).all(), kind
+    in0 = workloads.uniform_labels(np.random.default_rng(1), 50, orc.lam(5), 5)
+    o0, t = orc.proj_garble(5, 7, in0, workloads.proj_phi(np.random.default_rng(2), 50, 5, 7), 1)
+    pk = orc.tables_pack("proj", 50, t.reshape(-1), p=5, q=7)
+    assert pk.size == 50 * 5 * 16 and (orc.tables_unpack("proj", 50, pk, t.size, p=5, q=7) == t.reshape(-1)).all()
+    assert orc_for(4, rule=0).tables_packed_bytes("relu", 10) == 0          # ceil rule: 3^81 > 2^128
