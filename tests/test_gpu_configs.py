@@ -209,6 +209,36 @@ def test_config5_vgg_full_width_sampled():
     print("config 5: %.1f GB of tables per image" % (g.table_bytes / 2 / 1e9))
 
 
+def test_config5_vgg_batch64_streamed():
+    """Config 5 as stated: all 64 images, streamed in 32 chunks of 2 images through one set of buffers (garble, encode,
+    evaluate, decode per chunk; element and wire indices of a chunk start at its first image).  Every decoded output of
+    every image against the plain evaluation, all labels valid, and the label invariant on the output boundary of
+    every chunk.  (Labels and table bytes of sampled values: test_config5_vgg_full_width_sampled.)"""
+    from paper_2302_06361_amd import Context, StreamedNetwork
+    net = workloads.vgg(seed=5, batch=64)
+    ctx = Context(net["primes"], net["seed"], net["digits"])
+    chunk = 2
+    g = StreamedNetwork(ctx, net, batch=chunk)
+    P = int(np.prod(net["primes"]))
+    n_in, n_out = net["n_in"], 10
+    pv = plain.run_network(net["layers"], net["x"], P, 64)[-1].reshape(64, n_out)
+    last = len(net["layers"])
+    for b in range(0, 64, chunk):
+        g.batch_base = b
+        g.rebase()
+        x = torch.as_tensor(net["x"][b * n_in:(b + chunk) * n_in]).to(ctx.device)
+
+        def boundary(i, zero, act, b=b):
+            if i == last:
+                check_invariant(ctx, zero, act, pv[b:b + chunk].reshape(-1), "images %d-%d, output boundary" % (b, b + chunk - 1))
+        values, valid = g.run(x, boundary)
+        torch.cuda.synchronize()
+        assert valid.cpu().numpy().all(), b
+        assert (values.cpu().numpy() == plain.to_signed(pv[b:b + chunk].reshape(-1), P)).all(), b
+        if b % 16 == 0:
+            print("images %d-%d ok" % (b, b + chunk - 1), flush=True)
+
+
 @pytest.mark.parametrize("name", ["f", "F"])
 def test_paper_cifar_model_shapes(name):
     """the CIFAR-sized models f and F of the paper's table (7-prime base, rescaling by 2^5 after every ReLU): one
