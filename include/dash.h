@@ -214,17 +214,6 @@ size_t dash_tables_packed_bytes(const dash_ctx *ctx, const dash_layer *layer);
 int dash_tables_pack(dash_ctx *ctx, const dash_layer *layer, const void *tables, void *packed, void *hip_stream);
 int dash_tables_unpack(dash_ctx *ctx, const dash_layer *layer, const void *packed, void *tables, void *hip_stream);
 
-/* Benchmark instrumentation (not part of the scheme): while enabled, every launch of the kernel
- * classes below is bracketed by two HIP events on its stream.  dash_profile_read synchronises,
- * returns the summed kernel time, the number of launches, the units processed (ciphertext rows for
- * GARBLE and for GARBLE_DIGITS, the fused kernel for the digit gates of a sign gadget; gates for EVAL,
- * label-digit MACs for LINEAR) and the algorithmic bytes moved in the
- * one-byte-per-digit layout (GARBLE per gate: input labels + function table + output zero label +
- * p rows; EVAL per gate: input labels + one row + output label), then clears the record. */
-enum { DASH_PROF_GARBLE = 0, DASH_PROF_EVAL = 1, DASH_PROF_LINEAR = 2, DASH_PROF_GARBLE_DIGITS = 3, DASH_PROF_KINDS = 4 };
-int dash_profile_enable(dash_ctx *ctx, int on);
-int dash_profile_read(dash_ctx *ctx, int kind, double *ms, int64_t *launches, double *units, double *alg_bytes);
-
 const char *dash_strerror(int status);
 
 #ifdef __cplusplus

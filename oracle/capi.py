@@ -35,6 +35,7 @@ def lib():
         _lib.orc_scale_bytes_per_elem.restype = C.c_size_t
         _lib.orc_signact_bytes_per_elem.restype = C.c_size_t
         _lib.orc_tables_packed_bytes.restype = C.c_size_t
+        _lib.orc_hash_calls.restype = C.c_ulonglong
     return _lib
 
 
@@ -48,6 +49,11 @@ def _u8(a):
 
 def _ptrs(arrs):
     return (C.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+
+
+def hash_calls():
+    """hash evaluations since the library was loaded (a garbler spends exactly one per ciphertext)"""
+    return lib().orc_hash_calls()
 
 
 def aes128_encrypt(key, block):

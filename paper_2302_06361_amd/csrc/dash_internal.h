@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "../../include/dash.h"
+#include "../../include/dash_profile.h"
 #include "dash_core.h"
 #include "dash_launch.h"
 

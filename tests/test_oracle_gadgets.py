@@ -282,27 +282,41 @@ def test_scale_and_relu_random_values_base8():
 
 
 # ---------------------------------------------------------------- table sizes
-def test_table_row_counts_base8_and_base12():
-    """rows per value: sign n*sum(p) + (n-1)*k*d + d_1; ReLU adds sum(p) + 2k + 2k short rows;
-    one scaling step is the sign without residue 0 plus 2(k-1) cast rows (Sec. The Scaling Operation, Garbling)"""
-    for k, sign_rows, relu_extra in ((8, 1141, 93 + 16), (12, 4253, 221 + 24)):
+def test_ciphertext_counts_base8_and_base12():
+    """Ciphertexts per value, counted as the hashes the garbler spends (one per ciphertext), against the numbers
+    worked out by hand.  With the digit and cast gates of the mixed-radix addition merged into one projection per
+    (residue, digit), a sign gadget with digits (d_1; d_2..d_n) over k primes has
+        n * sum(p) digit rows + k * (d_2 + .. + d_n) carry rows + d_1 final rows:
+        base 8, (26; 12 x 6): 7 * 77 + 8 * 72 + 26 = 1141;  base 12, (46; 17 x 10): 11 * 197 + 12 * 170 + 46 = 4253.
+    The paper's count for the same digits (Sec. The Scaling Operation, Garbling: alpha = t sum(p) + 2k sum_{i>=2} m_i +
+    2n(k-1) + m_1, with separate cast gates) is 539 + 1152 + 98 + 26 = 1815 and 2167 + 4080 + 242 + 46 = 6535.
+    ReLU adds sum(p) + 2k rows and 2k one-digit rows (half gates); one scaling step is the sign gadget without
+    residue 0 (n * 2 rows fewer) plus 2(k-1) cast rows, as in the paper's alpha + 2(k-1)."""
+    for k, sign, relu, scale_step, paper_alpha in ((8, 1141, 1141 + 77 + 16 + 16, 1141 - 7 * 2 + 14, 1815),
+                                                   (12, 4253, 4253 + 197 + 24 + 24, 4253 - 11 * 2 + 22, 6535)):
         orc = orc_for(k)
+        zero = [orc.input_labels(0, 1, i) for i in range(k)]
+        h0 = capi.hash_calls()
+        orc.signact_garble(3, zero)
+        h1 = capi.hash_calls()
+        orc.relu_garble(4, zero)
+        h2 = capi.hash_calls()
+        orc.scale_garble(5, zero, 3)
+        h3 = capi.hash_calls()
+        assert h1 - h0 == sign + 2 * k              # the sign activation: the gadget and k two-row gates
+        assert h2 - h1 == relu
+        assert h3 - h2 == 3 * scale_step
+        assert sign < paper_alpha
         n, d = orc.n, orc.digits
-        sp = sum(orc.primes)
-        rows_sign = n * sp + sum(k * d[j] for j in range(1, n)) + d[0]
-        assert rows_sign == sign_rows
-        # bytes: recompute from pitches
-        pit = lambda m: capi.pitch(orc.lam(m))
-        mj = [None] + [orc.mj(j) for j in range(1, n + 1)]
-        b = sum(p * pit(mj[j]) for p in orc.primes for j in range(1, n + 1))
-        b += sum(mj[j] * pit(mj[j - 1]) for j in range(2, n + 1)) + mj[1] * pit(2)
-        relu = b + sum(p * pit(p) + 2 * pit(p) + 8 for p in orc.primes)
-        assert orc.relu_bytes_per_elem() == relu
-        b1 = sum(p * pit(mj[j]) for p in orc.primes[1:] for j in range(1, n + 1))
-        b1 += sum(mj[j] * pit(mj[j - 1]) for j in range(2, n + 1)) + mj[1] * pit(2)
-        b1 += sum(2 * pit(p) for p in orc.primes[1:])
-        assert orc.scale_bytes_per_elem() == b1
-        assert relu_extra == sp + 2 * k + 2 * k
+        assert paper_alpha == n * sum(orc.primes) + 2 * k * sum(d[1:]) + 2 * n * (k - 1) + d[0]
+    # and the evaluator spends one hash per gate: 63 gates per base-8 sign gadget, 143 per base-12 one
+    for k, gates in ((8, 8 * 7 + 7), (12, 12 * 11 + 11)):
+        orc = orc_for(k)
+        zero = [orc.input_labels(0, 1, i) for i in range(k)]
+        out0, tab = orc.signact_garble(3, zero)
+        h0 = capi.hash_calls()
+        orc.signact_eval(3, zero, tab)
+        assert capi.hash_calls() - h0 == gates + k
 
 
 # ---------------------------------------------------------------- decode
