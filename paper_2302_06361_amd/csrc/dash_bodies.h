@@ -230,22 +230,31 @@ DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, con
 #pragma unroll
     for (int i = 0; i < (int)MC::ndw; i++) cw[i] = 0;
     const int n = (int)L.n;
+    // The digit sums do not depend on the chain: the sum of the next digit is fetched before the hash of the current
+    // gate, so that its latency passes under the hash (a lane has nothing else to overlap it with).
+    uint32_t sm[MC::ndw], s1[M1::ndw];
+#pragma unroll
+    for (int i = 0; i < (int)MC::ndw; i++) sm[i] = ld_dw(L.sum[n], e, i);
     for (int j = n; j >= 3; j--) {                  // carry out of digit j into digit j-1, same modulus
         uint32_t in[MC::ndw];
 #pragma unroll
-        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(ld_dw(L.sum[j], e, i), cw[i], Mc);   // cw = 0 at j = n
+        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(sm[i], cw[i], Mc);   // cw = 0 at j = n
+#pragma unroll
+        for (int i = 0; i < (int)MC::ndw; i++) sm[i] = ld_dw(L.sum[j - 1], e, i);
         chain_gate(L, Mc, Mc, e, j, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { cw[i] = w; }, T);
     }
     {                                               // digit 2 -> carry into digit 1 (modulus of the first digit)
         uint32_t in[MC::ndw];
 #pragma unroll
-        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(ld_dw(L.sum[2], e, i), cw[i], Mc);
+        for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(sm[i], cw[i], Mc);
+#pragma unroll
+        for (int i = 0; i < (int)M1::ndw; i++) s1[i] = ld_dw(L.sum[1], e, i);
         chain_gate(L, Mc, Mf, e, 2, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { c1[i] = w; }, T);
     }
     {                                               // final gate: digit 1 -> the sign bit
         uint32_t in[M1::ndw];
 #pragma unroll
-        for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(ld_dw(L.sum[1], e, i), c1[i], Mf);
+        for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(s1[i], c1[i], Mf);
         Dw4 bits[8];                                // the 128 digits of the output wire: stored 16 bytes at a time
         chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { bits[i >> 2].w[i & 3] = w; }, T);
 #pragma unroll

@@ -90,25 +90,48 @@ struct DecodeArgs {
     uint8_t* valid;
 };
 
+// De: 16 lanes per value, one per residue: lane (value, i) recovers the residue a_i from the colours and checks the whole
+// label of residue i; the value's first lane then adds up the CRT terms.  (A lane per value that walked over the residues
+// spent the latency of k dependent label comparisons: 37 us for the ten outputs of one inference.)
 __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
-    uint32_t e = blockIdx.x * kThreads + threadIdx.x;
-    if (e >= A.n) return;
-    bool ok = true;
-    unsigned __int128 acc = 0;
-    for (uint32_t i = 0; i < A.k; i++) {
+    static_assert(DASH_MAX_PRIMES == 16 && kThreads % 16 == 0, "lane roles");
+    __shared__ uint32_t res[kThreads];                   // residue, or 0xffffffff for a label that is not valid
+    const uint32_t e = blockIdx.x * (kThreads / 16) + threadIdx.x / 16, i = threadIdx.x % 16;
+    uint32_t r = 0;
+    if (e < A.n && i < A.k) {
         const ModInfo M = A.mods[A.prime[i]];
         const LView &a = A.act[i], &z = A.zero[i];
         uint32_t a0 = *(const uint32_t*)(a.p + (uint64_t)e * 16), z0 = *(const uint32_t*)(z.p + (uint64_t)e * 16);
         uint32_t v = mod_m((a0 & 0xff) + M.m - (z0 & 0xff), M);      // colour difference; R's colour is 1
         const uint32_t* dv = M.dtab + (size_t)v * M.ndw;
+        bool ok = true;
         for (uint32_t j = 0; j < M.ndw; j++) {
             uint32_t aw = *(const uint32_t*)(a.p + (int64_t)(j >> 2) * a.cs + (uint64_t)e * 16 + (j & 3) * 4);
             uint32_t zw = *(const uint32_t*)(z.p + (int64_t)(j >> 2) * z.cs + (uint64_t)e * 16 + (j & 3) * 4);
             if (aw != addmod4(zw, dv[j], M)) ok = false;
         }
-        acc += (unsigned __int128)A.crt_coef[i] * v;
+        r = ok ? v : 0xffffffffu;
     }
-    uint64_t X = (uint64_t)(acc % A.P);
+    res[threadIdx.x] = r;
+    __syncthreads();
+    if (e >= A.n || i != 0) return;
+    bool ok = true;
+    uint64_t X = 0;                     // running CRT sum, kept below P
+    for (uint32_t t = 0; t < A.k; t++) {
+        const uint32_t v = res[threadIdx.x + t];
+        if (v == 0xffffffffu) { ok = false; continue; }
+        // X += v * coef mod P by doubling (v < 128, coef < P < 2^62: no overflow, no wide division)
+        uint64_t acc = 0;
+        const uint64_t cf = A.crt_coef[t];
+#pragma unroll
+        for (int b = 6; b >= 0; b--) {
+            acc += acc;
+            if (acc >= A.P) acc -= A.P;
+            if ((v >> b) & 1u) { acc += cf; if (acc >= A.P) acc -= A.P; }
+        }
+        X += acc;
+        if (X >= A.P) X -= A.P;
+    }
     int64_t s = (2 * X >= A.P) ? (int64_t)X - (int64_t)A.P : (int64_t)X;
     A.values[e] = ok ? s : 0;
     A.valid[e] = ok ? 1 : 0;
@@ -483,7 +506,7 @@ int dash_decode(dash_ctx* c, const dash_labels* act, const dash_labels* zero, in
         A.act[i] = view_of(act, i);
         A.zero[i] = view_of(zero, i);
     }
-    hipLaunchKernelGGL(k_decode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream, A);
+    hipLaunchKernelGGL(k_decode, dim3((uint32_t)((n + kThreads / 16 - 1) / (kThreads / 16))), dim3(kThreads), 0, (hipStream_t)stream, A);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
