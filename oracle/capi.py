@@ -52,7 +52,7 @@ def _ptrs(arrs):
 
 
 def hash_calls():
-    """hash evaluations since the library was loaded (a garbler spends exactly one per ciphertext)"""
+    """hash evaluations made by the calling thread so far (a garbler spends exactly one per ciphertext)"""
     return lib().orc_hash_calls()
 
 

@@ -204,10 +204,11 @@ static void draw(const octx *c, int domain, int layer, uint32_t slot, u64 elem, 
  * as a random permutation; Sec. Implementation: labels are compressed to 128 bits
  * first).  K = compress_p(L); X = K xor tweak; h = AES_fixed(X) xor X;
  * H = decompress_q(h).  tweak = elem:u64 | slot:u32 | layer:u16 | 0:u16. */
-static unsigned long long hash_calls;      /* every ciphertext costs the garbler exactly one hash: a way to count them */
-unsigned long long orc_hash_calls(void) { return __atomic_load_n(&hash_calls, __ATOMIC_RELAXED); }
+/* every ciphertext costs the garbler exactly one hash: a way to count them (per calling thread) */
+static __thread unsigned long long hash_calls;
+unsigned long long orc_hash_calls(void) { return hash_calls; }
 static void hash(const octx *c, const u8 *L, int p, int layer, uint32_t slot, u64 elem, int q, u8 *out) {
-    __atomic_fetch_add(&hash_calls, 1, __ATOMIC_RELAXED);
+    hash_calls++;
     u128 K = compress(L, c->lam[p], p);
     u128 T = (u128)elem | ((u128)slot << 64) | ((u128)(layer & 0xffff) << 96);
     u128 X = K ^ T;
