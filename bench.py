@@ -476,6 +476,35 @@ def micro_paper_models(torch, workloads):
                 note="the paper's figures (its table of online runtimes, other hardware) include a modelled 1 Gbit/s transfer; context only")
 
 
+def micro_aes(torch, workloads, log2_blocks=24, repeat=16, reps=3):
+    """AES-128 alone in the three forms the library holds (dash_profile.h): the gate kernels' T-table look-ups in LDS
+    in both table layouts, and the table-free bit-plane form (32 blocks per lane).  2^24 blocks resident in HBM,
+    `repeat` encryptions in a row per block so that the 32 bytes of traffic per block do not matter."""
+    from paper_2302_06361_amd import Context
+    ctx = Context(workloads.PRIMES[:3], bytes(range(16)), workloads.DIGITS[3])
+    n = 1 << log2_blocks
+    gen = torch.Generator(device=ctx.device)
+    gen.manual_seed(3)
+    d_in = torch.randint(0, 256, (n, 16), dtype=torch.uint8, device=ctx.device, generator=gen)
+    d_out = torch.empty_like(d_in)
+    names = ["tables_4KB_per_workgroup", "tables_per_bank_64KB", "bit_planes_32_blocks_per_lane"]
+    out = {}
+    for v, name in enumerate(names):
+        ctx.profile_aes(v, bytes(range(16)), d_in, d_out, repeat)       # warm-up
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            ctx.profile_aes(v, bytes(range(16)), d_in, d_out, repeat)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / reps
+        out[name] = dict(ms_per_launch=ms, blocks_per_s=n * repeat / (ms * 1e-3))
+    ctx.close()
+    return dict(workload="AES-128 alone: 2^%d blocks, %d encryptions in a row per block" % (log2_blocks, repeat), forms=out,
+                executed_valu_per_block=dict(bit_planes_32_blocks_per_lane=630, note="static count of the kernel's instructions"))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -485,7 +514,7 @@ def main():
     ap.add_argument("--images", type=int, default=2, help="images of config 5's batch of 64 to stream (64 = the whole config, about 11 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true", help="the config-2 step alone")
-    ap.add_argument("--only", choices=["config1", "config3", "config4", "config5", "paper_models"],
+    ap.add_argument("--only", choices=["config1", "config3", "config4", "config5", "paper_models", "aes"],
                     help="run one of the other configurations alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -499,7 +528,7 @@ def main():
 
     if a.only:
         fn = dict(config1=micro_mlp, config3=micro_projection, config4=micro_contraction,
-                  config5=lambda t, w: micro_vgg(t, w, images=a.images), paper_models=micro_paper_models)[a.only]
+                  config5=lambda t, w: micro_vgg(t, w, images=a.images), paper_models=micro_paper_models, aes=micro_aes)[a.only]
         print(json.dumps(fn(torch, workloads)))
         return
 

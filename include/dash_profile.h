@@ -22,6 +22,17 @@ enum { DASH_PROF_GARBLE = 0, DASH_PROF_EVAL = 1, DASH_PROF_LINEAR = 2, DASH_PROF
 int dash_profile_enable(dash_ctx *ctx, int on);
 int dash_profile_read(dash_ctx *ctx, int kind, double *ms, int64_t *launches, double *units, double *alg_bytes);
 
+/* AES-128 encryption alone (FIPS-197), in each form the library holds, for measuring them against each other
+ * and for checking each against the standard: out[i] = AES_key applied `repeat` times to in[i], i < n_blocks.
+ *   variant 0: T-tables in LDS, one 4 KB copy per workgroup (what small gate launches use);
+ *   variant 1: T-tables replicated per LDS bank, 64 KB per workgroup (what large gate launches use);
+ *   variant 2: bit planes, 32 blocks per lane, no tables; n_blocks must be a multiple of 2048 (DASH_ESIZE).
+ * key: 16 bytes, host.  in, out: device, 16 bytes per block, may be the same buffer.  Enqueues on `stream`
+ * (variant 2 first waits for the stream and copies its key masks into a per-GPU array of the library, so calls
+ * of variant 2 that overlap on one GPU race).  Allocates nothing. */
+int dash_profile_aes(dash_ctx *ctx, int variant, const uint8_t *key, const void *in, void *out, uint64_t n_blocks,
+                     int repeat, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ NOALLOC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = ["dash_ctx_create", "dash_ctx_destroy", "dash_lambda", "dash_ctx_offset", "dash_ctx_one", "dash_ctx_digits",
            "dash_layer_sizes", "dash_weights_bytes", "dash_weights_prepare", "dash_garble_layer", "dash_eval_layer",
-           "dash_garble_layers", "dash_eval_layers", "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_tables_packed_bytes", "dash_tables_pack", "dash_tables_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read"]
+           "dash_garble_layers", "dash_eval_layers", "dash_eval_layer_noalloc", "dash_input_labels", "dash_encode", "dash_decode", "dash_labels_pack", "dash_labels_unpack", "dash_tables_packed_bytes", "dash_tables_pack", "dash_tables_unpack", "dash_strerror", "dash_profile_enable", "dash_profile_read", "dash_profile_aes"]
 
 
 class DashError(RuntimeError):
@@ -198,6 +198,18 @@ class Context:
         ms, n, u, b = C.c_double(), C.c_int64(), C.c_double(), C.c_double()
         _check(self.L.dash_profile_read(self.h, int(kind), C.byref(ms), C.byref(n), C.byref(u), C.byref(b)), "dash_profile_read")
         return dict(ms=ms.value, launches=n.value, units=u.value, bytes=b.value)
+
+    def profile_aes(self, variant, key, blocks_in, blocks_out, repeat=1):
+        """AES-128 alone (variant 0: 4 KB tables, 1: bank-replicated tables, 2: bit planes) on device byte tensors
+        [n][16]; out = AES_key^repeat(in)"""
+        import torch
+        key = bytes(key)
+        assert len(key) == 16 and blocks_in.dtype == torch.uint8 and blocks_out.dtype == torch.uint8
+        assert blocks_in.is_cuda and blocks_out.is_cuda and blocks_in.is_contiguous() and blocks_out.is_contiguous()
+        assert blocks_in.numel() % 16 == 0 and blocks_out.numel() == blocks_in.numel()
+        kb = (C.c_uint8 * 16).from_buffer_copy(key)
+        _check(self.L.dash_profile_aes(self.h, int(variant), kb, C.c_void_p(blocks_in.data_ptr()), C.c_void_p(blocks_out.data_ptr()),
+                                       C.c_uint64(blocks_in.numel() // 16), int(repeat), _stream()), "dash_profile_aes")
 
     # ---- the ABI calls, same names -------------------------------------------------------------
     def layer_sizes(self, layer):

@@ -283,3 +283,35 @@ def test_cast_and_half_gate_bodies_under_sanitizers(tmp_path):
     run_cast(tmp_path, exe, 7, 40, 3, rule=1)
     run_cast(tmp_path, exe, 5, 70, 2, lam2=64)                   # label lengths given explicitly: modulus 2 shorter than 128
     run_cast(tmp_path, exe, 13, 33, 0, lam2=100, lam_p=9)
+
+
+def test_bitsliced_aes_against_the_standard_and_the_oracle(tmp_path):
+    """dash_aes_sliced.h (32 blocks per lane on bit planes, generated S-box circuit) on the host under the
+    sanitizers: FIPS-197 Appendix B and C.1 vectors, and random blocks under random keys against the oracle's AES."""
+    exe = os.path.join(HERE, "aes_sliced_emul.bin")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-o", exe, os.path.join(HERE, "aes_sliced_emul.cpp")])
+
+    def run(key, blocks):
+        fin, fout = str(tmp_path / "aes_in.bin"), str(tmp_path / "aes_out.bin")
+        open(fin, "wb").write(bytes(key) + blocks.tobytes())
+        r = subprocess.run([exe, fin, fout], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-3000:]
+        return np.fromfile(fout, np.uint8).reshape(-1, 16)
+
+    # Appendix C.1: key 00..0f, plaintext 00 11 .. ff
+    pt = np.zeros((32, 16), np.uint8)
+    pt[5] = np.frombuffer(bytes.fromhex("00112233445566778899aabbccddeeff"), np.uint8)
+    out = run(bytes(range(16)), pt)
+    assert out[5].tobytes().hex() == "69c4e0d86a7b0430d8cdb78070b4c55a"
+    # Appendix B: key 2b7e..., input 3243...
+    pt[31] = np.frombuffer(bytes.fromhex("3243f6a8885a308d313198a2e0370734"), np.uint8)
+    out = run(bytes.fromhex("2b7e151628aed2a6abf7158809cf4f3c"), pt)
+    assert out[31].tobytes().hex() == "3925841d02dc09fbdc118597196a0b32"
+    g = np.random.default_rng(5)
+    for _ in range(3):
+        key = g.integers(0, 256, 16, dtype=np.uint8)
+        blocks = g.integers(0, 256, (96, 16), dtype=np.uint8)
+        out = run(key.tobytes(), blocks)
+        for j in range(96):
+            assert (out[j] == capi.aes128_encrypt(key, blocks[j])).all(), j

@@ -190,3 +190,43 @@ def test_tables_pack_needs_rows_below_128_bits():
     with pytest.raises(DashError, match="not implemented"):
         ctx.tables_pack(lay, t, t)
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_aes_forms_against_the_standard_and_the_oracle(variant):
+    """Every form of AES-128 the library holds (4 KB tables, bank-replicated tables, bit planes) on the GPU: FIPS-197
+    Appendix B and C.1 vectors, random blocks against the oracle's AES, repeated application, the size rule of the
+    bit-plane form."""
+    import torch
+    from oracle import capi
+    from paper_2302_06361_amd import binding
+    ctx = binding.Context(workloads.PRIMES[:3], bytes(range(16)), workloads.DIGITS[3])
+    n = 4096 + (0 if variant == 2 else 77)
+    g = np.random.default_rng(11 + variant)
+    blocks = g.integers(0, 256, (n, 16), dtype=np.uint8)
+    blocks[5] = np.frombuffer(bytes.fromhex("00112233445566778899aabbccddeeff"), np.uint8)
+    blocks[2049] = np.frombuffer(bytes.fromhex("3243f6a8885a308d313198a2e0370734"), np.uint8)
+    d_in = torch.from_numpy(blocks).cuda()
+    d_out = torch.empty_like(d_in)
+    ctx.profile_aes(variant, bytes(range(16)), d_in, d_out)
+    out = d_out.cpu().numpy()
+    assert out[5].tobytes().hex() == "69c4e0d86a7b0430d8cdb78070b4c55a"
+    key_b = bytes.fromhex("2b7e151628aed2a6abf7158809cf4f3c")
+    ctx.profile_aes(variant, key_b, d_in, d_out)
+    out_b = d_out.cpu().numpy()
+    assert out_b[2049].tobytes().hex() == "3925841d02dc09fbdc118597196a0b32"
+    key_np = np.frombuffer(key_b, np.uint8)
+    for j in list(range(0, n, 97)) + [n - 1]:
+        assert (out_b[j] == capi.aes128_encrypt(key_np, blocks[j])).all(), j
+    # three applications in one call
+    ctx.profile_aes(variant, key_b, d_in, d_out, repeat=3)
+    out3 = d_out.cpu().numpy()
+    for j in (0, 63, 64, 2047, 2048, n - 1):
+        v = blocks[j]
+        for _ in range(3):
+            v = capi.aes128_encrypt(key_np, v)
+        assert (out3[j] == v).all(), j
+    if variant == 2:
+        with pytest.raises(binding.DashError):
+            ctx.profile_aes(2, key_b, d_in[:100], d_out[:100])
