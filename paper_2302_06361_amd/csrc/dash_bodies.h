@@ -345,6 +345,26 @@ DASH_HD void digits_eval_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, u
     }
 }
 
+// The same gates with one lane per (element, residue, digit j): every lane compresses the label again, but a lane's
+// chain is one hash instead of n.  For gadgets over few elements, whose time is the length of that chain.
+template <class MC, class M1, class Tab>
+DASH_HD void digits_eval_wide_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t j, uint32_t tx, const Tab& T) {
+    const DigitsRes& R = L.res[by];
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem || j < 1 || j > L.n) return;
+    const ModInfo Mp = L.mods[R.p];
+    uint32_t colour = 0;
+    U128 K = {{0, 0, 0, 0}};
+    with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(R.in, e, i); }, &colour); });
+    if constexpr (cmod_m<MC>::value != 0) {
+        if (j == 1) digit_gate(L, R, M1{nullptr}, K, colour, e, 1, T);
+        else digit_gate(L, R, MC{nullptr}, K, colour, e, (int)j, T);
+    } else {
+        const ModInfo Mo = L.mods[L.m[j]];
+        digit_gate(L, R, Mo, K, colour, e, (int)j, T);
+    }
+}
+
 // ---- garbler, digit gates of the sign gadget ---------------------------------------------------
 // One lane per (element g, value a) of a residue: the label of a is formed and compressed once, then one
 // ciphertext row per digit: rows[colour] = out0 + phi_j(a) R_{m_j} + H_{m_j}(label, slot_j).

@@ -64,6 +64,7 @@ struct dash_ctx {
     uint64_t banked_min_lanes;       // launches of this many lanes or more use the bank-replicated AES tables
     uint64_t fused_min_elems[2];     // [garble, eval]: sign gadgets over this many elements or more run their digit gates in
                                      // the fused kernels (a lane walks the n gates of a residue); smaller ones one gate per lane
+    uint64_t wide_max_lanes;         // evaluator: sign gadgets of at most this many digit gates run them one per lane
     uint64_t digits_banked_min_lanes;   // the banked-table threshold of the fused garbling kernel (n hashes per lane)
     const uint8_t* phi_pm1[DASH_MAX_PRIMES];                         // {1, p-1}
     int gemm_tile;                   // tile shape of the MFMA contraction: 0 by layer shape, 1 big, 2 wide (tuning and test hook)
@@ -82,6 +83,7 @@ int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s);
 int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
 int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
 int launch_cast_halve(const dash_ctx* c, CastLaunch& L, int njobs, hipStream_t s);
+int launch_cast_digits_eval(const dash_ctx* c, CastLaunch& C, int njobs, DigitsLaunch& L, hipStream_t s);
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
 
 // layer pipelines (dash_layers.hip)

@@ -157,7 +157,9 @@ GateJob phi_job(int p, int q, LView in, const uint8_t* phi, uint32_t slot, LView
 // up (optional): a second output wire, bit + up_coef * up_one.
 int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
               int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s, const LView* up = nullptr,
-              const LView* up_one = nullptr, uint32_t up_coef = 0) {
+              const LView* up_one = nullptr, uint32_t up_coef = 0, CastLaunch* pre = nullptr, int pre_jobs = 0) {
+    // pre (evaluator of the scaling gadget): the cast-and-halve step that produces x[first_res..]; it runs in the
+    // launch of the digit gates when they are fused, else in a launch of its own before them
     const int k = c->k, n = c->n;
     size_t off[DASH_MAX_PRIMES * DASH_MAX_DIGITS + DASH_MAX_DIGITS], cum = 0;
     for (int sl = 0; sl < sign_nslots(c); sl++) { off[sl] = cum * E; cum += sign_slot_bytes(c, sl, first_res); }
@@ -176,6 +178,10 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     // label: one launch for all k n gates, whose lanes form and compress a label once for n rows (garbler) or n
     // gates (evaluator).  Small gadgets keep one gate per lane (n times the lanes, a chain n times shorter).
     if (E < c->fused_min_elems[garble ? 0 : 1]) {
+        if (pre) {
+            const int st = launch_cast_halve(c, *pre, pre_jobs, s);
+            if (st) return st;
+        }
         for (int i = first_res; i < k; i++)
             for (int j = 1; j <= n; j++) {
                 int sl = i * n + (j - 1);
@@ -202,7 +208,7 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
                 if (c->phi_digit[i][j] != R.phi + (size_t)(j - 1) * c->prime[i]) return DASH_EINVAL;
             }
         }
-        const int st = garble ? launch_digits_garble(c, DL, s) : launch_digits_eval(c, DL, s);
+        const int st = garble ? launch_digits_garble(c, DL, s) : pre ? launch_cast_digits_eval(c, *pre, pre_jobs, DL, s) : launch_digits_eval(c, DL, s);
         if (st) return st;
     }
     // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
@@ -487,17 +493,19 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
                 J.addc = addc_of(p);
                 J.out = bnew[i];
                 cum += 2 * pitch_of(c, p);
-                if (nj == kMaxJobs || i == k - 1) {
-                    const int st = launch_cast_halve(c, CL, nj, s);
-                    if (st) return st;
-                    nj = 0;
-                }
             }
+            // (k - 1 <= kMaxJobs: one launch, which sign_core merges with the digit gates' when those are fused)
+            const uint32_t upc = (c0 + 1) % 2;
+            const int st = sign_core(c, false, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
+                                     last ? nullptr : &one[0], upc, &CL, nj);
+            if (st) return st;
         }
-        const uint32_t upc = (c0 + 1) % 2;
-        int st = sign_core(c, garble, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
-                           last ? nullptr : &one[0], upc);
-        if (st) return st;
+        if (garble) {
+            const uint32_t upc = (c0 + 1) % 2;
+            const int st = sign_core(c, true, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
+                                     last ? nullptr : &one[0], upc);
+            if (st) return st;
+        }
         if (last) {
             AffineBatcher ab(c, E, s);
             Term t0[2] = {Term{pl.w.bit, 1}, Term{one[0], c0}};

@@ -136,7 +136,7 @@ def digits_emul():
     return DIGITS_EXE
 
 
-def run_digits(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):
+def run_digits(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40, wide=False):
     """the n digit gates of every residue in one pass over its label: gate (t, j) is an ordinary projection gate
     p_t -> m_j with slot slot0 + t n + (j - 1) (Appendix, approximated sign), so every output must equal the
     oracle's evaluation of that gate on the same table segment"""
@@ -153,7 +153,7 @@ def run_digits(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_b
             t[:, :, :lam_o] = g.integers(0, mj, (n_elem, p, lam_o))
             row.append(t)
         tabs.append(row)
-    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 0, elem_base)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 2 if wide else 0, elem_base)
     blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % len(primes), *primes)
     blob += b"".join(a.tobytes() for a in acts)
     blob += b"".join(t.tobytes() for row in tabs for t in row)
@@ -180,6 +180,14 @@ def test_digit_gate_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5)                 # one digit, one residue
     run_digits(digits_emul, tmp_path, [5, 7], [26, 12, 12], 0, 100)      # a reduced-accuracy set
+
+
+def test_digit_gates_one_per_lane_under_sanitizers(digits_emul, tmp_path):
+    """the form for gadgets over few elements: a lane per (element, residue, digit)"""
+    run_digits(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 300, wide=True)
+    run_digits(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 260, wide=True)
+    run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1, wide=True)
+    run_digits(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
 
 def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):

@@ -100,11 +100,29 @@ def test_activation_bank_replicated_tables_forced(monkeypatch, k):
     byte of ReLU and scaling layers of the 8- and the 12-prime base against the oracle"""
     monkeypatch.setenv("DASH_BANKED_MIN_LANES", "1")
     monkeypatch.setenv("DASH_DIGITS_BANKED_MIN_LANES", "1")
+    monkeypatch.setenv("DASH_WIDE_MAX_LANES", "0")       # the evaluator's digit gates fused per residue, as on wide layers
     P = int(np.prod(workloads.PRIMES[:k]))
     g = np.random.default_rng(100 + k)
     X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], g.integers(0, P, 1296)])     # 1301 values: ragged tiles of 1024 lanes
     run_activation(k, "relu", X, elem_base=2 ** 31 + 3)
     run_activation(k, "scale", X[:333], repeat=2, elem_base=77)
+
+
+@pytest.mark.parametrize("wide", ["0", "1000000000000"])
+def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide):
+    """The evaluator runs the digit gates of a sign gadget one lane per (element, residue, digit) for gadgets over few
+    elements and one lane per (element, residue) with n hashes, fused with the scaling gadget's cast step, for the rest:
+    both forms forced on the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the
+    oracle."""
+    monkeypatch.setenv("DASH_WIDE_MAX_LANES", wide)
+    for k in (8, 12):
+        P = int(np.prod(workloads.PRIMES[:k]))
+        X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], np.random.default_rng(300 + k).integers(0, P, 296)])
+        run_activation(k, "relu", X, elem_base=5)
+        run_activation(k, "scale", X, repeat=3, elem_base=2 ** 32 + 1)
+    P5 = int(np.prod(workloads.PRIMES[:5]))
+    run_activation(5, "scale", np.random.default_rng(9).integers(0, P5, 300), repeat=2)       # run-time digit set
+    run_activation(5, "sign", np.random.default_rng(10).integers(0, P5, 300))
 
 
 def test_activation_floor_rule():
