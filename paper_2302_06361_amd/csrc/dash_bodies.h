@@ -417,6 +417,36 @@ DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by,
 
 // evaluator, scaling gadget: cast = rows[colour(y)] - H_p(y) (two-row gate Z_2 -> Z_p, identity function), then
 // b = (x + addc * one - cast) * 2^-1 mod p.  The cast label itself is not stored.
+template <class P>
+DASH_HD uint32_t halve4(uint32_t x, uint32_t cast, uint32_t inv2, const P& Pm) {
+    uint32_t b = 0;
+    // digits past lambda: x and cast are 0 there, and inv2 * p = 0 mod p
+    for (int b8 = 0; b8 < 4; b8++) b |= mod_m(mul24(inv2, byte_of(x, b8) + Pm.m - byte_of(cast, b8)), Pm) << (8 * b8);
+    return b;
+}
+// compile-time label length: b of element e in registers (xw: its chunks), 16-byte loads
+template <class PD>
+DASH_HD void cast_halve_regs(const CastJob& J, const PD& P, uint32_t e, uint32_t colour, const U128& h, Dw4* xw) {
+    constexpr int ndw = (int)PD::ndw, nch = (int)PD::nchunk;
+    const uint32_t inv2 = (J.p + 1) / 2;
+    const uint32_t* row = (const uint32_t*)(J.table + ((size_t)e * 2 + colour) * (P.ndw * 4));
+    uint32_t rw[ndw];
+#pragma unroll
+    for (int i = 0; i < ndw; i++) rw[i] = row[i];
+#pragma unroll
+    for (int ch = 0; ch < nch; ch++) xw[ch] = ld_chunk(J.x, e, ch);
+    if (J.addc) {
+#pragma unroll
+        for (int ch = 0; ch < nch; ch++) {
+            const Dw4 ow = ld_chunk(J.one, e, ch);
+#pragma unroll
+            for (int q = 0; q < 4; q++) xw[ch].w[q] = axpymod4(xw[ch].w[q], J.addc, ow.w[q], P);
+        }
+    }
+    decompress(P, h, [&](int i, uint32_t hd) { xw[i >> 2].w[i & 3] = halve4(xw[i >> 2].w[i & 3], submod4(rw[i], hd, P), inv2, P); });
+#pragma unroll
+    for (int i = ndw; i < nch * 4; i++) xw[i >> 2].w[i & 3] = 0;
+}
 template <class Tab>
 DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
     const CastJob& J = L.jobs[by];
@@ -429,43 +459,55 @@ DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint
     const uint32_t inv2 = (J.p + 1) / 2;
     with_mod(Mp, [&](auto P) {
         typedef decltype(P) PD;
-        const uint32_t* row = (const uint32_t*)(J.table + ((size_t)e * 2 + colour) * (P.ndw * 4));
-        auto halve = [&](uint32_t x, uint32_t cast) {
-            uint32_t b = 0;
-            // digits past lambda: x and cast are 0 there, and inv2 * p = 0 mod p
-            for (int b8 = 0; b8 < 4; b8++) b |= mod_m(mul24(inv2, byte_of(x, b8) + P.m - byte_of(cast, b8)), P) << (8 * b8);
-            return b;
-        };
         if constexpr (cmod_m<PD>::value != 0) {
-            // compile-time label length: everything in registers, 16-byte loads and stores
-            constexpr int ndw = (int)PD::ndw, nch = (int)PD::nchunk;
-            uint32_t rw[ndw];
-            Dw4 xw[nch];
+            Dw4 xw[PD::nchunk];
+            cast_halve_regs(J, P, e, colour, h, xw);
 #pragma unroll
-            for (int i = 0; i < ndw; i++) rw[i] = row[i];
-#pragma unroll
-            for (int ch = 0; ch < nch; ch++) xw[ch] = ld_chunk(J.x, e, ch);
-            if (J.addc) {
-#pragma unroll
-                for (int ch = 0; ch < nch; ch++) {
-                    const Dw4 ow = ld_chunk(J.one, e, ch);
-#pragma unroll
-                    for (int q = 0; q < 4; q++) xw[ch].w[q] = axpymod4(xw[ch].w[q], J.addc, ow.w[q], P);
-                }
-            }
-            decompress(P, h, [&](int i, uint32_t hd) { xw[i >> 2].w[i & 3] = halve(xw[i >> 2].w[i & 3], submod4(rw[i], hd, P)); });
-#pragma unroll
-            for (int i = ndw; i < nch * 4; i++) xw[i >> 2].w[i & 3] = 0;
-#pragma unroll
-            for (int ch = 0; ch < nch; ch++) st_chunk(J.out, e, ch, xw[ch]);
+            for (int ch = 0; ch < (int)PD::nchunk; ch++) st_chunk(J.out, e, ch, xw[ch]);
         } else {
+            const uint32_t* row = (const uint32_t*)(J.table + ((size_t)e * 2 + colour) * (P.ndw * 4));
             decompress(P, h, [&](int i, uint32_t hd) {
                 const uint32_t cast = submod4(row[i], hd, P);
                 uint32_t x = ld_dw(J.x, e, i);
                 if (J.addc) x = axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
-                st_dw(J.out, e, i, halve(x, cast));
+                st_dw(J.out, e, i, halve4(x, cast, inv2, P));
             });
             for (int i = (int)P.ndw; i < (int)P.nchunk * 4; i++) st_dw(J.out, e, i, 0);
+        }
+    });
+}
+
+// The cast step and ONE digit gate per lane: lane (element, odd prime, digit j) forms b as above (the lanes of
+// digit 1 store it), compresses it from its registers and evaluates digit gate j: a chain of two hashes, for
+// gadgets over few elements.  Only for primes with a compile-time description (the launcher checks).
+template <class MC, class M1, class Tab>
+DASH_HD void cast_digit_wide_body(const CastLaunch& C, const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t j, uint32_t tx, const Tab& T) {
+    const CastJob& J = C.jobs[by];
+    const DigitsRes& R = L.res[by];
+    const uint32_t e = bx * kThreads + tx;
+    if (e >= L.n_elem || j < 1 || j > L.n) return;
+    const ModInfo Mp = C.mods[J.p];
+    uint32_t colour = 0;
+    U128 K2 = compress_mod2(C.mods, [&](int i) { return ld_dw(C.y, e, i); }, &colour);
+    U128 h = hash_block(K2, C.elem_base + e, J.slot, C.layer, C.key.rk, T);
+    with_mod(Mp, [&](auto P) {
+        typedef decltype(P) PD;
+        if constexpr (cmod_m<PD>::value != 0) {
+            Dw4 xw[PD::nchunk];
+            cast_halve_regs(J, P, e, colour, h, xw);
+            if (j == 1) {
+#pragma unroll
+                for (int ch = 0; ch < (int)PD::nchunk; ch++) st_chunk(J.out, e, ch, xw[ch]);
+            }
+            uint32_t cb = 0;
+            const U128 K = compress(P, [&](int i) { return xw[i >> 2].w[i & 3]; }, &cb);
+            if constexpr (cmod_m<MC>::value != 0) {
+                if (j == 1) digit_gate(L, R, M1{nullptr}, K, cb, e, 1, T);
+                else digit_gate(L, R, MC{nullptr}, K, cb, e, (int)j, T);
+            } else {
+                const ModInfo Mo = L.mods[L.m[j]];
+                digit_gate(L, R, Mo, K, cb, e, (int)j, T);
+            }
         }
     });
 }
@@ -482,10 +524,27 @@ DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_
     U128 h = hash_block(K, L.elem_base + e, J.slot, L.layer, L.key.rk, T);
     uint32_t s = *(const uint32_t*)(J.S + ((size_t)e * 2 + colour) * 4);
     uint32_t beta = mod_m(s + Mp.m - mod_u128(h, Mp), Mp);
-    for (int i = 0; i < (int)Mp.nchunk * 4; i++) {
-        uint32_t v = axpymod4(ld_dw(J.V, e, i), beta, ld_dw(J.x, e, i), Mp);
-        st_dw(J.z, e, i, submod4(v, ld_dw(J.U, e, i), Mp));
-    }
+    with_mod(Mp, [&](auto P) {
+        typedef decltype(P) PD;
+        if constexpr (cmod_m<PD>::value != 0) {
+            // compile-time label length: all loads first, 16 bytes each, then the arithmetic in registers
+            constexpr int nch = (int)PD::nchunk;
+            Dw4 v[nch], x[nch], u[nch];
+#pragma unroll
+            for (int ch = 0; ch < nch; ch++) { v[ch] = ld_chunk(J.V, e, ch); x[ch] = ld_chunk(J.x, e, ch); u[ch] = ld_chunk(J.U, e, ch); }
+#pragma unroll
+            for (int ch = 0; ch < nch; ch++) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) v[ch].w[q] = submod4(axpymod4(v[ch].w[q], beta, x[ch].w[q], P), u[ch].w[q], P);
+                st_chunk(J.z, e, ch, v[ch]);
+            }
+        } else {
+            for (int i = 0; i < (int)P.nchunk * 4; i++) {
+                uint32_t v = axpymod4(ld_dw(J.V, e, i), beta, ld_dw(J.x, e, i), P);
+                st_dw(J.z, e, i, submod4(v, ld_dw(J.U, e, i), P));
+            }
+        }
+    });
 }
 
 }  // namespace dash

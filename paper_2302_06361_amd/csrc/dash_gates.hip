@@ -139,26 +139,85 @@ struct StagedSink {
     __device__ __forceinline__ void put(int i, uint32_t w) { st[i] = w; }
 };
 
+// a row kept in the lane's registers, with the address it goes to (0: the lane has no row to stage)
+template <int NDW> struct RegSink {
+    uint32_t w[NDW];
+    uint64_t addr = 0;
+    __device__ __forceinline__ void begin(uint8_t* table, uint64_t row_index, uint32_t pitch) { addr = (uint64_t)(table + row_index * pitch); }
+    __device__ __forceinline__ void put(int i, uint32_t v) { w[i] = v; }
+};
+
 template <class QD, bool Banked>
-__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const GateLaunch L) {
-    static_assert(!(stage_rows<QD>::value && Banked), "staged rows use the shared tables");
+__global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_proj_garble(const GateLaunch L) {
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
-    const uint64_t rows = (uint64_t)L.jobs[blockIdx.y].n_elem * L.jobs[blockIdx.y].p;      // (unused by the one-dimensional banked form)
+    const uint64_t rows = (uint64_t)L.jobs[blockIdx.y].n_elem * L.jobs[blockIdx.y].p;      // (unused by the one-dimensional banked forms)
     const uint32_t tiles = (uint32_t)((rows + kThreads - 1) / kThreads);
-    if constexpr (stage_rows<QD>::value) {
+    if constexpr (stage_rows<QD>::value && Banked) {
+        // Long rows with the bank-replicated tables: 64 KB of tables leave room to stage 16 dwords per lane, so a lane keeps
+        // its row in registers and its wave writes the rows out in ndw / 16 passes of 64 bytes per row, 16 bytes per lane,
+        // consecutive lanes consecutive pieces.  One-dimensional grid over the tiles of all jobs.
+        constexpr int ndw = stage_rows<QD>::ndw, kPass = 16, stride = kPass + 1, pieces = kPass / 4;
+        static_assert(ndw % kPass == 0, "whole passes");
+        __shared__ uint32_t tt[kBankTabWords];
+        __shared__ uint32_t stage[kBigThreads * stride];
+        __shared__ uint64_t sdst[kBigThreads];
+        const BankTab T = load_banktab(tt, L.ttab);
+        const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+        const int lane = threadIdx.x & 63, w0 = threadIdx.x & ~63;       // this wave's rows: w0 .. w0 + 63
+        auto tiles_of = [&](uint32_t j) { return (uint32_t)(((uint64_t)L.jobs[j].n_elem * L.jobs[j].p + kThreads - 1) / kThreads); };
+        uint32_t total = 0;
+        for (uint32_t j = 0; j < L.njobs; j++) total += tiles_of(j);
+        uint32_t job = 0, base = 0, next = tiles_of(0);
+        // (every wave stages and writes out its own 64 rows: no barrier between waves)
+        const uint32_t rounds = (total + gridDim.x * kGateTiles - 1) / (gridDim.x * kGateTiles);
+        for (uint32_t r = 0; r < rounds; r++) {
+            const uint32_t t = (r * gridDim.x + blockIdx.x) * kGateTiles + sub;
+            RegSink<ndw> sink;
+            if (t < total) {
+                while (t >= next) { job++; base = next; next += tiles_of(job); }
+                garble_body<QD>(L, t - base, __builtin_amdgcn_readfirstlane(job), tx, T, sink);
+            }
+            sdst[threadIdx.x] = sink.addr;
+#pragma unroll
+            for (int pass = 0; pass < ndw / kPass; pass++) {
+                if (sink.addr) {
+#pragma unroll
+                    for (int i = 0; i < kPass; i++) stage[threadIdx.x * stride + i] = sink.w[pass * kPass + i];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                for (int id = lane; id < 64 * pieces; id += 64) {
+                    const int k = w0 + id / pieces, part = id % pieces;
+                    const uint64_t d = sdst[k];
+                    if (d) {
+                        const uint32_t* src = stage + k * stride + part * 4;
+                        uint32_t* dst = (uint32_t*)(d + (uint64_t)pass * (kPass * 4) + part * 16);
+                        uint32_t v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3];
+                        dst[0] = v0; dst[1] = v1; dst[2] = v2; dst[3] = v3;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    } else if constexpr (stage_rows<QD>::value) {
+        // Long rows, shared tables: every WAVE stages its 64 rows in its own part of LDS and writes them out itself, 16 bytes
+        // per lane, eight consecutive lanes one row: no barrier between waves (a wave's LDS accesses complete in order).
         __shared__ uint32_t tt[kTabWords];
         const LdsTab T = load_ttab(tt, L.ttab);
         constexpr int ndw = stage_rows<QD>::ndw, stride = ndw + 1, pieces = ndw / 4;
         __shared__ uint32_t stage[kThreads * stride];
         __shared__ uint32_t srow[kThreads];
         uint8_t* table = L.jobs[blockIdx.y].table;
+        const int lane = threadIdx.x & 63, w0 = threadIdx.x & ~63;       // this wave's rows: w0 .. w0 + 63
         for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
             srow[threadIdx.x] = 0xffffffffu;
             StagedSink sink{stage + threadIdx.x * stride, srow + threadIdx.x};
             garble_body<QD>(L, tile, blockIdx.y, threadIdx.x, T, sink);
-            __syncthreads();
-            for (int id = threadIdx.x; id < kThreads * pieces; id += kThreads) {
-                const int k = id / pieces, part = id - k * pieces;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int id = lane; id < 64 * pieces; id += 64) {
+                const int k = w0 + id / pieces, part = id % pieces;
                 const uint32_t r = srow[k];
                 if (r != 0xffffffffu) {
                     const uint32_t* src = stage + k * stride + part * 4;
@@ -167,7 +226,8 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const
                     dst[0] = v0; dst[1] = v1; dst[2] = v2; dst[3] = v3;
                 }
             }
-            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     } else {
         __shared__ uint32_t tt[gate_tab<Banked>::words];
@@ -197,10 +257,8 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_garble(const
 #define DASH_GARBLE_K(MOD, LAM) k_proj_garble<CMod<MOD, LAM>, false>,
 static const GateKernel kGarbleKernels[] = {k_proj_garble<ModInfo, false>, DASH_HOT_MODS(DASH_GARBLE_K)};
 #undef DASH_GARBLE_K
-// with BankTab (the kernel for staged rows stays with the shared tables)
-template <class QD, bool Staged = stage_rows<QD>::value> struct banked_garble { static constexpr GateKernel k = k_proj_garble<QD, true>; };
-template <class QD> struct banked_garble<QD, true> { static constexpr GateKernel k = k_proj_garble<QD, false>; };
-#define DASH_GARBLE_KB(MOD, LAM) banked_garble<CMod<MOD, LAM>>::k,
+// with BankTab
+#define DASH_GARBLE_KB(MOD, LAM) k_proj_garble<CMod<MOD, LAM>, true>,
 static const GateKernel kGarbleKernelsBanked[] = {k_proj_garble<ModInfo, true>, DASH_HOT_MODS(DASH_GARBLE_KB)};
 #undef DASH_GARBLE_KB
 #define DASH_GARBLE_S(MOD, LAM) stage_rows<CMod<MOD, LAM>>::value,
@@ -213,7 +271,7 @@ static const bool kGarbleStaged[] = {false, DASH_HOT_MODS(DASH_GARBLE_S)};
 // compresses the label of a once for the n rows it garbles.  The residues differ in length (n_elem * p rows):
 // the blocks share the concatenation of their tiles (one-dimensional grid).
 template <class MC, class M1, bool Banked>
-__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_digits_garble(const DigitsLaunch L) {
+__global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_digits_garble(const DigitsLaunch L) {
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     __shared__ uint32_t tt[gate_tab<Banked>::words];
     const auto T = gate_tab<Banked>::load(tt, L.ttab);
@@ -297,12 +355,13 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
     if (rows >= (1ull << 32)) return DASH_ESIZE;      // staged rows carry a 32-bit row index
     const int ki = q ? hot_mod_index(c->mods[q]) : 0;
     const bool staged = kGarbleStaged[ki];
-    const bool banked = !staged && (uint64_t)units >= c->banked_min_lanes;
+    const bool banked = (uint64_t)units >= c->banked_min_lanes;
     L.njobs = (uint32_t)njobs;
     dim3 grid(gate_grid_x_for(blocks, njobs, banked), njobs);
     if (banked) {       // one-dimensional: all jobs' tiles, 1024 lanes (4 tiles) per block at a time, two blocks per CU
         const uint64_t nb = (tiles_sum + 3) / 4;
-        grid = dim3((uint32_t)(nb < 512 ? nb : 512));
+        const uint64_t cap = staged ? 256 : 512;      // (long rows also stage in LDS: one block per CU)
+        grid = dim3((uint32_t)(nb < cap ? nb : cap));
     }
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
     hipLaunchKernelGGL(banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);

@@ -15,7 +15,7 @@ namespace dash {
 
 // ------------------------------------------------------------------------------------------ eval
 template <class QD, bool Banked>
-__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_proj_eval(const GateLaunch L) {
+__global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_proj_eval(const GateLaunch L) {
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     __shared__ uint32_t tt[gate_tab<Banked>::words];
     const auto T = gate_tab<Banked>::load(tt, L.ttab);
@@ -62,7 +62,7 @@ int launch_eval(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
 // One launch for the k n digit gates of a sign gadget (four launches of k_proj_eval before), lane = (element,
 // residue): the label is loaded and compressed once for its n gates.
 template <class MC, class M1, bool Banked>
-__global__ __launch_bounds__(gate_tab<Banked>::threads) void k_digits_eval(const DigitsLaunch L) {
+__global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_digits_eval(const DigitsLaunch L) {
     constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
     __shared__ uint32_t tt[gate_tab<Banked>::words];
     const auto T = gate_tab<Banked>::load(tt, L.ttab);
@@ -238,6 +238,16 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads) void k_cast_digits_eval(
     }
 }
 
+// the same with one lane per (element, odd prime, digit): blockIdx.y = prime, blockIdx.z = digit - 1
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_cast_digit_wide(const CastLaunch C, const DigitsLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x)
+        cast_digit_wide_body<MC, M1>(C, L, tile, blockIdx.y, blockIdx.z + 1, threadIdx.x, T);
+}
+
 static int check_cast(const dash_ctx* c, const CastLaunch& L, int njobs, double* bytes) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
@@ -255,9 +265,35 @@ int launch_cast_digits_eval(const dash_ctx* c, CastLaunch& C, int njobs, DigitsL
     if (L.n < 1 || L.n > (uint32_t)kMaxChain || L.nres < 1 || L.nres > 16 || (int)L.nres != njobs) return DASH_EINVAL;
     if (C.n_elem != L.n_elem || C.layer != L.layer || C.elem_base != L.elem_base) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
-    if ((uint64_t)L.n_elem * L.nres * L.n <= c->wide_max_lanes) {      // few elements: a lane per digit gate, the cast step before it
-        const int st = launch_cast_halve(c, C, njobs, s);
-        return st ? st : launch_digits_eval(c, L, s);
+    if ((uint64_t)L.n_elem * L.nres * L.n <= c->wide_max_lanes) {
+        // few elements: a lane per digit gate that repeats the cast step of its residue (primes with compile-time label
+        // lengths), else the cast step in a launch of its own before the digit gates
+        bool hot = true;
+        for (int j = 0; j < njobs; j++) if (C.jobs[j].p > 255 || !hot_mod_index(c->mods[C.jobs[j].p])) hot = false;
+        if (!hot) {
+            const int st = launch_cast_halve(c, C, njobs, s);
+            return st ? st : launch_digits_eval(c, L, s);
+        }
+        bool uniform = false;
+        double bytes = 0;
+        int st = check_cast(c, C, njobs, &bytes);
+        if (st) return st;
+        st = check_digits(c, L, &uniform, &bytes);
+        if (st) return st;
+        for (uint32_t i = 0; i < L.nres; i++) {
+            const DigitsRes& R = L.res[i];
+            const CastJob& J = C.jobs[i];
+            if (R.p != J.p || R.in.p != J.out.p || R.in.cs != J.out.cs || R.in.es != J.out.es) return DASH_EINVAL;
+        }
+        C.key = c->fixed; C.ttab = c->d_ttab; C.mods = c->d_mods;
+        const int typed = typed_digits(c, L, uniform);
+        ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.nres * (L.n + 1), bytes);
+        dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)(L.nres * L.n)), L.nres, L.n);
+        if (typed == 1) hipLaunchKernelGGL((k_cast_digit_wide<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, C, L);
+        else if (typed == 2) hipLaunchKernelGGL((k_cast_digit_wide<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, C, L);
+        else hipLaunchKernelGGL((k_cast_digit_wide<ModInfo, ModInfo>), grid, dim3(kThreads), 0, s, C, L);
+        DASH_HIP(hipGetLastError());
+        return DASH_OK;
     }
     double bytes = 0;
     int st = check_cast(c, C, njobs, &bytes);

@@ -85,6 +85,50 @@ int main(int argc, char** argv) {
     for (uint32_t bx = 0; bx < tiles; bx++)
         for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) hg_finish_body(H, bx, 0, tx, HostTab());
 
+    // The lane-per-digit form of the cast step with the digit gates behind it (cast_digit_wide_body) against the two bodies
+    // it combines (cast_halve_body above, digits_eval_wide_body on its output): same b, same digit wires.  Two digits with
+    // moduli 26 and 96, tables filled by a small generator; exactly-sized buffers.  (Only primes with a compile-time
+    // description take that form.)
+    if (hot_mod_index(Mp)) {
+        const uint32_t dm[3] = {0, 26, 96};
+        DigitsLaunch D;
+        memset(&D, 0, sizeof(D));
+        expand_key(fixed, Sb, D.key.rk);
+        D.mods = mods.data(); D.elem_base = elem_base; D.layer = (uint32_t)layer; D.n_elem = n; D.n = 2; D.nres = 1;
+        D.out_cs = (int64_t)16 * n;
+        size_t out_bytes = 0, tab_bytes = 0;
+        for (int j = 1; j <= 2; j++) {
+            D.m[j] = dm[j];
+            D.row_prefix[j] = j == 1 ? 0 : D.row_prefix[j - 1] + mods[dm[j - 1]].ndw * 4;
+            D.out_prefix[j] = out_bytes;
+            out_bytes += (size_t)mods[dm[j]].nchunk * n * 16;
+            tab_bytes += (size_t)n * p * mods[dm[j]].ndw * 4;
+        }
+        std::vector<uint8_t> dtab(tab_bytes);
+        uint32_t lcg = 12345u + (uint32_t)p;
+        size_t at = 0;
+        for (int j = 1; j <= 2; j++)
+            for (size_t r = 0; r < (size_t)n * p; r++)
+                for (uint32_t d = 0; d < mods[dm[j]].ndw * 4; d++) {
+                    lcg = lcg * 1664525u + 1013904223u;
+                    dtab[at++] = d < mods[dm[j]].lam ? (uint8_t)((lcg >> 16) % dm[j]) : 0;
+                }
+        std::vector<uint8_t> o_ref(out_bytes, 0xEE), o_new(out_bytes, 0xEE), cb2((size_t)Mp.nchunk * n * 16, 0xEE);
+        D.res[0].p = (uint32_t)p; D.res[0].slot0 = (uint32_t)slot + 7; D.res[0].table = dtab.data();
+        D.res[0].in = LView{cb.data(), (int64_t)16 * n, 16u}; D.res[0].out = o_ref.data();
+        for (uint32_t bx = 0; bx < tiles; bx++)
+            for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++)
+                for (uint32_t j = 0; j <= 3; j++) digits_eval_wide_body<ModInfo, ModInfo>(D, bx, 0, j, tx, HostTab());
+        CastLaunch C2 = C;
+        C2.jobs[0].out = LView{cb2.data(), (int64_t)16 * n, 16u};
+        D.res[0].in = C2.jobs[0].out; D.res[0].out = o_new.data();
+        for (uint32_t bx = 0; bx < tiles; bx++)
+            for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++)
+                for (uint32_t j = 0; j <= 3; j++) cast_digit_wide_body<ModInfo, ModInfo>(C2, D, bx, 0, j, tx, HostTab());
+        if (cb2 != cb) { fprintf(stderr, "cast_digit_wide_body: b differs\n"); return 3; }
+        if (o_new != o_ref) { fprintf(stderr, "cast_digit_wide_body: digit wires differ\n"); return 3; }
+    }
+
     std::vector<uint8_t> ob((size_t)n * Mp.lam), oz((size_t)n * Mp.lam);
     from_chunked(cb, n, Mp, ob.data());
     from_chunked(cz, n, Mp, oz.data());
