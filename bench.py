@@ -308,6 +308,12 @@ def micro_projection(torch, workloads, reps=2):
                eval=dict(hbm_algorithmic_GBps=eval_bytes / (ems * 1e-3) / 1e9, hbm_frac=eval_bytes / (ems * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          alu_frac_algorithmic=ops_e / (ems * 1e-3) / 1e12 / ALU_PEAK_TOPS),
                kernels=dict(k_proj_garble=kg, k_proj_eval=ke))
+    pmc, note = load_pmc()
+    if pmc and "proj2p24_eval_traffic_bytes_per_gate" in pmc:
+        # HBM bytes from the committed counters (FETCH_SIZE + WRITE_SIZE, scaled): the evaluator's row gather moves whole lines
+        et, gt = pmc["proj2p24_eval_traffic_bytes_per_gate"] * pb.n, pmc["proj2p24_garble_traffic_bytes_per_row"] * pb.rows
+        out["eval"].update(traffic=et, hbm_traffic_GBps=et / (ems * 1e-3) / 1e9, hbm_traffic_frac=et / (ems * 1e-3) / 1e9 / HBM_PEAK_GBS, counters=note)
+        out["garble"].update(traffic=gt, hbm_traffic_GBps=gt / (gms * 1e-3) / 1e9, counters=note)
     del pb
     ctx.close()
     torch.cuda.empty_cache()
