@@ -55,7 +55,11 @@ struct LinArgs {
     LinPrime pr[DASH_MAX_PRIMES];
 };
 
-// one lane per (output value, chunk): 16 accumulators, one 16-byte label word per tap; blockIdx.y = prime
+// S lanes per (output value, chunk): 16 accumulators, one 16-byte label word per tap; blockIdx.y = prime.  S = 1 for
+// layers with enough outputs to fill the chip; S = 16 for layers with few (the last dense layers of a network at
+// batch 1): the reduction index is dealt out in groups of four to 16 neighbouring lanes, whose partial sums are
+// added up with lane shuffles, so that a lane's loop is 16 times shorter.
+template <int S>
 __global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs AA) {
     struct { uint32_t p; const int8_t* w; const int32_t* bias; const uint8_t* one; LView in, out; int64_t kpad;
              int batch, in_h, in_w, in_c, out_c, kh, kw, stride, pad, out_h, out_w; } A;
@@ -67,8 +71,10 @@ __global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs AA) {
     }
     const ModInfo M = AA.mods[A.p];
     const int64_t n_out = (int64_t)A.batch * A.out_h * A.out_w * A.out_c;
-    int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (idx >= n_out * M.nchunk) return;
+    const int64_t gl = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t idx = gl / S;
+    const int sl = (int)(gl % S);                       // this lane's share of the reduction index
+    if (idx >= n_out * M.nchunk) return;                // (the S lanes of an output leave together)
     const uint32_t ch = (uint32_t)(idx / n_out);
     const int64_t o = idx - (int64_t)ch * n_out;
     int co = (int)(o % A.out_c);
@@ -86,7 +92,11 @@ __global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs AA) {
     // four taps instead of 128 with a multiply-add per byte).
     const int K = A.kh * A.kw * A.in_c;
     int ky = 0, kx = 0, ci = 0;
-    for (int k0 = 0; k0 < K; k0 += 4) {
+    for (int k0 = 4 * sl; k0 < K; k0 += 4 * S) {
+        if constexpr (S > 1) {                          // not consecutive groups: the tap of k0 by division
+            const int tap = k0 / A.in_c;
+            ci = k0 - tap * A.in_c; ky = tap / A.kw; kx = tap - ky * A.kw;
+        }
         const uint32_t w4 = *(const uint32_t*)(wrow + k0);
         uint4 v[4];
 #pragma unroll
@@ -111,6 +121,14 @@ __global__ __launch_bounds__(kThreads) void k_linear_direct(const LinArgs AA) {
             acc[4 * q + 2] = __builtin_amdgcn_udot4(d2, w4, acc[4 * q + 2], false);
             acc[4 * q + 3] = __builtin_amdgcn_udot4(d3, w4, acc[4 * q + 3], false);
         }
+    }
+    if constexpr (S > 1) {
+        // the S partial sums of every accumulator (S consecutive lanes of one wave, all of them here): butterfly
+#pragma unroll
+        for (int off = S / 2; off >= 1; off >>= 1)
+#pragma unroll
+            for (int d = 0; d < 16; d++) acc[d] += (uint32_t)__shfl_xor((int)acc[d], off, 64);
+        if (sl != 0) return;
     }
     // (p-1)^2 * K < 2^31 is checked on the host; reduce in two steps so the magic division applies (n < 2^24)
     uint32_t bm = 0;
@@ -224,7 +242,11 @@ int linear_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_label
     }
     {
         ProfScope ps(c->prof, DASH_PROF_LINEAR, s, macs, bytes);
-        hipLaunchKernelGGL(k_linear_direct, dim3((uint32_t)((lanes + kThreads - 1) / kThreads), c->k), dim3(kThreads), 0, s, A);
+        // few outputs and a long reduction: 16 lanes per output
+        if (lanes <= 16384 && K >= 64)
+            hipLaunchKernelGGL(k_linear_direct<16>, dim3((uint32_t)((lanes * 16 + kThreads - 1) / kThreads), c->k), dim3(kThreads), 0, s, A);
+        else
+            hipLaunchKernelGGL(k_linear_direct<1>, dim3((uint32_t)((lanes + kThreads - 1) / kThreads), c->k), dim3(kThreads), 0, s, A);
     }
     DASH_HIP(hipGetLastError());
     return DASH_OK;

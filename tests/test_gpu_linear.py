@@ -63,6 +63,9 @@ def test_conv_lenet_shapes():
 def test_conv_stride_and_padding():
     run_linear(5, 2, 9, 9, 3, 4, 3, 2, 1, -3, 3, True, 7)
     run_linear(5, 1, 8, 8, 2, 5, 4, 2, 0, -3, 3, False, 8)
+    # few outputs and a long reduction (the form with 16 lanes per output), taps outside the image, odd channel count
+    run_linear(5, 1, 6, 6, 8, 3, 3, 1, 1, -3, 3, True, 12)
+    run_linear(8, 2, 5, 5, 7, 2, 5, 2, 2, -8, 7, True, 13, garble=False)
 
 
 def test_conv_vgg_block_shape():
