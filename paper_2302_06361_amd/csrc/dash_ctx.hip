@@ -104,13 +104,19 @@ __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
         uint32_t a0 = *(const uint32_t*)(a.p + (uint64_t)e * 16), z0 = *(const uint32_t*)(z.p + (uint64_t)e * 16);
         uint32_t v = mod_m((a0 & 0xff) + M.m - (z0 & 0xff), M);      // colour difference; R's colour is 1
         const uint32_t* dv = M.dtab + (size_t)v * M.ndw;
-        bool ok = true;
-        for (uint32_t j = 0; j < M.ndw; j++) {
-            uint32_t aw = *(const uint32_t*)(a.p + (int64_t)(j >> 2) * a.cs + (uint64_t)e * 16 + (j & 3) * 4);
-            uint32_t zw = *(const uint32_t*)(z.p + (int64_t)(j >> 2) * z.cs + (uint64_t)e * 16 + (j & 3) * 4);
-            if (aw != addmod4(zw, dv[j], M)) ok = false;
+        // whole label: active = zero + v R, a 16-digit chunk (16 bytes of each label) at a time
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        uint32_t bad = 0;
+        for (uint32_t ch = 0; ch < M.nchunk; ch++) {
+            const u32x4 aw = *(const u32x4*)(a.p + (int64_t)ch * a.cs + (uint64_t)e * 16);
+            const u32x4 zw = *(const u32x4*)(z.p + (int64_t)ch * z.cs + (uint64_t)e * 16);
+#pragma unroll
+            for (uint32_t q = 0; q < 4; q++) {
+                const uint32_t j = 4 * ch + q;
+                if (j < M.ndw) bad |= aw[q] ^ addmod4(zw[q], dv[j], M);
+            }
         }
-        r = ok ? v : 0xffffffffu;
+        r = bad ? 0xffffffffu : v;
     }
     res[threadIdx.x] = r;
     __syncthreads();
