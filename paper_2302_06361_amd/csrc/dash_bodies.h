@@ -419,6 +419,13 @@ DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by,
 // b = (x + addc * one - cast) * 2^-1 mod p.  The cast label itself is not stored.
 template <class P>
 DASH_HD uint32_t halve4(uint32_t x, uint32_t cast, uint32_t inv2, const P& Pm) {
+    if (Pm.m <= 127) {
+        // four digits at once (p odd): t = (x - cast) mod p, then t / 2 for even t and (t + p) / 2 for odd t.  Bytes stay
+        // below 2p <= 254, and the bit that the shift brings in from the byte above is masked off.
+        const uint32_t t = submod4(x, cast, Pm);
+        const uint32_t odd = t & 0x01010101u;
+        return ((t + odd * Pm.m) >> 1) & 0x7f7f7f7fu;
+    }
     uint32_t b = 0;
     // digits past lambda: x and cast are 0 there, and inv2 * p = 0 mod p
     for (int b8 = 0; b8 < 4; b8++) b |= mod_m(mul24(inv2, byte_of(x, b8) + Pm.m - byte_of(cast, b8)), Pm) << (8 * b8);
@@ -440,7 +447,7 @@ DASH_HD void cast_halve_regs(const CastJob& J, const PD& P, uint32_t e, uint32_t
         for (int ch = 0; ch < nch; ch++) {
             const Dw4 ow = ld_chunk(J.one, e, ch);
 #pragma unroll
-            for (int q = 0; q < 4; q++) xw[ch].w[q] = axpymod4(xw[ch].w[q], J.addc, ow.w[q], P);
+            for (int q = 0; q < 4; q++) xw[ch].w[q] = J.addc == 1 ? addmod4(xw[ch].w[q], ow.w[q], P) : axpymod4(xw[ch].w[q], J.addc, ow.w[q], P);
         }
     }
     decompress(P, h, [&](int i, uint32_t hd) { xw[i >> 2].w[i & 3] = halve4(xw[i >> 2].w[i & 3], submod4(rw[i], hd, P), inv2, P); });
@@ -469,7 +476,7 @@ DASH_HD void cast_halve_body(const CastLaunch& L, uint32_t bx, uint32_t by, uint
             decompress(P, h, [&](int i, uint32_t hd) {
                 const uint32_t cast = submod4(row[i], hd, P);
                 uint32_t x = ld_dw(J.x, e, i);
-                if (J.addc) x = axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
+                if (J.addc) x = J.addc == 1 ? addmod4(x, ld_dw(J.one, e, i), P) : axpymod4(x, J.addc, ld_dw(J.one, e, i), P);
                 st_dw(J.out, e, i, halve4(x, cast, inv2, P));
             });
             for (int i = (int)P.ndw; i < (int)P.nchunk * 4; i++) st_dw(J.out, e, i, 0);

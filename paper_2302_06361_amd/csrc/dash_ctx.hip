@@ -317,13 +317,16 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
 
     // device pool layout
     size_t bytes = phi.size();
-    size_t off_delta[256], off_dtab[256], off_one0[DASH_MAX_PRIMES], off_one[DASH_MAX_PRIMES];
+    size_t off_delta[256], off_dtab[256], off_one0[DASH_MAX_PRIMES], off_one[DASH_MAX_PRIMES], off_shift[DASH_MAX_PRIMES];
     auto take = [&](size_t n) { size_t o = bytes; bytes += (n + 255) & ~(size_t)255; return o; };
     for (int m = 2; m < 256; m++) if (used[m]) {
         off_delta[m] = take(c->mods[m].nchunk * 16);
         off_dtab[m] = take((size_t)m * c->mods[m].ndw * 4);
     }
-    for (int i = 0; i < k; i++) { off_one0[i] = take(c->mods[c->prime[i]].nchunk * 16); off_one[i] = take(c->mods[c->prime[i]].nchunk * 16); }
+    for (int i = 0; i < k; i++) {
+        off_one0[i] = take(c->mods[c->prime[i]].nchunk * 16); off_one[i] = take(c->mods[c->prime[i]].nchunk * 16);
+        off_shift[i] = take(c->mods[c->prime[i]].nchunk * 16);
+    }
     const size_t off_zero = take(256);
     c->pool_bytes = bytes;
 
@@ -346,6 +349,7 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
         for (int i = 0; i < k; i++) {
             c->d_one0[i] = c->d_pool + off_one0[i];
             c->d_one[i] = c->d_pool + off_one[i];
+            c->d_shift[i] = c->d_pool + off_shift[i];
             for (int j = 1; j <= c->n; j++) c->phi_digit[i][j] = c->d_pool + off_digit[(size_t)i * (c->n + 1) + j];
             c->phi_pm1[i] = c->d_pool + off_pm1[i];
         }
@@ -381,6 +385,13 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
             A.terms[0] = Term{LView{c->d_one0[i], 16, 16}, 1};
             A.terms[1] = Term{LView{c->d_delta[p], 16, 16}, 1};
             A.jobs[0] = AffineJob{(uint32_t)p, 0, 2, 0, LView{c->d_one[i], 16, 16}};
+            if (launch_affine(c, A, 1, 0) != DASH_OK) { fail = true; break; }
+            // the constant that the scaling gadget's halving adds from its second repetition on (Sec. The Scaling Operation,
+            // ShiftDown by floor(P / 4)), as a label: (-floor(P / 4) mod p) * one
+            memset(&A, 0, sizeof(A));
+            A.n_elem = 1;
+            A.terms[0] = Term{LView{c->d_one[i], 16, 16}, (uint32_t)(((uint64_t)p - (c->P / 4) % (uint64_t)p) % (uint64_t)p)};
+            A.jobs[0] = AffineJob{(uint32_t)p, 0, 1, 0, LView{c->d_shift[i], 16, 16}};
             if (launch_affine(c, A, 1, 0) != DASH_OK) { fail = true; break; }
         }
         if (fail) break;

@@ -55,6 +55,7 @@ struct dash_ctx {
     uint8_t* d_delta[256];           // chunked label of R_m (nchunk*16 bytes)
     uint8_t* d_one0[DASH_MAX_PRIMES];
     uint8_t* d_one[DASH_MAX_PRIMES];
+    uint8_t* d_shift[DASH_MAX_PRIMES];   // (-floor(P / 4) mod p) times the active one-label: the ShiftDown constant of the scaling gadget, evaluator's side
     // function tables (device)
     const uint8_t* phi_digit[DASH_MAX_PRIMES][DASH_MAX_DIGITS + 1];  // [i][j] -> [p_i]
     const uint8_t* phi_carry[DASH_MAX_DIGITS + 1];                   // [j] -> [m_j], j = 2..n

@@ -489,8 +489,9 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
                 CastJob& J = CL.jobs[nj++];
                 J.p = p; J.slot = sb + (i - 1); J.table = tb + cum * E;
                 J.x = rep == 0 ? x[i] : bold[i];
-                J.one = one[i];
-                J.addc = addc_of(p);
+                // the constant comes as a label of its own (the context holds addc * one): coefficient 1, a packed addition
+                J.one = LView{c->d_shift[i], 16, 0u};
+                J.addc = addc_of(p) ? 1u : 0u;
                 J.out = bnew[i];
                 cum += 2 * pitch_of(c, p);
             }
