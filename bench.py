@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """bench.py -- one GPU, the whole hot path.
 
-A "step" is one pass of the whole path over one batch of synthetic input on config 2 of the benchmark spec, the
-configuration the metric is quoted on: garble the LeNet-5-shaped network (batch 16, 8-prime CRT base, 128-bit
+A "step" is one pass of the whole path over one batch of synthetic input on the second of the five benchmark
+configurations, the one the metric is quoted on: garble the LeNet-5-shaped network (batch 16, 8-prime CRT base, 128-bit
 labels), encode the inputs, evaluate the garbled network, decode.  Inputs, weights and every buffer are resident
 in HBM before the timed region.  The other four configurations are measured after the timed steps and reported
 in `configs` of the same JSON line (config 1: batch-1 latency; config 3: projection gates/s; config 4:
@@ -59,7 +59,11 @@ def load_pmc():
     return vals, "taken at commit %s%s" % (vals.get("commit", "?"), "; STALE: the gate-kernel sources have changed since" if stale else "")
 
 
-# ---- algorithmic work of one hash, in 32-bit lane operations (derivation: the design doc, Measurement) ----------------
+# ---- algorithmic work of one hash, in 32-bit lane operations ---------------------------------------------------
+# What the method needs on a 32-bit SIMD lane, however the kernels are written: AES 256 (160 table indices, two
+# three-input xors per column and round, 16 for the last round, 4 for the feed-forward); label of value a: 4 per dword;
+# compress: 3 per dword + 16 for the wide multiply-adds; base-q digits: 3 per digit + 132 for the long division of the
+# 128-bit number; packed modular additions: 4 per dword.
 def _lam_ceil(m):
     lam, v = 0, 1
     while v < (1 << 128):
