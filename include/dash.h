@@ -173,8 +173,9 @@ int dash_eval_layers(dash_ctx *ctx, int n, const dash_layer *layers, const dash_
 int dash_eval_layer_noalloc(dash_ctx *ctx, const dash_layer *layer, const dash_labels *in_act, const void *tables,
                             dash_labels *out_act, void *hip_stream);
 
-/* e: zero labels of circuit-input wires first_wire .. first_wire + zero->n_elem - 1, every residue. */
-int dash_input_labels(dash_ctx *ctx, int64_t first_wire, dash_labels *zero, void *hip_stream);
+/* e: zero labels of the circuit-input wires first_wire .. first_wire + n - 1, every residue, into elements 0 .. n - 1
+ * of `zero` (n <= zero->n_elem, else DASH_EINVAL). */
+int dash_input_labels(dash_ctx *ctx, int64_t first_wire, int64_t n, dash_labels *zero, void *hip_stream);
 /* En: out = zero + (value mod p) * R_p (Sec. Quantization and Encoding: Encode(x) = x mod P).
  * values: device int64 [n].  A residue whose data pointer is NULL in both bundles is skipped (bundles that carry
  * a single residue, as the inputs of PROJ gates do); NULL in only one of them is DASH_EINVAL. */

@@ -229,9 +229,11 @@ class Context:
         torch.cuda.current_stream().synchronize()     # wt may be freed after return
         return buf
 
-    def input_labels(self, first_wire, zero):
+    def input_labels(self, first_wire, zero, n=None):
+        """zero labels of the input wires first_wire .. first_wire + n - 1 (n: all elements of `zero` by default)"""
         cz = zero.c()
-        _check(self.L.dash_input_labels(self.h, C.c_int64(first_wire), C.byref(cz), _stream()), "dash_input_labels")
+        n = cz.n_elem if n is None else n
+        _check(self.L.dash_input_labels(self.h, C.c_int64(first_wire), C.c_int64(n), C.byref(cz), _stream()), "dash_input_labels")
 
     def encode(self, values, zero, out):
         cz, co = zero.c(), out.c()

@@ -473,10 +473,9 @@ static int check_labels(const dash_ctx* c, const dash_labels* t, int64_t n, int 
     return DASH_OK;
 }
 
-int dash_input_labels(dash_ctx* c, int64_t first_wire, dash_labels* zero, void* stream) {
-    if (!c || !zero || first_wire < 0) return DASH_EINVAL;
-    int64_t n = zero->n_elem;
-    if (n < 0 || n > 0x7fffffff) return DASH_ESIZE;
+int dash_input_labels(dash_ctx* c, int64_t first_wire, int64_t n, dash_labels* zero, void* stream) {
+    if (!c || !zero || first_wire < 0 || n < 0 || n > zero->n_elem) return DASH_EINVAL;
+    if (n > 0x7fffffff) return DASH_ESIZE;
     int st = check_labels(c, zero, n);
     if (st) return st;
     DrawLaunch L;

@@ -46,6 +46,24 @@ def test_input_labels_encode_decode(n):
     assert (values.cpu().numpy() == rv).all() and (valid.cpu().numpy() == rok).all() and rok.all()
 
 
+def test_input_labels_count_argument():
+    """dash_input_labels draws the first n labels of the tensor and leaves the rest alone; n beyond the tensor is refused"""
+    from paper_2302_06361_amd import Labels
+    from paper_2302_06361_amd.binding import DashError
+    ctx, orc = both(5)
+    zero = Labels(ctx, 300, zero=True)
+    ctx.input_labels(77, zero, n=130)
+    torch.cuda.synchronize()
+    for i in range(5):
+        got = zero.to_numpy(i)
+        assert (got[:130] == orc.input_labels(77, 130, i)).all()
+        assert (got[130:] == 0).all()
+    with pytest.raises(DashError):
+        ctx.input_labels(0, zero, n=301)
+    with pytest.raises(DashError):
+        ctx.input_labels(0, zero, n=-1)
+
+
 def test_decode_flags_forged_labels():
     ctx, orc = both(5)
     n = 300
