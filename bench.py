@@ -490,8 +490,8 @@ def micro_paper_models(torch, workloads):
 
 
 def micro_aes(torch, workloads, log2_blocks=24, repeat=16, reps=3):
-    """AES-128 alone in the three forms the library holds (dash_profile.h): the gate kernels' T-table look-ups in LDS
-    in both table layouts, and the table-free bit-plane form (32 blocks per lane).  2^24 blocks resident in HBM,
+    """AES-128 alone in the forms the library holds (dash_profile.h): the gate kernels' T-table look-ups in LDS
+    in both table layouts, the table-free bit-plane form (32 blocks per lane), and all four tables per bank.  2^24 blocks resident in HBM,
     `repeat` encryptions in a row per block so that the 32 bytes of traffic per block do not matter."""
     from paper_2302_06361_amd import Context
     ctx = Context(workloads.PRIMES[:3], bytes(range(16)), workloads.DIGITS[3])
@@ -500,7 +500,7 @@ def micro_aes(torch, workloads, log2_blocks=24, repeat=16, reps=3):
     gen.manual_seed(3)
     d_in = torch.randint(0, 256, (n, 16), dtype=torch.uint8, device=ctx.device, generator=gen)
     d_out = torch.empty_like(d_in)
-    names = ["tables_4KB_per_workgroup", "tables_per_bank_64KB", "bit_planes_32_blocks_per_lane"]
+    names = ["tables_4KB_per_workgroup", "tables_per_bank_64KB", "bit_planes_32_blocks_per_lane", "four_tables_per_bank_128KB"]
     out = {}
     for v, name in enumerate(names):
         ctx.profile_aes(v, bytes(range(16)), d_in, d_out, repeat)       # warm-up

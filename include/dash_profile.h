@@ -27,6 +27,8 @@ int dash_profile_read(dash_ctx *ctx, int kind, double *ms, int64_t *launches, do
  *   variant 0: T-tables in LDS, one 4 KB copy per workgroup (what small gate launches use);
  *   variant 1: T-tables replicated per LDS bank, 64 KB per workgroup (what large gate launches use);
  *   variant 2: bit planes, 32 blocks per lane, no tables; n_blocks must be a multiple of 2048 (DASH_ESIZE).
+ *   variant 3: all four T-tables replicated per LDS bank, 128 KB per workgroup (no gate kernel uses it: they run
+ *              slower with half the waves per SIMD).
  * key: 16 bytes, host.  in, out: device, 16 bytes per block, may be the same buffer.  Enqueues on `stream`
  * (variant 2 first waits for the stream and copies its key masks into a per-GPU array of the library, so calls
  * of variant 2 that overlap on one GPU race).  Allocates nothing. */

@@ -200,7 +200,7 @@ class Context:
         return dict(ms=ms.value, launches=n.value, units=u.value, bytes=b.value)
 
     def profile_aes(self, variant, key, blocks_in, blocks_out, repeat=1):
-        """AES-128 alone (variant 0: 4 KB tables, 1: bank-replicated tables, 2: bit planes) on device byte tensors
+        """AES-128 alone (variant 0: 4 KB tables, 1: bank-replicated tables T0/T1, 2: bit planes, 3: bank-replicated T0..T3) on device byte tensors
         [n][16]; out = AES_key^repeat(in)"""
         import torch
         key = bytes(key)

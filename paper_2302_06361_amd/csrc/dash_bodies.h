@@ -92,6 +92,9 @@ struct DirectSink {
     DASH_HD void put(int i, uint32_t w) { row[i] = w; }
 };
 
+// tag: the output modulus' compile-time description is chosen per job inside the kernel
+struct PerJobMod {};
+
 // garble: one lane per ciphertext row r = gate * p + a.  QD: description type of the output modulus
 // (every job of a launch has the same output modulus), fixed at compile time for the hot moduli.
 template <class QD, class Tab, class Sink>
@@ -119,7 +122,9 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
 
     // the output modulus: the kernel's compile-time description, or the run-time record (the instantiation for any
     // modulus, which also serves launches that mix output moduli; choosing a compile-time description per job inside
-    // it, as eval_body does, was measured much slower here: the kernel then needs the registers of its largest case)
+    // it, as eval_body does, was measured much slower on large launches: the kernel then needs the registers of its
+    // largest case), or, QD = PerJobMod, that choice per job: for launches of few rows, where a lane's run time and
+    // not the number of waves in flight decides)
     auto finish = [&](const auto& Q) {
         typedef std::decay_t<decltype(Q)> QT;
         if (J.mode == PAY_SHORT) {
@@ -154,6 +159,7 @@ DASH_HD void garble_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t
         }
     };
     if constexpr (cmod_m<QD>::value != 0) finish(make_mod<QD>::from(Mq));
+    else if constexpr (std::is_same<QD, PerJobMod>::value) with_mod(Mq, finish);
     else finish(Mq);
 }
 
@@ -386,8 +392,10 @@ DASH_HD void digit_row(const DigitsLaunch& L, const DigitsRes& R, const MO& Mo, 
         decompress(Mo, h, [&](int i, uint32_t hd) { row[i] = addmod4(addmod4(ld_dw(out0, g, i), gload32(df + i), Mo), hd, Mo); });
     }
 }
+// j0 = 0: all n digits of the lane's (element, value); j0 = 1..n: digit j0 only (gadgets over few elements: a lane per
+// row, a chain of one hash)
 template <class MC, class M1, class Tab>
-DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T, uint32_t j0 = 0) {
     const DigitsRes& R = L.res[by];
     const ModInfo Mp = L.mods[R.p];
     const uint64_t r0 = (uint64_t)bx * kThreads;
@@ -403,12 +411,15 @@ DASH_HD void digits_garble_body(const DigitsLaunch& L, uint32_t bx, uint32_t by,
         const uint32_t* da = P.dtab + a * P.ndw;
         K = compress(P, [&](int i) { return addmod4(ld_dw(R.in, g, i), gload32(da + i), P); }, &colour);
     });
+    const int jlo = j0 ? (int)j0 : 1, jhi = j0 ? (int)j0 : (int)L.n;
     if constexpr (cmod_m<MC>::value != 0) {
-        digit_row(L, R, M1{L.mods[L.m[1]].dtab}, K, colour, g, a, 1, T);
-        const MC Mc{L.mods[L.m[2]].dtab};
-        for (int j = 2; j <= (int)L.n; j++) digit_row(L, R, Mc, K, colour, g, a, j, T);
+        if (jlo == 1) digit_row(L, R, M1{L.mods[L.m[1]].dtab}, K, colour, g, a, 1, T);
+        if (jhi >= 2) {
+            const MC Mc{L.mods[L.m[2]].dtab};
+            for (int j = jlo < 2 ? 2 : jlo; j <= jhi; j++) digit_row(L, R, Mc, K, colour, g, a, j, T);
+        }
     } else {
-        for (int j = 1; j <= (int)L.n; j++) {
+        for (int j = jlo; j <= jhi; j++) {
             const ModInfo Mo = L.mods[L.m[j]];      // a copy in registers: through the reference every use is a load
             digit_row(L, R, Mo, K, colour, g, a, j, T);
         }

@@ -286,6 +286,21 @@ __global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_d
     }
 }
 
+// the same with one lane per ciphertext row: blockIdx.y = digit - 1 (gadgets over few elements)
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_digits_garble_wide(const DigitsLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    auto tiles_of = [&](uint32_t i) { return (uint32_t)(((uint64_t)L.n_elem * L.res[i].p + kThreads - 1) / kThreads); };
+    uint32_t total = 0;
+    for (uint32_t i = 0; i < L.nres; i++) total += tiles_of(i);
+    uint32_t res = 0, base = 0, next = tiles_of(0);
+    for (uint32_t t = blockIdx.x; t < total; t += gridDim.x) {
+        while (t >= next) { res++; base = next; next += tiles_of(res); }
+        digits_garble_body<MC, M1>(L, t - base, __builtin_amdgcn_readfirstlane(res), threadIdx.x, T, blockIdx.y + 1);
+    }
+}
+
 int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
     if (L.n < 1 || L.n > (uint32_t)kMaxChain || L.nres < 1 || L.nres > 16) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
@@ -308,11 +323,20 @@ int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
         for (uint32_t j = 1; j <= L.n; j++) bytes += (double)L.n_elem * (c->mods[R.p].lam + (1.0 + R.p) * c->mods[L.m[j]].lam);
     }
     if (tiles > 0x7fffffffull) return DASH_ESIZE;
+    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
+    const ModInfo &M1 = c->mods[L.m[1]], &Mc = c->mods[L.m[L.n >= 2 ? 2 : 1]];
+    if ((uint64_t)units <= c->few_rows_max) {      // few rows: a lane per row, so that a lane's chain is one hash
+        dim3 grid(grid_x_for(tiles, (int)L.n), L.n);
+        ProfScope ps(c->prof, DASH_PROF_GARBLE_DIGITS, s, units, bytes);
+        if (uniform && is(Mc, 96, 20) && is(M1, 26, 28)) hipLaunchKernelGGL((k_digits_garble_wide<CMod<96, 20>, CMod<26, 28>>), grid, dim3(kThreads), 0, s, L);
+        else if (uniform && is(Mc, 204, 17) && is(M1, 46, 24)) hipLaunchKernelGGL((k_digits_garble_wide<CMod<204, 17>, CMod<46, 24>>), grid, dim3(kThreads), 0, s, L);
+        else hipLaunchKernelGGL((k_digits_garble_wide<ModInfo, ModInfo>), grid, dim3(kThreads), 0, s, L);
+        DASH_HIP(hipGetLastError());
+        return DASH_OK;
+    }
     const bool banked = (uint64_t)(units / L.n) >= c->digits_banked_min_lanes;
     dim3 grid(gate_grid_x_for(tiles, 1, banked));
     const dim3 block(banked ? kBigThreads : kThreads);
-    auto is = [](const ModInfo& M, uint32_t m, uint32_t lam) { return M.m == m && M.lam == lam; };
-    const ModInfo &M1 = c->mods[L.m[1]], &Mc = c->mods[L.m[L.n >= 2 ? 2 : 1]];
     ProfScope ps(c->prof, DASH_PROF_GARBLE_DIGITS, s, units, bytes);
     if (uniform && is(Mc, 96, 20) && is(M1, 26, 28)) {
         if (banked) hipLaunchKernelGGL((k_digits_garble<CMod<96, 20>, CMod<26, 28>, true>), grid, block, 0, s, L);
@@ -364,7 +388,9 @@ int launch_garble(const dash_ctx* c, GateLaunch& L, int njobs, hipStream_t s) {
         grid = dim3((uint32_t)(nb < cap ? nb : cap));
     }
     ProfScope ps(c->prof, DASH_PROF_GARBLE, s, units, bytes);
-    hipLaunchKernelGGL(banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki], grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
+    GateKernel k = banked ? kGarbleKernelsBanked[ki] : kGarbleKernels[ki];
+    if (ki == 0 && !banked && (uint64_t)units <= c->few_rows_max) k = k_proj_garble<PerJobMod, false>;      // few rows: see garble_body
+    hipLaunchKernelGGL(k, grid, dim3(banked ? kBigThreads : kThreads), 0, s, L);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }

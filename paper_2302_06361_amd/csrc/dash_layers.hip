@@ -155,21 +155,32 @@ GateJob phi_job(int p, int q, LView in, const uint8_t* phi, uint32_t slot, LView
 // first segment inside the layer table (already offset for the element count), offsets per slot follow
 // the slot order.  On return w.bit holds [X >= P/2] (negate = 0) or its complement.
 // up (optional): a second output wire, bit + up_coef * up_one.
+// garbler: fresh zero labels of every gate output of a sign gadget
+void sign_draws(const dash_ctx* c, DrawBatcher& db, int first_res, uint32_t slot_base, const SignWires& w) {
+    const int k = c->k, n = c->n;
+    for (int i = first_res; i < k; i++)
+        for (int j = 1; j <= n; j++) db.add(c->mj[j], DOM_GATE, slot_base + i * n + (j - 1), w.A[i][j]);
+    for (int j = n; j >= 2; j--) db.add(c->mj[j - 1], DOM_GATE, slot_base + k * n + (j - 2), w.C[j - 1]);
+    db.add(2, DOM_GATE, slot_base + k * n + n - 1, w.bit);
+}
+
+// Launches of few rows are bound by the time of one lane, not by the number of lanes: gates of different output moduli
+// then share a launch (the instantiation that picks the modulus' compile-time description per job).
+bool few_rows(const dash_ctx* c, uint64_t rows) { return rows <= c->few_rows_max; }
+
 int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
               int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s, const LView* up = nullptr,
-              const LView* up_one = nullptr, uint32_t up_coef = 0, CastLaunch* pre = nullptr, int pre_jobs = 0) {
+              const LView* up_one = nullptr, uint32_t up_coef = 0, CastLaunch* pre = nullptr, int pre_jobs = 0, bool drawn = false) {
     // pre (evaluator of the scaling gadget): the cast-and-halve step that produces x[first_res..]; it runs in the
     // launch of the digit gates when they are fused, else in a launch of its own before them
+    // drawn (garbler): the caller has drawn the zero labels (sign_draws) in a launch of its own
     const int k = c->k, n = c->n;
     size_t off[DASH_MAX_PRIMES * DASH_MAX_DIGITS + DASH_MAX_DIGITS], cum = 0;
     for (int sl = 0; sl < sign_nslots(c); sl++) { off[sl] = cum * E; cum += sign_slot_bytes(c, sl, first_res); }
 
-    if (garble) {   // fresh zero labels of every gate output
+    if (garble && !drawn) {
         DrawBatcher db(c, E, layer, elem_base, s);
-        for (int i = first_res; i < k; i++)
-            for (int j = 1; j <= n; j++) db.add(c->mj[j], DOM_GATE, slot_base + i * n + (j - 1), w.A[i][j]);
-        for (int j = n; j >= 2; j--) db.add(c->mj[j - 1], DOM_GATE, slot_base + k * n + (j - 2), w.C[j - 1]);
-        db.add(2, DOM_GATE, slot_base + k * n + n - 1, w.bit);
+        sign_draws(c, db, first_res, slot_base, w);
         db.flush();
         if (db.status) return db.status;
     }
@@ -239,6 +250,9 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         }
         ab.flush();
         if (ab.status) return ab.status;
+        uint64_t chain_rows = 0;
+        for (int j = 1; j <= n; j++) chain_rows += (uint64_t)E * c->mj[j];
+        gb.mixed = few_rows(c, chain_rows);
         for (int j = n; j >= 1; j--) chain_gate(j);
         gb.flush();
         return gb.status;
@@ -336,7 +350,9 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         }
         db.flush();
         if (db.status) return db.status;
-        GateBatcher gb(c, true, E, layer, eb, s), gb2(c, true, E, layer, eb, s, true);   // the two-row tables share launches
+        uint64_t hg_rows = 0;
+        for (int i = 0; i < k; i++) hg_rows += (uint64_t)E * (c->prime[i] + 4);
+        GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, hg_rows)), gb2(c, true, E, layer, eb, s, true);   // the two-row tables share launches
         for (int i = 0; i < k; i++) {
             int p = c->prime[i];
             GateJob J = phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
@@ -460,8 +476,9 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         auto addc_of = [&](uint32_t p) { return rep == 0 ? 0u : (uint32_t)((p - quarter % p) % p); };
         size_t cum = 0;
         if (garble) {
-            DrawBatcher db(c, E, layer, eb, s);
+            DrawBatcher db(c, E, layer, eb, s);      // with the zero labels of this repetition's sign gadget
             for (int i = 1; i < k; i++) db.add(c->prime[i], DOM_GATE, sb + (i - 1), pl.cast[i]);
+            sign_draws(c, db, 1, sb + (k - 1), pl.w);
             db.flush();
             if (db.status) return db.status;
             GateBatcher gb(c, true, E, layer, eb, s, true);
@@ -504,7 +521,7 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         if (garble) {
             const uint32_t upc = (c0 + 1) % 2;
             const int st = sign_core(c, true, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
-                                     last ? nullptr : &one[0], upc);
+                                     last ? nullptr : &one[0], upc, nullptr, 0, true);
             if (st) return st;
         }
         if (last) {

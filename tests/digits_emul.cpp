@@ -3,7 +3,7 @@
 // of libdash.
 //
 // usage: digits_emul <in.bin> <out.bin>
-//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate); uint64 elem_base;
+//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate, 3 garble with a lane per row); uint64 elem_base;
 //        int32 m[n] (digit 1..n); int32 p[nres];
 //        for t < nres: u8 label_t[n_elem][lam(p_t)]            (active labels; garble: zero labels)
 //      evaluate:
@@ -37,7 +37,8 @@ int main(int argc, char** argv) {
     int32_t hd[8];
     uint64_t elem_base;
     if (fread(hd, 4, 8, f) != 8 || fread(&elem_base, 8, 1, f) != 1) return 2;
-    const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6], garble = hd[7] == 1;
+    const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6], garble = hd[7] == 1 || hd[7] == 3;
+    const bool wide_rows = hd[7] == 3;      // garble with one lane per ciphertext row
     const bool wide = hd[7] == 2;      // evaluate with one lane per digit gate
     const uint32_t E = (uint32_t)hd[1];
     if (n < 1 || n > kMaxChain || nres < 1 || nres > 16) return 2;
@@ -120,11 +121,12 @@ int main(int argc, char** argv) {
         for (uint32_t by = 0; by < (uint32_t)nres; by++) {
             const uint32_t tiles = (uint32_t)(((uint64_t)E * p[by] + kThreads - 1) / kThreads);
             for (uint32_t bx = 0; bx < tiles; bx++)
-                for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
-                    if (variant == 1) digits_garble_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T);
-                    else if (variant == 2) digits_garble_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T);
-                    else digits_garble_body<ModInfo, ModInfo>(L, bx, by, tx, T);
-                }
+                for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++)
+                    for (uint32_t j0 = wide_rows ? 1 : 0; j0 <= (wide_rows ? (uint32_t)n : 0u); j0++) {
+                        if (variant == 1) digits_garble_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T, j0);
+                        else if (variant == 2) digits_garble_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T, j0);
+                        else digits_garble_body<ModInfo, ModInfo>(L, bx, by, tx, T, j0);
+                    }
         }
         f = fopen(argv[2], "wb");
         if (!f) return 2;

@@ -1,4 +1,4 @@
-// Host emulation of ONE evaluator launch that mixes output moduli: 16 jobs, one per modulus with a compile-time
+// Host emulation of ONE evaluator launch (and, below, one garbler launch) that mixes output moduli: 16 jobs, one per modulus with a compile-time
 // description, run through eval_body<ModInfo> (the instantiation that picks a description per job) lane by lane over
 // exactly-sized host buffers under the address sanitizer: every table-row address and every label store must stay
 // inside its job's buffers.  The results are compared with the single-modulus instantiations on the same inputs.
@@ -70,6 +70,49 @@ int main(int argc, char** argv) {
                 });
         if (out[j] != out_typed[j]) { fprintf(stderr, "job %d (q = %d): mixed launch differs\n", j, hot[j]); return 1; }
         for (uint8_t b : out[j]) if (b >= hot[j]) { fprintf(stderr, "job %d: digit out of range\n", j); return 1; }
+    }
+    // The garbler's launch for few rows (garble_body<PerJobMod>): the same 16 jobs garbled in one pass, every table byte equal to
+    // the single-modulus instantiation's and to the run-time-constant one's.
+    std::vector<std::vector<uint32_t>> dtab(256);
+    for (int j = 0; j < 16; j++) {
+        ModInfo& M = mods[hot[j]];
+        dtab[hot[j]].assign((size_t)M.m * M.ndw, 0);
+        std::vector<uint32_t> delta(M.lam);
+        for (uint32_t d = 0; d < M.lam; d++) delta[d] = d == 0 ? 1u : rnd() % M.m;
+        for (uint32_t a = 0; a < M.m; a++)
+            for (uint32_t d = 0; d < M.lam; d++) dtab[hot[j]][(size_t)a * M.ndw + d / 4] |= ((a * delta[d]) % M.m) << (8 * (d % 4));
+        M.dtab = dtab[hot[j]].data();
+    }
+    std::vector<std::vector<uint8_t>> phi(16), out0(16), tab_any(16), tab_typed(16), tab_run(16);
+    for (int j = 0; j < 16; j++) {
+        GateJob& J = G.jobs[j];
+        const ModInfo& Mq = mods[J.q];
+        phi[j].resize((size_t)n * J.p);
+        for (auto& v : phi[j]) v = (uint8_t)(rnd() % J.q);
+        out0[j].assign((size_t)Mq.nchunk * n * 16, 0);
+        for (uint32_t e = 0; e < n; e++)
+            for (uint32_t d = 0; d < Mq.lam; d++) out0[j][((size_t)(d / 16) * n + e) * 16 + d % 16] = (uint8_t)(rnd() % J.q);
+        J.phi = phi[j].data(); J.phi_stride = J.p;
+        J.out = LView{out0[j].data(), (int64_t)16 * n, 16u};
+        tab_any[j].assign(table[j].size(), 0xEE);
+        tab_typed[j].assign(table[j].size(), 0xDD);
+        tab_run[j].assign(table[j].size(), 0xCC);
+    }
+    for (int j = 0; j < 16; j++) {
+        const uint32_t gb = (uint32_t)(((uint64_t)n * G.jobs[j].p + kThreads - 1) / kThreads);
+        for (uint32_t bx = 0; bx < gb; bx++)
+            for (uint32_t tx = 0; tx < kThreads; tx++) {
+                DirectSink sink;
+                G.jobs[j].table = tab_any[j].data();
+                garble_body<PerJobMod>(G, bx, j, tx, HostTab(), sink);
+                G.jobs[j].table = tab_run[j].data();
+                garble_body<ModInfo>(G, bx, j, tx, HostTab(), sink);
+                G.jobs[j].table = tab_typed[j].data();
+                with_mod(mods[hot[j]], [&](auto Qd) {
+                    if constexpr (cmod_m<decltype(Qd)>::value != 0) garble_body<decltype(Qd)>(G, bx, j, tx, HostTab(), sink);
+                });
+            }
+        if (tab_any[j] != tab_typed[j] || tab_any[j] != tab_run[j]) { fprintf(stderr, "job %d (q = %d): garbled tables differ\n", j, hot[j]); return 1; }
     }
     printf("ok\n");
     return 0;

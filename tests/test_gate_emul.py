@@ -190,7 +190,7 @@ def test_digit_gates_one_per_lane_under_sanitizers(digits_emul, tmp_path):
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
 
-def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):
+def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40, wide=False):
     """the garbler's side of the same gates: rows[colour(l0 + a R_p)] = out0 + phi_j(a) R_{m_j} + H(l0 + a R_p), every
     table segment against the oracle's projection gate with the same zero labels and function table"""
     orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
@@ -200,7 +200,7 @@ def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0,
     phis = [np.stack([g.integers(0, mj, p).astype(np.uint8) for mj in m]) for p in primes]
     want = [[orc.proj_garble(p, mj, in0[t], phis[t][j], layer, slot0 + t * n + j, elem_base) for j, mj in enumerate(m)]
             for t, p in enumerate(primes)]
-    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 1, elem_base)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 3 if wide else 1, elem_base)
     blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % len(primes), *primes)
     blob += b"".join(a.tobytes() for a in in0)
     blob += b"".join(orc.delta(p).tobytes() for p in primes) + b"".join(orc.delta(mj).tobytes() for mj in m)
@@ -227,6 +227,14 @@ def test_digit_row_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits_garble(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
     run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5)
+
+
+def test_digit_rows_one_per_lane_under_sanitizers(digits_emul, tmp_path):
+    """the garbler's form for gadgets over few elements: a lane per ciphertext row (element, value, digit)"""
+    run_digits_garble(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 150, wide=True)
+    run_digits_garble(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 130, wide=True)
+    run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1, wide=True)
+    run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
 
 # ---- one evaluator launch that mixes output moduli -------------------------------------------------

@@ -211,7 +211,7 @@ def test_tables_pack_needs_rows_below_128_bits():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_aes_forms_against_the_standard_and_the_oracle(variant):
     """Every form of AES-128 the library holds (4 KB tables, bank-replicated tables, bit planes) on the GPU: FIPS-197
     Appendix B and C.1 vectors, random blocks against the oracle's AES, repeated application, the size rule of the

@@ -101,6 +101,7 @@ def test_activation_bank_replicated_tables_forced(monkeypatch, k):
     monkeypatch.setenv("DASH_BANKED_MIN_LANES", "1")
     monkeypatch.setenv("DASH_DIGITS_BANKED_MIN_LANES", "1")
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", "0")       # the evaluator's digit gates fused per residue, as on wide layers
+    monkeypatch.setenv("DASH_GARBLE_FEW_ROWS", "0")      # and the garbler's launches in the forms for many rows
     P = int(np.prod(workloads.PRIMES[:k]))
     g = np.random.default_rng(100 + k)
     X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], g.integers(0, P, 1296)])     # 1301 values: ragged tiles of 1024 lanes
@@ -111,10 +112,12 @@ def test_activation_bank_replicated_tables_forced(monkeypatch, k):
 @pytest.mark.parametrize("wide", ["0", "1000000000000"])
 def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide):
     """The evaluator runs the digit gates of a sign gadget one lane per (element, residue, digit) for gadgets over few
-    elements and one lane per (element, residue) with n hashes, fused with the scaling gadget's cast step, for the rest:
-    both forms forced on the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the
-    oracle."""
+    elements and one lane per (element, residue) with n hashes, fused with the scaling gadget's cast step, for the rest;
+    the garbler likewise has a form of its launches for few rows (a lane per row of the digit gates; gates of different
+    output moduli in one launch, each job with its modulus' compile-time code) and one for many: both forms forced on
+    the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the oracle."""
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", wide)
+    monkeypatch.setenv("DASH_GARBLE_FEW_ROWS", wide)
     for k in (8, 12):
         P = int(np.prod(workloads.PRIMES[:k]))
         X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], np.random.default_rng(300 + k).integers(0, P, 296)])
