@@ -7,6 +7,7 @@
 #include <mutex>
 #include <new>
 
+#include "dash_bodies.h"
 #include "dash_hostconst.h"
 #include "dash_internal.h"
 
@@ -64,19 +65,30 @@ __global__ void k_delta_tab(ModInfo M, uint8_t* delta, uint32_t* dtab) {
 }
 __global__ void k_fix_colour(uint8_t* delta) { delta[0] = 1; }
 
-__global__ __launch_bounds__(kThreads) void k_encode(const ModInfo* mods, uint32_t m, const int64_t* values, uint32_t n,
-                                                     LView zero, LView out) {
-    uint32_t e = blockIdx.x * kThreads + threadIdx.x;
-    if (e >= n) return;
-    const ModInfo M = mods[m];
-    int64_t v = values[e] % (int64_t)m;
+struct EncodeArgs {
+    const ModInfo* mods;
+    uint32_t n;
+    uint32_t prime[DASH_MAX_PRIMES];      // 0: residue absent from the bundles
+    LView zero[DASH_MAX_PRIMES], out[DASH_MAX_PRIMES];
+    const int64_t* values;
+};
+
+// En: one lane per (value, 16-digit chunk) of one residue (blockIdx.y): active = zero + (value mod p) R_p
+__global__ __launch_bounds__(kThreads) void k_encode(const EncodeArgs A) {
+    const uint32_t m = A.prime[blockIdx.y];
+    if (m == 0) return;
+    const ModInfo M = A.mods[m];
+    const uint64_t t = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t ch = (uint32_t)(t / A.n), e = (uint32_t)(t - (uint64_t)ch * A.n);      // a wave's lanes: consecutive values of one chunk
+    if (ch >= M.nchunk) return;
+    int64_t v = A.values[e] % (int64_t)m;
     if (v < 0) v += m;
     const uint32_t* dv = M.dtab + (size_t)v * M.ndw;
-    for (uint32_t i = 0; i < M.nchunk * 4; i++) {
-        uint32_t z = *(const uint32_t*)(zero.p + (int64_t)(i >> 2) * zero.cs + (uint64_t)e * 16 + (i & 3) * 4);
-        uint32_t w = i < M.ndw ? addmod4(z, dv[i], M) : 0;
-        *(uint32_t*)(out.p + (int64_t)(i >> 2) * out.cs + (uint64_t)e * 16 + (i & 3) * 4) = w;
-    }
+    const Dw4 z = ld_chunk(A.zero[blockIdx.y], e, (int)ch);
+    Dw4 w;
+#pragma unroll
+    for (uint32_t q = 0; q < 4; q++) w.w[q] = ch * 4 + q < M.ndw ? addmod4(z.w[q], dv[ch * 4 + q], M) : 0;
+    st_chunk(A.out[blockIdx.y], e, (int)ch, w);
 }
 
 struct DecodeArgs {
@@ -498,11 +510,18 @@ int dash_encode(dash_ctx* c, const int64_t* values, int64_t n, const dash_labels
         if (st) return st;
     }
     if (n == 0) return DASH_OK;
+    EncodeArgs A;
+    memset(&A, 0, sizeof(A));
+    A.mods = c->d_mods; A.n = (uint32_t)n; A.values = values;
+    uint32_t nchunk = 0;
     for (int i = 0; i < c->k; i++) {
         if (!zero->data[i] && !out->data[i]) continue;
-        hipLaunchKernelGGL(k_encode, dim3((uint32_t)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream,
-                           c->d_mods, (uint32_t)c->prime[i], values, (uint32_t)n, view_of(zero, i), view_of(out, i));
+        A.prime[i] = (uint32_t)c->prime[i]; A.zero[i] = view_of(zero, i); A.out[i] = view_of(out, i);
+        nchunk = std::max(nchunk, c->mods[c->prime[i]].nchunk);
     }
+    if (nchunk == 0) return DASH_OK;
+    hipLaunchKernelGGL(k_encode, dim3((uint32_t)(((uint64_t)n * nchunk + kThreads - 1) / kThreads), (uint32_t)c->k), dim3(kThreads), 0,
+                       (hipStream_t)stream, A);
     DASH_HIP(hipGetLastError());
     return DASH_OK;
 }
