@@ -28,7 +28,8 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
 ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 PMC_FILE = os.path.join(ROOT, "profiles", "gate_kernels_lenet_b16_pmc_per_unit.txt")
-GATE_SOURCES = ["dash_core.h", "dash_bodies.h", "dash_tabs.h", "dash_launch.h", "dash_gates.hip", "dash_gates_eval.hip", "dash_layers.hip"]
+GATE_SOURCES = ["dash_core.h", "dash_bodies.h", "dash_tabs.h", "dash_launch.h", "dash_gates.hip", "dash_gates_digits.hip", "dash_gates_eval.hip",
+                "dash_gates_digits_eval.hip", "dash_gates_cast.hip", "dash_layers.hip"]
 
 
 def gate_source_hash():

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 SO = os.path.join(HERE, "libdash.so")
-SOURCES = ["dash_ctx.hip", "dash_gates.hip", "dash_gates_eval.hip", "dash_layers.hip", "dash_linear.hip", "dash_gemm.hip", "dash_aesprof.hip"]
+SOURCES = ["dash_ctx.hip", "dash_gates.hip", "dash_gates_digits.hip", "dash_gates_eval.hip", "dash_gates_digits_eval.hip", "dash_gates_cast.hip", "dash_layers.hip", "dash_linear.hip", "dash_gemm.hip", "dash_aesprof.hip"]
 HEADERS = ["dash_core.h", "dash_launch.h", "dash_bodies.h", "dash_hostconst.h", "dash_internal.h", "dash_tabs.h", "dash_aes_sliced.h", "dash_sbox_circuit.h", os.path.join("..", "..", "include", "dash.h"),
            os.path.join("..", "..", "include", "dash_profile.h")]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",

@@ -494,7 +494,7 @@ DASH_HD uint32_t mod_u128(const U128& h, const MI& M) {
 // the default digit sets, with their label lengths under the ceil rule.
 #define DASH_HOT_MODS(X) \
     X(2, 128) X(3, 81) X(5, 56) X(7, 46) X(11, 38) X(13, 35) X(17, 32) X(19, 31) X(23, 29) X(29, 27) X(31, 26) X(37, 25) \
-    X(26, 28) X(96, 20) X(46, 24) X(204, 17)
+    X(26, 28) X(96, 20) X(46, 24) X(204, 17) X(10, 39) X(91, 20) X(22, 29) X(90, 20)
 
 // f(description of M): compile-time description for the hot moduli, run-time otherwise
 template <class F>
@@ -519,6 +519,29 @@ DASH_HD int hot_mod_index(const ModInfo& M) {
     DASH_HOT_MODS(DASH_MOD_IDX)
 #undef DASH_MOD_IDX
     return 0;
+}
+
+// Digit sets (d_1; d, .., d) of the sign gadget whose kernels exist with compile-time moduli, as (m_c, lambda, m_1, lambda):
+// m_1 = d_1 the accumulation modulus of digit 1, m_c = k d that of the others.  The default sets of the 8-, 12-, 7- and
+// 9-prime bases (the bases of the paper's models), under the ceil rule.
+#define DASH_DIGIT_SETS(X) X(96, 20, 26, 28) X(204, 17, 46, 24) X(91, 20, 10, 39) X(90, 20, 22, 29)
+template <class MC_, class M1_> struct DigitSet { typedef MC_ MC; typedef M1_ M1; };
+// index (1..) of the set with these two moduli, 0 if none
+DASH_HD int digit_set_index(const ModInfo& Mc, const ModInfo& M1) {
+    int idx = 0;
+#define DASH_SET_IDX(MC, LC, M1_, L1) idx++; if (Mc.m == MC && Mc.lam == LC && M1.m == M1_ && M1.lam == L1) return idx;
+    DASH_DIGIT_SETS(DASH_SET_IDX)
+#undef DASH_SET_IDX
+    return 0;
+}
+// f(DigitSet of compile-time descriptions) for index 1.., f(DigitSet<ModInfo, ModInfo>) for 0
+template <class F>
+void with_digit_set(int index, F&& f) {
+    int idx = 0;
+#define DASH_SET_CASE(MC, LC, M1_, L1) if (++idx == index) { f(DigitSet<CMod<MC, LC>, CMod<M1_, L1>>{}); return; }
+    DASH_DIGIT_SETS(DASH_SET_CASE)
+#undef DASH_SET_CASE
+    f(DigitSet<ModInfo, ModInfo>{});
 }
 
 }  // namespace dash

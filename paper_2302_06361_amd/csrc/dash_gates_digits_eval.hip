@@ -1,0 +1,112 @@
+// dash_gates_digits_eval.hip -- the evaluator's kernels for the sign gadget (Appendix, Approximated Garbled Sign and
+// Garbled Mixed-Radix Addition).
+//
+//   k_digits_eval : the k n digit gates of a sign gadget, one lane per (element, residue): one compress, n gates
+//   k_digits_eval_wide : the same gates one per lane, for gadgets over few elements
+//   k_chain_eval  : the n dependent gates of the mixed-radix addition of a sign gadget, one lane per element
+//
+// Jobs, table layouts and compile-time moduli as in dash_gates.hip.
+#include "dash_tabs.h"
+
+namespace dash {
+
+// ------------------------------------------------------------------- digit gates of the sign gadget, evaluator
+// One launch for the k n digit gates of a sign gadget (four launches of k_proj_eval before), lane = (element,
+// residue): the label is loaded and compressed once for its n gates.
+template <class MC, class M1, bool Banked>
+__global__ __launch_bounds__(gate_tab<Banked>::threads, Banked ? 8 : 1) void k_digits_eval(const DigitsLaunch L) {
+    constexpr int kGateTiles = gate_tab<Banked>::threads / kThreads;
+    __shared__ uint32_t tt[gate_tab<Banked>::words];
+    const auto T = gate_tab<Banked>::load(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    const uint32_t sub = threadIdx.x / kThreads, tx = threadIdx.x % kThreads;
+    for (uint32_t tile = blockIdx.x * kGateTiles + sub; tile < tiles; tile += gridDim.x * kGateTiles)
+        digits_eval_body<MC, M1>(L, tile, blockIdx.y, tx, T);
+}
+
+// one lane per (element, residue, digit): blockIdx.y = residue, blockIdx.z = digit - 1
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_digits_eval_wide(const DigitsLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x)
+        digits_eval_wide_body<MC, M1>(L, tile, blockIdx.y, blockIdx.z + 1, threadIdx.x, T);
+}
+
+int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
+    bool uniform = false;
+    double bytes = 0;
+    const int st = check_digits(c, L, &uniform, &bytes);
+    if (st) return st;
+    if (L.n_elem == 0) return DASH_OK;
+    const int typed = typed_digits(c, L, uniform);
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.nres * L.n, bytes);
+    if ((uint64_t)L.n_elem * L.nres * L.n <= c->wide_max_lanes) {
+        // few elements: the launch does not fill the chip, its time is the chain of hashes of one lane
+        dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)(L.nres * L.n)), L.nres, L.n);
+        with_digit_set(typed, [&](auto ds) {
+            typedef decltype(ds) DS;
+            hipLaunchKernelGGL((k_digits_eval_wide<typename DS::MC, typename DS::M1>), grid, dim3(kThreads), 0, s, L);
+        });
+        DASH_HIP(hipGetLastError());
+        return DASH_OK;
+    }
+    // (by lanes, not by hashes: with n hashes per lane the 64 KB tables were still measured slower below this size)
+    const bool banked = (uint64_t)L.n_elem * L.nres >= c->banked_min_lanes;
+    dim3 grid(gate_grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)L.nres, banked), L.nres);
+    const dim3 block(banked ? kBigThreads : kThreads);
+    with_digit_set(typed, [&](auto ds) {
+        typedef decltype(ds) DS;
+        if (banked) hipLaunchKernelGGL((k_digits_eval<typename DS::MC, typename DS::M1, true>), grid, block, 0, s, L);
+        else hipLaunchKernelGGL((k_digits_eval<typename DS::MC, typename DS::M1, false>), grid, block, 0, s, L);
+    });
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+// ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
+// One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
+// whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
+// other set takes the body with run-time constants.
+template <class MC, class M1>
+__global__ __launch_bounds__(kThreads) void k_chain_eval(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1>(L, tile, threadIdx.x, T);
+}
+__global__ __launch_bounds__(kThreads) void k_chain_eval_generic(const ChainLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_generic_body(L, tile, threadIdx.x, T);
+}
+
+int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
+    if (L.n < 2 || L.n > (uint32_t)kMaxChain) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    bool uniform = true;
+    double bytes = 0;
+    for (uint32_t j = 1; j <= L.n; j++) {
+        if (L.m[j] < 2 || L.m[j] > 255 || !L.table[j] || !L.sum[j].p || (j < L.n && !L.carry[j].p)) return DASH_EINVAL;
+        if (j >= 3 && L.m[j] != L.m[2]) uniform = false;
+        bytes += (double)L.n_elem * (c->mods[L.m[j]].lam + (j >= 2 ? c->mods[L.m[j - 1]].lam : 128));
+    }
+    if ((uint64_t)L.n_elem * 255 >= (1ull << 32)) return DASH_ESIZE;
+    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
+    const bool bit128 = c->mods[2].lam == 128;      // the fused bodies write the 128 digits of the sign wire
+    const int typed = bit128 && uniform ? digit_set_index(c->mods[L.m[2]], c->mods[L.m[1]]) : 0;
+    with_digit_set(typed, [&](auto ds) {
+        typedef decltype(ds) DS;
+        if constexpr (cmod_m<typename DS::MC>::value != 0) hipLaunchKernelGGL((k_chain_eval<typename DS::MC, typename DS::M1>), grid, dim3(kThreads), 0, s, L);
+        else hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
+    });
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
+}  // namespace dash

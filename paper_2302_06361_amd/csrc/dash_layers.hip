@@ -88,8 +88,9 @@ void plan_sign(const dash_ctx* c, Arena& ar, int64_t E, int first_res, SignWires
 // Collects independent gate jobs and launches them grouped by output modulus (a launch runs one
 // instantiation of the gate kernel, chosen by the output modulus), up to kMaxJobs per launch.
 // mixed = true puts jobs of any output moduli into the same launch (the instantiation with run-time
-// constants): for the many small batches whose output moduli all differ (one cast or half gate per
-// prime), where a launch per modulus would cost more than the slower digit extraction.
+// constants; garbling launches of few rows: the one that picks compile-time constants per job): for the
+// many small batches whose output moduli all differ (one cast or half gate per prime), where a launch
+// per modulus would cost more than the slower digit extraction, and for gadgets of few rows altogether.
 struct GateBatcher {
     static constexpr int kSlots = 4;
     const dash_ctx* c; bool garble; hipStream_t s; bool mixed = false;

@@ -101,4 +101,27 @@ inline uint32_t common_q(const GateLaunch& L, int njobs) {
     return L.jobs[0].q;
 }
 
+// argument checks shared by the evaluator's digit-gate launchers; sets the launch's key and table pointers
+inline int check_digits(const dash_ctx* c, DigitsLaunch& L, bool* uniform, double* bytes) {
+    if (L.n < 1 || L.n > (uint32_t)kMaxChain || L.nres < 1 || L.nres > 16) return DASH_EINVAL;
+    if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    *uniform = L.n >= 2;
+    for (uint32_t j = 1; j <= L.n; j++) {
+        if (L.m[j] < 2 || L.m[j] > 255 || !c->mods[L.m[j]].dtab) return DASH_EINVAL;
+        if (j >= 3 && L.m[j] != L.m[2]) *uniform = false;
+    }
+    for (uint32_t i = 0; i < L.nres; i++) {
+        const DigitsRes& R = L.res[i];
+        if (R.p < 2 || R.p > 255 || !c->mods[R.p].dtab || !R.in.p || !R.table || !R.out) return DASH_EINVAL;
+        for (uint32_t j = 1; j <= L.n; j++) *bytes += (double)L.n_elem * (c->mods[R.p].lam + 2.0 * c->mods[L.m[j]].lam);
+    }
+    return DASH_OK;
+}
+
+// index of the digit set's kernels with compile-time moduli (digit_set_index), 0 = none
+inline int typed_digits(const dash_ctx* c, const DigitsLaunch& L, bool uniform) {
+    return uniform ? digit_set_index(c->mods[L.m[L.n >= 2 ? 2 : 1]], c->mods[L.m[1]]) : 0;
+}
+
 }  // namespace dash

@@ -83,9 +83,11 @@ int main(int argc, char** argv) {
     const uint32_t tiles = (E + kThreads - 1) / kThreads;
     for (uint32_t bx = 0; bx < tiles; bx++)
         for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
-            if (variant == 1) chain_eval_body<CMod<96, 20>, CMod<26, 28>>(L, bx, tx, T);
-            else if (variant == 2) chain_eval_body<CMod<204, 17>, CMod<46, 24>>(L, bx, tx, T);
-            else chain_eval_generic_body(L, bx, tx, T);
+            with_digit_set(variant, [&](auto ds) {
+                typedef decltype(ds) DS;
+                if constexpr (cmod_m<typename DS::MC>::value != 0) chain_eval_body<typename DS::MC, typename DS::M1>(L, bx, tx, T);
+                else chain_eval_generic_body(L, bx, tx, T);
+            });
         }
     std::vector<uint8_t> out((size_t)E * lam2);
     for (uint32_t e = 0; e < E; e++)

@@ -3,7 +3,7 @@
 // of libdash.
 //
 // usage: digits_emul <in.bin> <out.bin>
-//   in : int32 n n_elem rule layer variant(0 run-time constants, 1 <96,26>, 2 <204,46>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate, 3 garble with a lane per row); uint64 elem_base;
+//   in : int32 n n_elem rule layer variant(0 run-time constants, else the index of the digit set's compile-time kernels: 1 <96,26>, 2 <204,46>, 3 <91,10>, 4 <90,22>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate, 3 garble with a lane per row); uint64 elem_base;
 //        int32 m[n] (digit 1..n); int32 p[nres];
 //        for t < nres: u8 label_t[n_elem][lam(p_t)]            (active labels; garble: zero labels)
 //      evaluate:
@@ -123,9 +123,10 @@ int main(int argc, char** argv) {
             for (uint32_t bx = 0; bx < tiles; bx++)
                 for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++)
                     for (uint32_t j0 = wide_rows ? 1 : 0; j0 <= (wide_rows ? (uint32_t)n : 0u); j0++) {
-                        if (variant == 1) digits_garble_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T, j0);
-                        else if (variant == 2) digits_garble_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T, j0);
-                        else digits_garble_body<ModInfo, ModInfo>(L, bx, by, tx, T, j0);
+                        with_digit_set(variant, [&](auto ds) {
+                            typedef decltype(ds) DS;
+                            digits_garble_body<typename DS::MC, typename DS::M1>(L, bx, by, tx, T, j0);
+                        });
                     }
         }
         f = fopen(argv[2], "wb");
@@ -140,15 +141,17 @@ int main(int argc, char** argv) {
             for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
                 if (wide) {      // one lane per digit gate (digit 0 and n + 1: lanes that must do nothing)
                     for (uint32_t j = 0; j <= (uint32_t)n + 1; j++) {
-                        if (variant == 1) digits_eval_wide_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, j, tx, T);
-                        else if (variant == 2) digits_eval_wide_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, j, tx, T);
-                        else digits_eval_wide_body<ModInfo, ModInfo>(L, bx, by, j, tx, T);
+                        with_digit_set(variant, [&](auto ds) {
+                            typedef decltype(ds) DS;
+                            digits_eval_wide_body<typename DS::MC, typename DS::M1>(L, bx, by, j, tx, T);
+                        });
                     }
                     continue;
                 }
-                if (variant == 1) digits_eval_body<CMod<96, 20>, CMod<26, 28>>(L, bx, by, tx, T);
-                else if (variant == 2) digits_eval_body<CMod<204, 17>, CMod<46, 24>>(L, bx, by, tx, T);
-                else digits_eval_body<ModInfo, ModInfo>(L, bx, by, tx, T);
+                with_digit_set(variant, [&](auto ds) {
+                    typedef decltype(ds) DS;
+                    digits_eval_body<typename DS::MC, typename DS::M1>(L, bx, by, tx, T);
+                });
             }
     f = fopen(argv[2], "wb");
     if (!f) return 2;

@@ -2,7 +2,7 @@
 // description, run through eval_body<ModInfo> (the instantiation that picks a description per job) lane by lane over
 // exactly-sized host buffers under the address sanitizer: every table-row address and every label store must stay
 // inside its job's buffers.  The results are compared with the single-modulus instantiations on the same inputs.
-// Test code, not part of libdash.   usage: mixed_emul <n_elem> <seed>
+// Test code, not part of libdash.   usage: mixed_emul <n_elem> <seed> <which list of 16 moduli: 0 or 1>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -24,16 +24,24 @@ static uint64_t rng_state;
 static uint32_t rnd() { rng_state = rng_state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(rng_state >> 33); }
 
 int main(int argc, char** argv) {
-    if (argc != 3) return 2;
+    if (argc != 4) return 2;
     const uint32_t n = (uint32_t)atoi(argv[1]);
     rng_state = (uint64_t)atoll(argv[2]);
     std::vector<ModInfo> mods(256);
     for (int m = 2; m < 256; m++) fill_modinfo(mods[m], m, 0);
+    // the default digit sets (d_1; d, .., d) of the 8-, 12-, 7- and 9-prime bases must find their kernels with compile-time
+    // moduli: accumulation moduli m_1 = d_1 and m_c = k d (Appendix, Approximated Garbled Sign)
+    static const int sets[4][3] = {{8, 26, 12}, {12, 46, 17}, {7, 10, 13}, {9, 22, 10}};
+    for (int i = 0; i < 4; i++)
+        if (digit_set_index(mods[sets[i][0] * sets[i][2]], mods[sets[i][1]]) != i + 1) { fprintf(stderr, "digit set %d has no compile-time kernels\n", i); return 1; }
     uint8_t S[256], fixed[16];
     make_sbox(S);
     make_ttab(S, TT);
     for (int i = 0; i < 16; i++) fixed[i] = (uint8_t)i;
-    static const int hot[16] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37, 26, 96, 46, 204};
+    // 20 moduli have compile-time descriptions, a launch takes 16 jobs: two lists
+    static const int hot0[16] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37, 26, 96, 46, 204};
+    static const int hot1[16] = {10, 91, 22, 90, 2, 3, 5, 7, 11, 13, 17, 19, 26, 96, 46, 204};
+    const int* hot = atoi(argv[3]) ? hot1 : hot0;
     GateLaunch G;
     memset(&G, 0, sizeof(G));
     expand_key(fixed, S, G.key.rk);

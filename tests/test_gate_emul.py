@@ -12,15 +12,27 @@ import workloads
 from oracle import capi
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-EXE = os.path.join(HERE, "gate_emul.bin")
 SEED = bytes(range(7, 23))
 
 
+EMULATIONS = ("gate_emul", "chain_emul", "digits_emul", "mixed_emul", "cast_emul", "aes_sliced_emul")
+
+
 @pytest.fixture(scope="module")
-def emul():
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", EXE, os.path.join(HERE, "gate_emul.cpp")])
-    return EXE
+def built():
+    """all emulation programs, compiled side by side (most of this module's time is their compilation)"""
+    procs = [(name, subprocess.Popen(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                                      "-o", os.path.join(HERE, name + ".bin"), os.path.join(HERE, name + ".cpp")],
+                                     stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)) for name in EMULATIONS]
+    for name, pr in procs:
+        out, _ = pr.communicate()
+        assert pr.returncode == 0, (name, out[-3000:])
+    return {name: os.path.join(HERE, name + ".bin") for name in EMULATIONS}
+
+
+@pytest.fixture(scope="module")
+def emul(built):
+    return built["gate_emul"]
 
 
 def run_case(emul, tmp_path, p, q, n, rule=0, shared=False, elem_base=2 ** 33 + 11, layer=9, slot=3):
@@ -62,14 +74,11 @@ def test_gate_bodies_sizes_and_rules(emul, tmp_path):
 
 
 # ---- the evaluator's fused carry chain ------------------------------------------------------------
-CHAIN_EXE = os.path.join(HERE, "chain_emul.bin")
 
 
 @pytest.fixture(scope="module")
-def chain_emul():
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", CHAIN_EXE, os.path.join(HERE, "chain_emul.cpp")])
-    return CHAIN_EXE
+def chain_emul(built):
+    return built["chain_emul"]
 
 
 def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70, lam2=0):
@@ -117,6 +126,8 @@ def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
     run_chain(chain_emul, tmp_path, [26] + [96] * 6, 0, 70)
     run_chain(chain_emul, tmp_path, [46] + [204] * 10, 2, 260)
     run_chain(chain_emul, tmp_path, [46] + [204] * 10, 0, 40)
+    run_chain(chain_emul, tmp_path, [10] + [91] * 5, 3, 130)            # the default sets of the 7- and 9-prime bases
+    run_chain(chain_emul, tmp_path, [22] + [90] * 8, 4, 130)
     run_chain(chain_emul, tmp_path, [2, 6], 0, 257)                 # small bases: generic body, a 128-digit first label
     run_chain(chain_emul, tmp_path, [2, 15, 27], 0, 65)
     run_chain(chain_emul, tmp_path, [4, 60, 56], 0, 33, rule=1)
@@ -126,14 +137,11 @@ def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
 
 
 # ---- the evaluator's fused digit gates --------------------------------------------------------------
-DIGITS_EXE = os.path.join(HERE, "digits_emul.bin")
 
 
 @pytest.fixture(scope="module")
-def digits_emul():
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", DIGITS_EXE, os.path.join(HERE, "digits_emul.cpp")])
-    return DIGITS_EXE
+def digits_emul(built):
+    return built["digits_emul"]
 
 
 def run_digits(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40, wide=False):
@@ -176,6 +184,8 @@ def test_digit_gate_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 300)
     run_digits(digits_emul, tmp_path, [3, 19], [26] + [96] * 6, 0, 70)
     run_digits(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 260)
+    run_digits(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17], [10] + [91] * 5, 3, 130)
+    run_digits(digits_emul, tmp_path, [2, 11, 23], [22] + [90] * 8, 4, 130)
     run_digits(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
     run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5)                 # one digit, one residue
@@ -186,6 +196,8 @@ def test_digit_gates_one_per_lane_under_sanitizers(digits_emul, tmp_path):
     """the form for gadgets over few elements: a lane per (element, residue, digit)"""
     run_digits(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 300, wide=True)
     run_digits(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 260, wide=True)
+    run_digits(digits_emul, tmp_path, [3, 17], [10] + [91] * 5, 3, 70, wide=True)
+    run_digits(digits_emul, tmp_path, [5, 23], [22] + [90] * 8, 4, 70, wide=True)
     run_digits(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1, wide=True)
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
@@ -224,6 +236,8 @@ def test_digit_row_bodies_under_sanitizers(digits_emul, tmp_path):
     run_digits_garble(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 150)
     run_digits_garble(digits_emul, tmp_path, [3, 19], [26] + [96] * 6, 0, 70)
     run_digits_garble(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 130)
+    run_digits_garble(digits_emul, tmp_path, [2, 7, 17], [10] + [91] * 5, 3, 70)
+    run_digits_garble(digits_emul, tmp_path, [3, 23], [22] + [90] * 8, 4, 70)
     run_digits_garble(digits_emul, tmp_path, [2, 3], [2, 6], 0, 257)
     run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1)
     run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5)
@@ -233,20 +247,20 @@ def test_digit_rows_one_per_lane_under_sanitizers(digits_emul, tmp_path):
     """the garbler's form for gadgets over few elements: a lane per ciphertext row (element, value, digit)"""
     run_digits_garble(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 150, wide=True)
     run_digits_garble(digits_emul, tmp_path, [2, 23, 37], [46] + [204] * 10, 2, 130, wide=True)
+    run_digits_garble(digits_emul, tmp_path, [5, 13], [10] + [91] * 5, 3, 40, wide=True)
+    run_digits_garble(digits_emul, tmp_path, [2, 19], [22] + [90] * 8, 4, 40, wide=True)
     run_digits_garble(digits_emul, tmp_path, [3, 5, 7], [4, 60, 56], 0, 33, rule=1, wide=True)
     run_digits_garble(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
 
 # ---- one evaluator launch that mixes output moduli -------------------------------------------------
-def test_mixed_output_moduli_in_one_eval_launch_under_sanitizers(tmp_path):
+def test_mixed_output_moduli_in_one_eval_launch_under_sanitizers(built, tmp_path):
     """the evaluator's any-modulus instantiation picks a compile-time description of the output modulus per job:
     16 jobs with the 16 described moduli as outputs in ONE launch, exactly-sized buffers, address sanitizer; same
     results as the single-modulus instantiations"""
-    exe = os.path.join(HERE, "mixed_emul.bin")
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", exe, os.path.join(HERE, "mixed_emul.cpp")])
-    for n, seed in ((1, 1), (257, 2), (300, 3)):
-        r = subprocess.run([exe, str(n), str(seed)], capture_output=True, text=True)
+    exe = built["mixed_emul"]
+    for n, seed, which in ((1, 1, 0), (257, 2, 0), (300, 3, 0), (130, 4, 1)):
+        r = subprocess.run([exe, str(n), str(seed), str(which)], capture_output=True, text=True)
         assert r.returncode == 0 and r.stdout.strip() == "ok", r.stderr[-3000:]
 
 
@@ -290,10 +304,8 @@ def run_cast(tmp_path, exe, p, n, addc, rule=0, lam2=0, lam_p=0, elem_base=2 ** 
         assert (z[e] == (V[e].astype(np.int64) + beta * x[e].astype(np.int64) - U[e]) % p).all(), ("half gate", e)
 
 
-def test_cast_and_half_gate_bodies_under_sanitizers(tmp_path):
-    exe = os.path.join(HERE, "cast_emul.bin")
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", exe, os.path.join(HERE, "cast_emul.cpp")])
+def test_cast_and_half_gate_bodies_under_sanitizers(built, tmp_path):
+    exe = built["cast_emul"]
     run_cast(tmp_path, exe, 3, 300, 0)
     run_cast(tmp_path, exe, 19, 257, 7)
     run_cast(tmp_path, exe, 7, 40, 3, rule=1)
@@ -301,12 +313,10 @@ def test_cast_and_half_gate_bodies_under_sanitizers(tmp_path):
     run_cast(tmp_path, exe, 13, 33, 0, lam2=100, lam_p=9)
 
 
-def test_bitsliced_aes_against_the_standard_and_the_oracle(tmp_path):
+def test_bitsliced_aes_against_the_standard_and_the_oracle(built, tmp_path):
     """dash_aes_sliced.h (32 blocks per lane on bit planes, generated S-box circuit) on the host under the
     sanitizers: FIPS-197 Appendix B and C.1 vectors, and random blocks under random keys against the oracle's AES."""
-    exe = os.path.join(HERE, "aes_sliced_emul.bin")
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-                           "-o", exe, os.path.join(HERE, "aes_sliced_emul.cpp")])
+    exe = built["aes_sliced_emul"]
 
     def run(key, blocks):
         fin, fout = str(tmp_path / "aes_in.bin"), str(tmp_path / "aes_out.bin")
