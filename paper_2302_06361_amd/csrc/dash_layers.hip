@@ -353,7 +353,8 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         if (db.status) return db.status;
         uint64_t hg_rows = 0;
         for (int i = 0; i < k; i++) hg_rows += (uint64_t)E * (c->prime[i] + 4);
-        GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, hg_rows)), gb2(c, true, E, layer, eb, s, true);   // the two-row tables share launches
+        // (few rows: everything in launches that mix output moduli; else one launch per output modulus, its compile-time code)
+        GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, hg_rows)), gb2(c, true, E, layer, eb, s, few_rows(c, hg_rows));
         for (int i = 0; i < k; i++) {
             int p = c->prime[i];
             GateJob J = phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
@@ -482,7 +483,7 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
             sign_draws(c, db, 1, sb + (k - 1), pl.w);
             db.flush();
             if (db.status) return db.status;
-            GateBatcher gb(c, true, E, layer, eb, s, true);
+            GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, (uint64_t)E * 2 * (k - 1)));
             for (int i = 1; i < k; i++) {
                 gb.add(phi_job(2, c->prime[i], pl.up, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
                 cum += 2 * pitch_of(c, c->prime[i]);
