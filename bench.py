@@ -481,6 +481,19 @@ def micro_mlp(torch, workloads):
     return out
 
 
+def micro_reduced_accuracy(torch, workloads, batch=16):
+    """Config 2's network with the reduced-accuracy sign (Appendix, Approximated Garbled Sign): the three-digit set
+    (26; 12, 12) instead of the exact seven-digit one: 27 digit and carry gates per sign gadget instead of 63."""
+    net = dict(workloads.lenet(seed=2, batch=batch))
+    net["digits"] = list(workloads.DIGITS_REDUCED[8])
+    out = latency(torch, net, reps=3)
+    out["workload"] = ("config 2's network (LeNet-5 shape, batch %d, 8 primes) with the sign digit set %s: the sign is wrong for at "
+                       "most 2 k / M = 0.43 %% of the values" % (batch, tuple(net["digits"])))
+    out["ms_per_inference_eval"] = out["eval_ms"] / batch
+    out["ms_per_inference_garble"] = out["garble_ms"] / batch
+    return out
+
+
 def micro_paper_models(torch, workloads):
     """The shapes of the paper's models A-F (Sec. Model architectures), batch 1, random weights: garbling time
     (offline in the paper) and evaluation time (its online figure, there including a modelled network cost)."""
@@ -528,7 +541,7 @@ def main():
     ap.add_argument("--images", type=int, default=2, help="images of config 5's batch of 64 to stream (64 = the whole config, about 11 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true", help="the config-2 step alone")
-    ap.add_argument("--only", choices=["config1", "config3", "config4", "config5", "paper_models", "aes"],
+    ap.add_argument("--only", choices=["config1", "config3", "config4", "config5", "paper_models", "reduced", "aes"],
                     help="run one of the other configurations alone (for profiling); prints its JSON object")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -542,7 +555,8 @@ def main():
 
     if a.only:
         fn = dict(config1=micro_mlp, config3=micro_projection, config4=micro_contraction,
-                  config5=lambda t, w: micro_vgg(t, w, images=a.images), paper_models=micro_paper_models, aes=micro_aes)[a.only]
+                  config5=lambda t, w: micro_vgg(t, w, images=a.images), paper_models=micro_paper_models,
+                  reduced=lambda t, w: micro_reduced_accuracy(t, w, a.batch), aes=micro_aes)[a.only]
         print(json.dumps(fn(torch, workloads)))
         return
 
@@ -670,6 +684,7 @@ def main():
         configs["config4"] = micro_contraction(torch, workloads)
         configs["config5"] = micro_vgg(torch, workloads, images=a.images)
         configs["paper_models"] = micro_paper_models(torch, workloads)
+        configs["config2_reduced_accuracy"] = micro_reduced_accuracy(torch, workloads, a.batch)
     out["configs"] = {k: configs[k] for k in sorted(configs)}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(net)
