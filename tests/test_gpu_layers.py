@@ -93,11 +93,12 @@ def test_activation_one_gate_per_lane_digit_path(monkeypatch):
     run_activation(7, "scale", np.random.default_rng(78).integers(0, P7, 200), repeat=2, digits=workloads.DIGITS[7])
 
 
-@pytest.mark.parametrize("k", [8, 12])
+@pytest.mark.parametrize("k", [7, 8, 9, 12])
 def test_activation_bank_replicated_tables_forced(monkeypatch, k):
     """the instantiations with bank-replicated AES tables (taken by launches of 2^20 lanes and more: the wide layers
-    of configs 2 and 5) forced for small layers, for the gate kernels and for the fused digit garbler alike: every
-    byte of ReLU and scaling layers of the 8- and the 12-prime base against the oracle"""
+    of configs 2 and 5 and of the model shapes f and F) forced for small layers, for the gate kernels and for the fused
+    digit garbler alike: every byte of ReLU and scaling layers of the 7-, 8-, 9- and 12-prime bases (the four digit sets
+    with compile-time kernels) against the oracle"""
     monkeypatch.setenv("DASH_BANKED_MIN_LANES", "1")
     monkeypatch.setenv("DASH_DIGITS_BANKED_MIN_LANES", "1")
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", "0")       # the evaluator's digit gates fused per residue, as on wide layers
@@ -118,7 +119,7 @@ def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide):
     the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the oracle."""
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", wide)
     monkeypatch.setenv("DASH_GARBLE_FEW_ROWS", wide)
-    for k in (8, 12):
+    for k in (7, 8, 9, 12):
         P = int(np.prod(workloads.PRIMES[:k]))
         X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], np.random.default_rng(300 + k).integers(0, P, 296)])
         run_activation(k, "relu", X, elem_base=5)
