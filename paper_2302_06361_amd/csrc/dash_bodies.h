@@ -198,7 +198,8 @@ DASH_HD void eval_body(const GateLaunch& L, uint32_t bx, uint32_t by, uint32_t t
 // ---- evaluator, carry chain of the sign gadget ------------------------------------------------
 // One gate of the chain for element e: the input label comes dword by dword from in_dw, the output label
 // goes dword by dword to out.
-template <class MI, class MO, class Tab, class In, class Out>
+// QUAD: the four lanes of a quad work on the same element and share the AES (hash_block_quad).
+template <bool QUAD = false, class MI, class MO, class Tab, class In, class Out>
 DASH_HD void chain_gate(const ChainLaunch& L, const MI& Mi, const MO& Mo, uint32_t e, int j, In in_dw, Out out, const Tab& T) {
     uint32_t colour = in_dw(0) & 0xffu;       // the row's loads go out before the hash
     const uint32_t* row = (const uint32_t*)(L.table[j] + ((size_t)e * Mi.m + colour) * (Mo.ndw * 4));
@@ -208,7 +209,8 @@ DASH_HD void chain_gate(const ChainLaunch& L, const MI& Mi, const MO& Mo, uint32
         for (int i = 0; i < (int)MO::ndw; i++) rw[i] = row[i];
     }
     U128 K = compress(Mi, in_dw, &colour);
-    U128 h = hash_block(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T);
+    U128 h = QUAD ? hash_block_quad(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T)
+                  : hash_block(K, L.elem_base + e, L.slot[j], L.layer, L.key.rk, T);
     if constexpr (cmod_m<MO>::value != 0) {
         decompress(Mo, h, [&](int i, uint32_t hd) { out(i, submod4(rw[i], hd, Mo)); });
     } else {
@@ -225,9 +227,13 @@ DASH_HD void chain_out(const ChainLaunch& L, uint32_t e, int i, uint32_t w) {
 // Digit sets whose digits 2..n share one accumulation modulus (description MC) and whose first digit has
 // description M1, both fixed at compile time: the carry label stays in registers from gate to gate.  The output
 // wire has modulus 2 and 128 digits (the launcher takes the generic body for any other label length of modulus 2).
-template <class MC, class M1, class Tab>
+// QUAD (layers of few elements, where the chain of one lane is the run time): four neighbouring lanes per element; they
+// do everything alike except the AES, which they share, and the stores, which the first of them does.
+template <class MC, class M1, bool QUAD = false, class Tab>
 DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, const Tab& T) {
-    const uint32_t e = bx * kThreads + tx;
+    const uint32_t lane = bx * kThreads + tx;
+    const uint32_t e = QUAD ? lane >> 2 : lane;
+    const bool writer = !QUAD || (lane & 3u) == 0;
     if (e >= L.n_elem) return;
     const MC Mc{nullptr};
     const M1 Mf{nullptr};
@@ -247,7 +253,7 @@ DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, con
         for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(sm[i], cw[i], Mc);   // cw = 0 at j = n
 #pragma unroll
         for (int i = 0; i < (int)MC::ndw; i++) sm[i] = ld_dw(L.sum[j - 1], e, i);
-        chain_gate(L, Mc, Mc, e, j, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { cw[i] = w; }, T);
+        chain_gate<QUAD>(L, Mc, Mc, e, j, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { cw[i] = w; }, T);
     }
     {                                               // digit 2 -> carry into digit 1 (modulus of the first digit)
         uint32_t in[MC::ndw];
@@ -255,14 +261,15 @@ DASH_HD void chain_eval_body(const ChainLaunch& L, uint32_t bx, uint32_t tx, con
         for (int i = 0; i < (int)MC::ndw; i++) in[i] = addmod4(sm[i], cw[i], Mc);
 #pragma unroll
         for (int i = 0; i < (int)M1::ndw; i++) s1[i] = ld_dw(L.sum[1], e, i);
-        chain_gate(L, Mc, Mf, e, 2, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { c1[i] = w; }, T);
+        chain_gate<QUAD>(L, Mc, Mf, e, 2, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { c1[i] = w; }, T);
     }
     {                                               // final gate: digit 1 -> the sign bit
         uint32_t in[M1::ndw];
 #pragma unroll
         for (int i = 0; i < (int)M1::ndw; i++) in[i] = addmod4(s1[i], c1[i], Mf);
         Dw4 bits[8];                                // the 128 digits of the output wire: stored 16 bytes at a time
-        chain_gate(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { bits[i >> 2].w[i & 3] = w; }, T);
+        chain_gate<QUAD>(L, Mf, M2, e, 1, [&](int i) { return in[i]; }, [&](int i, uint32_t w) { bits[i >> 2].w[i & 3] = w; }, T);
+        if (!writer) return;
 #pragma unroll
         for (int ch = 0; ch < 8; ch++) st_chunk(L.bit, e, ch, bits[ch]);
         if (L.up.p) {

@@ -69,12 +69,13 @@ int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
 // One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
 // whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
 // other set takes the body with run-time constants.
-template <class MC, class M1>
+// QUAD: four lanes per element, which share the AES of each gate (layers of few elements).
+template <class MC, class M1, bool QUAD>
 __global__ __launch_bounds__(kThreads) void k_chain_eval(const ChainLaunch L) {
     __shared__ uint32_t tt[kTabWords];
     const LdsTab T = load_ttab(tt, L.ttab);
-    const uint32_t tiles = (L.n_elem + kThreads - 1) / kThreads;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1>(L, tile, threadIdx.x, T);
+    const uint32_t tiles = (uint32_t)(((uint64_t)L.n_elem * (QUAD ? 4 : 1) + kThreads - 1) / kThreads);
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) chain_eval_body<MC, M1, QUAD>(L, tile, threadIdx.x, T);
 }
 __global__ __launch_bounds__(kThreads) void k_chain_eval_generic(const ChainLaunch L) {
     __shared__ uint32_t tt[kTabWords];
@@ -96,14 +97,17 @@ int launch_chain_eval(const dash_ctx* c, ChainLaunch& L, hipStream_t s) {
         bytes += (double)L.n_elem * (c->mods[L.m[j]].lam + (j >= 2 ? c->mods[L.m[j - 1]].lam : 128));
     }
     if ((uint64_t)L.n_elem * 255 >= (1ull << 32)) return DASH_ESIZE;
-    dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, 1));
+    const bool quad = (uint64_t)L.n_elem * 4 <= c->quad_max_lanes;
+    dim3 grid(grid_x_for(((uint64_t)L.n_elem * (quad ? 4 : 1) + kThreads - 1) / kThreads, 1));
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.n, bytes);
     const bool bit128 = c->mods[2].lam == 128;      // the fused bodies write the 128 digits of the sign wire
     const int typed = bit128 && uniform ? digit_set_index(c->mods[L.m[2]], c->mods[L.m[1]]) : 0;
     with_digit_set(typed, [&](auto ds) {
         typedef decltype(ds) DS;
-        if constexpr (cmod_m<typename DS::MC>::value != 0) hipLaunchKernelGGL((k_chain_eval<typename DS::MC, typename DS::M1>), grid, dim3(kThreads), 0, s, L);
-        else hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
+        if constexpr (cmod_m<typename DS::MC>::value != 0) {
+            if (quad) hipLaunchKernelGGL((k_chain_eval<typename DS::MC, typename DS::M1, true>), grid, dim3(kThreads), 0, s, L);
+            else hipLaunchKernelGGL((k_chain_eval<typename DS::MC, typename DS::M1, false>), grid, dim3(kThreads), 0, s, L);
+        } else hipLaunchKernelGGL(k_chain_eval_generic, grid, dim3(kThreads), 0, s, L);
     });
     DASH_HIP(hipGetLastError());
     return DASH_OK;

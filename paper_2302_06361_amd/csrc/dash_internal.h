@@ -66,6 +66,7 @@ struct dash_ctx {
     uint64_t fused_min_elems[2];     // [garble, eval]: sign gadgets over this many elements or more run their digit gates in
                                      // the fused kernels (a lane walks the n gates of a residue); smaller ones one gate per lane
     uint64_t wide_max_lanes;         // evaluator: sign gadgets of at most this many digit gates run them one per lane
+    uint64_t quad_max_lanes;         // evaluator: carry chains of at most this many lanes (4 per element) run four lanes per element
     uint64_t few_rows_max;           // garbler: launches of at most this many rows take the forms for few rows (a lane per row of the
                                      // digit gates; gates of different output moduli in one launch)
     uint64_t digits_banked_min_lanes;   // the banked-table threshold of the fused garbling kernel (n hashes per lane)

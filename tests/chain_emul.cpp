@@ -80,13 +80,16 @@ int main(int argc, char** argv) {
     }
     L.bit = LView{bit.data(), (int64_t)16 * E, 16u};
     HostTab T;
-    const uint32_t tiles = (E + kThreads - 1) / kThreads;
+    const bool quad = hd[6] != 0;      // four lanes per element (on the host each of them hashes on its own)
+    const uint32_t tiles = (E * (quad ? 4 : 1) + kThreads - 1) / kThreads;
     for (uint32_t bx = 0; bx < tiles; bx++)
         for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) {
             with_digit_set(variant, [&](auto ds) {
                 typedef decltype(ds) DS;
-                if constexpr (cmod_m<typename DS::MC>::value != 0) chain_eval_body<typename DS::MC, typename DS::M1>(L, bx, tx, T);
-                else chain_eval_generic_body(L, bx, tx, T);
+                if constexpr (cmod_m<typename DS::MC>::value != 0) {
+                    if (quad) chain_eval_body<typename DS::MC, typename DS::M1, true>(L, bx, tx, T);
+                    else chain_eval_body<typename DS::MC, typename DS::M1>(L, bx, tx, T);
+                } else chain_eval_generic_body(L, bx, tx, T);
             });
         }
     std::vector<uint8_t> out((size_t)E * lam2);

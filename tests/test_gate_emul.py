@@ -81,7 +81,7 @@ def chain_emul(built):
     return built["chain_emul"]
 
 
-def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70, lam2=0):
+def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 5, layer=4, slot0=70, lam2=0, quad=False):
     """m[0..n-1] = accumulation moduli of digits 1..n.  The tables are random bytes below the output modulus:
     the evaluator's result is defined by them alone, C_{j-1} = row[colour(S_j)] - H(S_j), S_j = sum_j + C_j
     (Appendix, Garbled Mixed-Radix Addition), recomputed here with the oracle's hash."""
@@ -100,7 +100,7 @@ def run_chain(chain_emul, tmp_path, m, variant, n_elem, rule=0, elem_base=2 ** 3
         t = np.zeros((n_elem, m[j], pitch), np.uint8)
         t[:, :, :lam_o] = g.integers(0, outm[j], (n_elem, m[j], lam_o))
         tabs.append(t)
-    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, lam2, 0, 0, elem_base)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, lam2, 1 if quad else 0, 0, elem_base)
     blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % n, *slots)
     blob += b"".join(s.tobytes() for s in sums) + b"".join(t.tobytes() for t in tabs)
     fin, fout = str(tmp_path / "cin.bin"), str(tmp_path / "cout.bin")
@@ -127,6 +127,8 @@ def test_chain_bodies_under_sanitizers(chain_emul, tmp_path):
     run_chain(chain_emul, tmp_path, [46] + [204] * 10, 2, 260)
     run_chain(chain_emul, tmp_path, [46] + [204] * 10, 0, 40)
     run_chain(chain_emul, tmp_path, [10] + [91] * 5, 3, 130)            # the default sets of the 7- and 9-prime bases
+    run_chain(chain_emul, tmp_path, [26] + [96] * 6, 1, 301, quad=True)    # four lanes per element (indexing and stores)
+    run_chain(chain_emul, tmp_path, [46] + [204] * 10, 2, 65, quad=True)
     run_chain(chain_emul, tmp_path, [22] + [90] * 8, 4, 130)
     run_chain(chain_emul, tmp_path, [2, 6], 0, 257)                 # small bases: generic body, a 128-digit first label
     run_chain(chain_emul, tmp_path, [2, 15, 27], 0, 65)

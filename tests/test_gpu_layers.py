@@ -119,6 +119,7 @@ def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide):
     the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the oracle."""
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", wide)
     monkeypatch.setenv("DASH_GARBLE_FEW_ROWS", wide)
+    monkeypatch.setenv("DASH_QUAD_MAX_LANES", wide)      # carry chain: four lanes per element that share each AES, or one
     for k in (7, 8, 9, 12):
         P = int(np.prod(workloads.PRIMES[:k]))
         X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], np.random.default_rng(300 + k).integers(0, P, 296)])
