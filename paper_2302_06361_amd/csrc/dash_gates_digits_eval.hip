@@ -67,7 +67,7 @@ int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
 
 // ------------------------------------------------------------------- carry chain of the sign gadget, evaluator
 // One launch for the n dependent gates of the mixed-radix addition (a launch per digit costs about 10 us each,
-// whatever the layer size, and they cannot overlap).  Instantiations for the two default digit sets; any
+// whatever the layer size, and they cannot overlap).  Instantiations for the digit sets with compile-time moduli (DASH_DIGIT_SETS); any
 // other set takes the body with run-time constants.
 // QUAD: four lanes per element, which share the AES of each gate (layers of few elements).
 template <class MC, class M1, bool QUAD>

@@ -258,8 +258,8 @@ def test_digit_rows_one_per_lane_under_sanitizers(digits_emul, tmp_path):
 # ---- one evaluator launch that mixes output moduli -------------------------------------------------
 def test_mixed_output_moduli_in_one_eval_launch_under_sanitizers(built, tmp_path):
     """the evaluator's any-modulus instantiation picks a compile-time description of the output modulus per job:
-    16 jobs with the 16 described moduli as outputs in ONE launch, exactly-sized buffers, address sanitizer; same
-    results as the single-modulus instantiations"""
+    16 jobs with 16 of the 20 described moduli as outputs in ONE launch (two lists, so that each of the 20 occurs),
+    exactly-sized buffers, address sanitizer; same results as the single-modulus instantiations"""
     exe = built["mixed_emul"]
     for n, seed, which in ((1, 1, 0), (257, 2, 0), (300, 3, 0), (130, 4, 1)):
         r = subprocess.run([exe, str(n), str(seed), str(which)], capture_output=True, text=True)
