@@ -11,6 +11,7 @@ Prints ONE JSON line.
 """
 import argparse
 import hashlib
+import re
 import json
 import os
 import sys
@@ -33,10 +34,14 @@ GATE_SOURCES = ["dash_core.h", "dash_bodies.h", "dash_tabs.h", "dash_launch.h", 
 
 
 def gate_source_hash():
-    """identifies the gate-kernel sources a counter file was taken with"""
+    """identifies the gate-kernel sources a counter file was taken with: their code, without comments and blank space
+    (a reworded comment does not make counters stale)"""
     h = hashlib.sha256()
     for name in GATE_SOURCES:
-        h.update(open(os.path.join(ROOT, "paper_2302_06361_amd", "csrc", name), "rb").read())
+        text = open(os.path.join(ROOT, "paper_2302_06361_amd", "csrc", name), encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
