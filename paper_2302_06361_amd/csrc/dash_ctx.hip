@@ -95,19 +95,22 @@ struct DecodeArgs {
     const ModInfo* mods;
     uint32_t k, n;
     uint32_t prime[DASH_MAX_PRIMES];
-    uint64_t crt_coef[DASH_MAX_PRIMES];   // (P/p_i) * ((P/p_i)^-1 mod p_i) mod P
+    uint64_t crt_part[DASH_MAX_PRIMES];   // P / p_i
+    uint32_t crt_inv[DASH_MAX_PRIMES];    // (P / p_i)^-1 mod p_i
     uint64_t P;
     LView act[DASH_MAX_PRIMES], zero[DASH_MAX_PRIMES];
     int64_t* values;
     uint8_t* valid;
 };
 
-// De: 16 lanes per value, one per residue: lane (value, i) recovers the residue a_i from the colours and checks the whole
-// label of residue i; the value's first lane then adds up the CRT terms.  (A lane per value that walked over the residues
+// De: 16 lanes per value, one per residue: lane (value, i) recovers the residue a_i from the colours, checks the whole
+// label of residue i and forms its CRT term ((a_i * (P/p_i)^-1) mod p_i) * (P/p_i), which is below P; the value's first
+// lane then adds up the terms.  (A lane per value that walked over the residues
 // spent the latency of k dependent label comparisons: 37 us for the ten outputs of one inference.)
 __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
     static_assert(DASH_MAX_PRIMES == 16 && kThreads % 16 == 0, "lane roles");
     __shared__ uint32_t res[kThreads];                   // residue, or 0xffffffff for a label that is not valid
+    __shared__ uint64_t term[kThreads];                  // CRT term of the residue
     const uint32_t e = blockIdx.x * (kThreads / 16) + threadIdx.x / 16, i = threadIdx.x % 16;
     uint32_t r = 0;
     if (e < A.n && i < A.k) {
@@ -129,6 +132,7 @@ __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
             }
         }
         r = bad ? 0xffffffffu : v;
+        term[threadIdx.x] = (uint64_t)mod_m(v * A.crt_inv[i], M) * A.crt_part[i];
     }
     res[threadIdx.x] = r;
     __syncthreads();
@@ -138,16 +142,7 @@ __global__ __launch_bounds__(kThreads) void k_decode(const DecodeArgs A) {
     for (uint32_t t = 0; t < A.k; t++) {
         const uint32_t v = res[threadIdx.x + t];
         if (v == 0xffffffffu) { ok = false; continue; }
-        // X += v * coef mod P by doubling (v < 128, coef < P < 2^62: no overflow, no wide division)
-        uint64_t acc = 0;
-        const uint64_t cf = A.crt_coef[t];
-#pragma unroll
-        for (int b = 6; b >= 0; b--) {
-            acc += acc;
-            if (acc >= A.P) acc -= A.P;
-            if ((v >> b) & 1u) { acc += cf; if (acc >= A.P) acc -= A.P; }
-        }
-        X += acc;
+        X += term[threadIdx.x + t];       // both below P < 2^62
         if (X >= A.P) X -= A.P;
     }
     int64_t s = (2 * X >= A.P) ? (int64_t)X - (int64_t)A.P : (int64_t)X;
@@ -543,7 +538,8 @@ int dash_decode(dash_ctx* c, const dash_labels* act, const dash_labels* zero, in
         int p = c->prime[i];
         uint64_t Ai = c->P / p;
         A.prime[i] = p;
-        A.crt_coef[i] = (uint64_t)(((u128)Ai * inv_mod((int)(Ai % p), p)) % c->P);
+        A.crt_part[i] = Ai;
+        A.crt_inv[i] = (uint32_t)inv_mod((int)(Ai % p), p);
         A.act[i] = view_of(act, i);
         A.zero[i] = view_of(zero, i);
     }
