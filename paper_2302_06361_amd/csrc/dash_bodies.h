@@ -572,4 +572,76 @@ DASH_HD void hg_finish_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_
     });
 }
 
+// The whole evaluator side of the mixed-modulus half gate (Appendix) for layers of few elements, where three dependent
+// launches cost more than their work: the four lanes of a quad take one (element, prime).  Lane 0 evaluates the garbler
+// half (U, from the label of x), lane 1 the evaluator half (V, from the sign bit's label), lane 2 the row that carries
+// beta: three hashes side by side; lane 0 then collects V and beta from its neighbours and stores z = V + beta x - U.
+// Primes with compile-time descriptions only (the launcher checks).  On the host a caller with role 0 works through
+// the three roles itself.
+template <class Tab>
+DASH_HD void hg_eval_quad_body(const HgLaunch& L, uint32_t bx, uint32_t by, uint32_t tx, const Tab& T) {
+    const HgJob& J = L.jobs[by];
+    const ModInfo Mp = L.mods[J.p];
+    const uint32_t lane = bx * kThreads + tx, e = lane >> 2, c = lane & 3u;
+    if (e >= L.n_elem) return;
+    with_mod(Mp, [&](auto P) {
+        typedef decltype(P) PD;
+        if constexpr (cmod_m<PD>::value != 0) {
+            constexpr int ndw = (int)PD::ndw, nch = (int)PD::nchunk;
+            Dw4 x[nch];
+            // one role: w = the gate's output label (roles 0 and 1), beta (role 2; role 3 repeats it and is not used)
+            auto run_role = [&](uint32_t role, uint32_t* w, uint32_t& beta) {
+                uint32_t colour = 0;
+                U128 K;
+                if (role == 0) {
+#pragma unroll
+                    for (int ch = 0; ch < nch; ch++) x[ch] = ld_chunk(J.x, e, ch);
+                    K = compress(P, [&](int i) { return x[i >> 2].w[i & 3]; }, &colour);
+                } else {
+                    K = compress_mod2(L.mods, [&](int i) { return ld_dw(J.y, e, i); }, &colour);
+                }
+                const uint32_t rows = role == 0 ? Mp.m : 2u;
+                const uint8_t* table = role == 0 ? J.G : J.Eh;
+                uint32_t rw[ndw];
+                uint32_t srow = 0;
+                if (role < 2) {
+                    const uint32_t* row = (const uint32_t*)(table + ((size_t)e * rows + colour) * (ndw * 4));
+#pragma unroll
+                    for (int i = 0; i < ndw; i++) rw[i] = row[i];
+                } else {
+                    srow = *(const uint32_t*)(J.S + ((size_t)e * 2 + colour) * 4);
+                }
+                const uint32_t slot = J.slot - 2 + (role < 2 ? role : 2u);
+                const U128 h = hash_block(K, L.elem_base + e, slot, L.layer, L.key.rk, T);
+                if (role < 2) decompress(P, h, [&](int i, uint32_t hd) { w[i] = submod4(rw[i], hd, P); });
+                else beta = mod_m(srow + Mp.m - mod_u128(h, Mp), Mp);
+            };
+            uint32_t u[ndw], v[ndw], beta = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+            run_role(c, u, beta);
+#pragma unroll
+            for (int i = 0; i < ndw; i++) v[i] = quad_lane<1>(u[i]);
+            beta = quad_lane<2>(beta);
+            if (c != 0) return;
+#else
+            if (c != 0) return;
+            uint32_t unused = 0;
+            run_role(1, v, unused);
+            run_role(2, u, beta);
+            run_role(0, u, unused);
+#endif
+#pragma unroll
+            for (int ch = 0; ch < nch; ch++) {
+                Dw4 z;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int i = 4 * ch + q;
+                    z.w[q] = i < ndw ? submod4(axpymod4(v[i], beta, x[ch].w[q], P), u[i], P) : 0u;
+                }
+                st_chunk(J.z, e, ch, z);
+            }
+        }
+    });
+}
+
 }  // namespace dash

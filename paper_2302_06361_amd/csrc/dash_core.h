@@ -360,6 +360,15 @@ DASH_HD void aes128_encrypt_quad(uint32_t s[4], const uint32_t* rk, const Tab& T
 #endif
 }
 
+// value that lane I (0..3) of the caller's quad holds (all four lanes active)
+template <int I> DASH_HD uint32_t quad_lane(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, I * 0x55, 0xf, 0xf, true);      // quad_perm:[I,I,I,I]
+#else
+    return v;
+#endif
+}
+
 // h = AES(X) xor X with X = K xor tweak; tweak = elem:u64 | slot:u32 | layer:u16 | 0:u16.
 template <class Tab>
 DASH_HD U128 hash_block(const U128& K, uint64_t elem, uint32_t slot, uint32_t layer, const uint32_t* rk, const Tab& T) {

@@ -64,6 +64,40 @@ __global__ __launch_bounds__(kThreads) void k_hg_finish(const HgLaunch L) {
     for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) hg_finish_body(L, tile, blockIdx.y, threadIdx.x, T);
 }
 
+// the half gate's two projection gates and its finish in one launch, four lanes per (element, prime): layers of few elements
+__global__ __launch_bounds__(kThreads) void k_hg_eval_quad(const HgLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    const LdsTab T = load_ttab(tt, L.ttab);
+    const uint32_t tiles = (uint32_t)(((uint64_t)L.n_elem * 4 + kThreads - 1) / kThreads);
+    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) hg_eval_quad_body(L, tile, blockIdx.y, threadIdx.x, T);
+}
+
+// whether launch_hg_eval_quad serves this layer: few elements, every prime with a compile-time description
+bool hg_eval_quad_wanted(const dash_ctx* c, uint32_t n_elem) {
+    if ((uint64_t)n_elem * 4 * c->k > c->quad_max_lanes) return false;
+    for (int i = 0; i < c->k; i++) if (!hot_mod_index(c->mods[c->prime[i]])) return false;
+    return true;
+}
+
+int launch_hg_eval_quad(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s) {
+    if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
+    if (L.n_elem == 0) return DASH_OK;
+    if (L.n_elem > (1u << 26)) return DASH_ESIZE;
+    double bytes = 0;
+    for (int j = 0; j < njobs; j++) {
+        const HgJob& J = L.jobs[j];
+        if (J.p < 2 || J.p > 255 || !hot_mod_index(c->mods[J.p]) || J.slot < 2) return DASH_EINVAL;
+        if (!J.x.p || !J.y.p || !J.z.p || !J.S || !J.G || !J.Eh) return DASH_EINVAL;
+        bytes += (double)L.n_elem * (2.0 * c->mods[2].lam + 4.0 * c->mods[J.p].lam + 4);
+    }
+    L.key = c->fixed; L.ttab = c->d_ttab; L.mods = c->d_mods;
+    dim3 grid(grid_x_for(((uint64_t)L.n_elem * 4 + kThreads - 1) / kThreads, njobs), njobs);
+    ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * njobs * 2, bytes);
+    hipLaunchKernelGGL(k_hg_eval_quad, grid, dim3(kThreads), 0, s, L);
+    DASH_HIP(hipGetLastError());
+    return DASH_OK;
+}
+
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;

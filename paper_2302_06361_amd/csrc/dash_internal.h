@@ -89,6 +89,8 @@ int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
 int launch_cast_halve(const dash_ctx* c, CastLaunch& L, int njobs, hipStream_t s);
 int launch_cast_digits_eval(const dash_ctx* c, CastLaunch& C, int njobs, DigitsLaunch& L, hipStream_t s);
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
+bool hg_eval_quad_wanted(const dash_ctx* c, uint32_t n_elem);
+int launch_hg_eval_quad(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
 
 // layer pipelines (dash_layers.hip)
 int layer_sizes(const dash_ctx* c, const dash_layer* L, int64_t* out_elems, size_t* table_bytes, size_t* scratch_bytes);

@@ -94,6 +94,9 @@ struct HgJob {
     uint32_t p, slot;
     LView x, y, U, V, z;
     const uint8_t* S;     // [elem][2][4]
+    // the two projection gates in front (the whole half gate in one launch, hg_eval_quad_body): garbler half [elem][p] rows
+    // with slot - 2, evaluator half [elem][2] rows with slot - 1; U and V are not stored then
+    const uint8_t *G, *Eh;
 };
 struct HgLaunch {
     AesKey key;

@@ -379,6 +379,14 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         ab.flush();
         return ab.status;
     }
+    HgLaunch H;
+    memset(&H, 0, sizeof(H));
+    H.n_elem = E; H.layer = layer; H.elem_base = eb;
+    int nj = 0;
+    for (int i = 0; i < k; i++) {
+        H.jobs[nj++] = HgJob{(uint32_t)c->prime[i], (uint32_t)(ns + 3 * i + 2), x[i], pl.w.bit, pl.U[i], pl.V[i], view_of(out, i), S[i], G[i], Eh[i]};
+    }
+    if (hg_eval_quad_wanted(c, E)) return launch_hg_eval_quad(c, H, nj, s);      // few elements: the whole half gate in one launch
     GateBatcher gb(c, false, E, layer, eb, s, true);
     for (int i = 0; i < k; i++) {
         int p = c->prime[i];
@@ -387,13 +395,6 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
     }
     gb.flush();
     if (gb.status) return gb.status;
-    HgLaunch H;
-    memset(&H, 0, sizeof(H));
-    H.n_elem = E; H.layer = layer; H.elem_base = eb;
-    int nj = 0;
-    for (int i = 0; i < k; i++) {
-        H.jobs[nj++] = HgJob{(uint32_t)c->prime[i], (uint32_t)(ns + 3 * i + 2), x[i], pl.w.bit, pl.U[i], pl.V[i], view_of(out, i), S[i]};
-    }
     return launch_hg_finish(c, H, nj, s);
 }
 

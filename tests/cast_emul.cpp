@@ -81,7 +81,7 @@ int main(int argc, char** argv) {
     expand_key(fixed, Sb, H.key.rk);
     H.mods = mods.data(); H.elem_base = elem_base; H.layer = (uint32_t)layer; H.n_elem = n;
     H.jobs[0] = HgJob{(uint32_t)p, (uint32_t)slot + 2, LView{cx.data(), (int64_t)16 * n, 16u}, LView{cy.data(), (int64_t)16 * n, 16u},
-                      LView{cU.data(), (int64_t)16 * n, 16u}, LView{cV.data(), (int64_t)16 * n, 16u}, LView{cz.data(), (int64_t)16 * n, 16u}, S.data()};
+                      LView{cU.data(), (int64_t)16 * n, 16u}, LView{cV.data(), (int64_t)16 * n, 16u}, LView{cz.data(), (int64_t)16 * n, 16u}, S.data(), nullptr, nullptr};
     for (uint32_t bx = 0; bx < tiles; bx++)
         for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) hg_finish_body(H, bx, 0, tx, HostTab());
 
@@ -127,6 +127,51 @@ int main(int argc, char** argv) {
                 for (uint32_t j = 0; j <= 3; j++) cast_digit_wide_body<ModInfo, ModInfo>(C2, D, bx, 0, j, tx, HostTab());
         if (cb2 != cb) { fprintf(stderr, "cast_digit_wide_body: b differs\n"); return 3; }
         if (o_new != o_ref) { fprintf(stderr, "cast_digit_wide_body: digit wires differ\n"); return 3; }
+    }
+
+    // The whole half gate in one pass (hg_eval_quad_body, four lanes per element) against the bodies it replaces: the two
+    // projection gates through eval_body, whose outputs U' and V' go into hg_finish_body.  Tables from a small generator,
+    // exactly-sized buffers; primes with a compile-time description only.
+    if (hot_mod_index(Mp)) {
+        const size_t pitch = (size_t)Mp.ndw * 4;
+        std::vector<uint8_t> G((size_t)n * p * pitch), Eh((size_t)n * 2 * pitch);
+        uint32_t lcg = 777u + (uint32_t)p;
+        for (auto* t : {&G, &Eh})
+            for (size_t r = 0; r < t->size() / pitch; r++)
+                for (size_t d = 0; d < pitch; d++) {
+                    lcg = lcg * 1664525u + 1013904223u;
+                    (*t)[r * pitch + d] = d < Mp.lam ? (uint8_t)((lcg >> 16) % p) : 0;
+                }
+        std::vector<uint8_t> u2((size_t)Mp.nchunk * n * 16, 0xEE), v2((size_t)Mp.nchunk * n * 16, 0xEE);
+        std::vector<uint8_t> z_ref((size_t)Mp.nchunk * n * 16, 0xEE), z_new((size_t)Mp.nchunk * n * 16, 0xDD);
+        GateLaunch GL;
+        memset(&GL, 0, sizeof(GL));
+        expand_key(fixed, Sb, GL.key.rk);
+        GL.mods = mods.data(); GL.layer = (uint32_t)layer; GL.njobs = 2;
+        for (int j = 0; j < 2; j++) {
+            GateJob& Q = GL.jobs[j];
+            Q.p = j == 0 ? (uint32_t)p : 2u; Q.q = (uint32_t)p; Q.slot = (uint32_t)slot + j; Q.mode = PAY_PHI;
+            Q.elem_base = elem_base; Q.n_elem = n;
+            Q.in = j == 0 ? LView{cx.data(), (int64_t)16 * n, 16u} : LView{cy.data(), (int64_t)16 * n, 16u};
+            Q.table = j == 0 ? G.data() : Eh.data();
+            Q.out = LView{(j == 0 ? u2 : v2).data(), (int64_t)16 * n, 16u};
+            for (uint32_t bx = 0; bx < tiles; bx++)
+                for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) eval_body<ModInfo>(GL, bx, j, tx, HostTab());
+        }
+        HgLaunch H2 = H;
+        H2.jobs[0].U = LView{u2.data(), (int64_t)16 * n, 16u};
+        H2.jobs[0].V = LView{v2.data(), (int64_t)16 * n, 16u};
+        H2.jobs[0].z = LView{z_ref.data(), (int64_t)16 * n, 16u};
+        for (uint32_t bx = 0; bx < tiles; bx++)
+            for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) hg_finish_body(H2, bx, 0, tx, HostTab());
+        H2.jobs[0].U = LView{nullptr, 0, 0u};
+        H2.jobs[0].V = LView{nullptr, 0, 0u};
+        H2.jobs[0].z = LView{z_new.data(), (int64_t)16 * n, 16u};
+        H2.jobs[0].G = G.data(); H2.jobs[0].Eh = Eh.data();
+        const uint32_t qtiles = (n * 4 + kThreads - 1) / kThreads;
+        for (uint32_t bx = 0; bx < qtiles; bx++)
+            for (uint32_t tx = 0; tx < (uint32_t)kThreads; tx++) hg_eval_quad_body(H2, bx, 0, tx, HostTab());
+        if (z_new != z_ref) { fprintf(stderr, "hg_eval_quad_body: z differs\n"); return 3; }
     }
 
     std::vector<uint8_t> ob((size_t)n * Mp.lam), oz((size_t)n * Mp.lam);
