@@ -335,6 +335,19 @@ DASH_HD void digit_gate(const DigitsLaunch& L, const DigitsRes& R, const MO& Mo,
     }
     for (int i = (int)Mo.ndw; i < (int)Mo.nchunk * 4; i++) st_dw(out, e, i, 0);
 }
+// the same gate with its output label handed to put(dword index, packed digits) instead of stored (compile-time moduli)
+template <class MO, class Tab, class Put>
+DASH_HD void digit_gate_to(const DigitsLaunch& L, const DigitsRes& R, const MO& Mo, const U128& K, uint32_t colour, uint32_t e, int j, const Tab& T,
+                           Put put) {
+    const uint8_t* seg = R.table + (size_t)L.n_elem * R.p * L.row_prefix[j];
+    const uint32_t* row = (const uint32_t*)(seg + ((size_t)e * R.p + colour) * (MO::ndw * 4));
+    uint32_t rw[MO::ndw];
+#pragma unroll
+    for (int i = 0; i < (int)MO::ndw; i++) rw[i] = row[i];
+    U128 h = hash_block(K, L.elem_base + e, R.slot0 + (uint32_t)(j - 1), L.layer, L.key.rk, T);
+    decompress(Mo, h, [&](int i, uint32_t hd) { put(i, submod4(rw[i], hd, Mo)); });
+}
+
 // MC, M1: descriptions of the accumulation moduli of digits 2..n and of digit 1 (compile time), or ModInfo for
 // both (any digit set: then every digit's constants are read from the table of moduli)
 template <class MC, class M1, class Tab>
@@ -535,6 +548,88 @@ DASH_HD void cast_digit_wide_body(const CastLaunch& C, const DigitsLaunch& L, ui
             }
         }
     });
+}
+
+// ---- evaluator, few elements: digit gates that add up their outputs --------------------------
+// A block takes 64 elements and one digit j; wave w of it takes residue w.  Every lane evaluates its digit gate (the
+// scaling gadget's lanes do the cast step first, as in cast_digit_wide_body) and adds the output label into the block's
+// accumulator, two digits per 32-bit word in 16-bit fields (phase 1); after a barrier the first wave reduces the sums
+// mod m_j and stores the wire S_j (phase 2).  The digit wires themselves are not stored, and the launch that added them
+// up is not needed.  Digit sets with compile-time moduli only.
+constexpr int kSumDw = 10;                  // dwords per label of the longest such modulus (39 digits)
+constexpr int kSumElems = 64;
+DASH_HD void sum_add(uint32_t* a, uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    atomicAdd(a, v);
+#else
+    *a += v;
+#endif
+}
+struct NoCast {};       // in place of the CastLaunch: the digit gates of a plain sign gadget
+template <class MC, class M1, class CastT, class Tab>
+DASH_HD void digits_sum_phase1(const CastT& C, const DigitsLaunch& L, uint32_t bx, uint32_t by, uint32_t j, uint32_t el, const Tab& T,
+                               uint32_t* acc) {
+    static_assert(MC::ndw <= kSumDw && M1::ndw <= kSumDw, "accumulator rows");
+    const DigitsRes& R = L.res[by];
+    const uint32_t e = bx * kSumElems + el;
+    if (e >= L.n_elem || j < 1 || j > L.n) return;
+    const ModInfo Mp = L.mods[R.p];
+    uint32_t colour = 0;
+    U128 K = {{0, 0, 0, 0}};
+    if constexpr (std::is_same<CastT, CastLaunch>::value) {        // scaling gadget: b of this residue first (stored by the lanes of digit 1)
+        const CastJob& J = C.jobs[by];
+        uint32_t c2 = 0;
+        const U128 K2 = compress_mod2(C.mods, [&](int i) { return ld_dw(C.y, e, i); }, &c2);
+        const U128 h = hash_block(K2, C.elem_base + e, J.slot, C.layer, C.key.rk, T);
+        with_mod(Mp, [&](auto P) {
+            typedef decltype(P) PD;
+            if constexpr (cmod_m<PD>::value != 0) {
+                Dw4 xw[PD::nchunk];
+                cast_halve_regs(J, P, e, c2, h, xw);
+                if (j == 1) {
+#pragma unroll
+                    for (int ch = 0; ch < (int)PD::nchunk; ch++) st_chunk(J.out, e, ch, xw[ch]);
+                }
+                K = compress(P, [&](int i) { return xw[i >> 2].w[i & 3]; }, &colour);
+            }
+        });
+    } else {
+        with_mod(Mp, [&](auto P) { K = compress(P, [&](int i) { return ld_dw(R.in, e, i); }, &colour); });
+    }
+    uint32_t* row = acc + (size_t)el * (kSumDw * 2);
+    auto put = [&](int i, uint32_t w) {
+        sum_add(row + 2 * i, w & 0x00ff00ffu);
+        sum_add(row + 2 * i + 1, (w >> 8) & 0x00ff00ffu);
+    };
+    if (j == 1) digit_gate_to(L, R, M1{nullptr}, K, colour, e, 1, T, put);
+    else digit_gate_to(L, R, MC{nullptr}, K, colour, e, (int)j, T, put);
+}
+template <class MO>
+DASH_HD void digits_sum_store(const DigitsLaunch& L, const MO& Mo, uint32_t e, uint32_t j, const uint32_t* row) {
+    const LView out{L.sum1 + L.sum_prefix[j], L.out_cs, 16u};
+#pragma unroll
+    for (int ch = 0; ch < (int)MO::nchunk; ch++) {
+        Dw4 z;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int i = 4 * ch + q;
+            uint32_t w = 0;
+            if (i < (int)MO::ndw) {      // fields below 16 * 255 < 2^24
+                const uint32_t ev = row[2 * i], od = row[2 * i + 1];
+                w = mod_m(ev & 0xffffu, Mo) | (mod_m(ev >> 16, Mo) << 16) | (mod_m(od & 0xffffu, Mo) << 8) | (mod_m(od >> 16, Mo) << 24);
+            }
+            z.w[q] = w;
+        }
+        st_chunk(out, e, ch, z);
+    }
+}
+template <class MC, class M1>
+DASH_HD void digits_sum_phase2(const DigitsLaunch& L, uint32_t bx, uint32_t j, uint32_t el, const uint32_t* acc) {
+    const uint32_t e = bx * kSumElems + el;
+    if (e >= L.n_elem || j < 1 || j > L.n) return;
+    const uint32_t* row = acc + (size_t)el * (kSumDw * 2);
+    if (j == 1) digits_sum_store(L, M1{nullptr}, e, j, row);
+    else digits_sum_store(L, MC{nullptr}, e, j, row);
 }
 
 // evaluator side of the mixed-modulus half gate: z = V + beta * x - U

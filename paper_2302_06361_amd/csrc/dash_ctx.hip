@@ -237,6 +237,8 @@ int dash_ctx_create(dash_ctx** out, const uint16_t* primes, int k, int lambda_ru
     c->fused_min_elems[0] = 0; c->fused_min_elems[1] = 0;
     c->wide_max_lanes = 1u << 18;
     if (const char* e = getenv("DASH_WIDE_MAX_LANES")) c->wide_max_lanes = strtoull(e, nullptr, 10);                 // tuning and test hook
+    c->sum_in_launch = 1;
+    if (const char* e = getenv("DASH_SUM_IN_LAUNCH")) c->sum_in_launch = atoi(e) != 0;                               // tuning and test hook
     c->quad_max_lanes = 1u << 18;
     if (const char* e = getenv("DASH_QUAD_MAX_LANES")) c->quad_max_lanes = strtoull(e, nullptr, 10);                 // tuning and test hook
     c->few_rows_max = 1u << 20;

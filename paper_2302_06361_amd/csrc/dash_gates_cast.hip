@@ -67,6 +67,23 @@ __global__ __launch_bounds__(kThreads) void k_cast_digit_wide(const CastLaunch C
         cast_digit_wide_body<MC, M1>(C, L, tile, blockIdx.y, blockIdx.z + 1, threadIdx.x, T);
 }
 
+// the same with the digit gates adding up their outputs themselves (digits_sum_phase1/2): block = 64 elements x the odd
+// primes (a wave each), blockIdx.y = digit - 1
+template <class MC, class M1>
+__global__ __launch_bounds__(1024) void k_cast_digits_sum_wide(const CastLaunch C, const DigitsLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    __shared__ uint32_t acc[kSumElems * kSumDw * 2];
+    for (int i = threadIdx.x; i < kSumElems * kSumDw * 2; i += blockDim.x) acc[i] = 0;
+    const LdsTab T = load_ttab(tt, L.ttab);                  // (ends with a barrier: the accumulator is clear after it)
+    // (the wave's number through a scalar register: the residue's record is then read with scalar loads, like a blockIdx)
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), el = threadIdx.x & 63u, j = blockIdx.y + 1;
+    if constexpr (cmod_m<MC>::value != 0) {
+        digits_sum_phase1<MC, M1>(C, L, blockIdx.x, wave, j, el, T, acc);
+        __syncthreads();                                     // every lane of the block gets here: phase 1 returns, it does not exit
+        if (wave == 0) digits_sum_phase2<MC, M1>(L, blockIdx.x, j, el, acc);
+    }
+}
+
 static int check_cast(const dash_ctx* c, const CastLaunch& L, int njobs, double* bytes) {
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets
@@ -107,6 +124,16 @@ int launch_cast_digits_eval(const dash_ctx* c, CastLaunch& C, int njobs, DigitsL
         C.key = c->fixed; C.ttab = c->d_ttab; C.mods = c->d_mods;
         const int typed = typed_digits(c, L, uniform);
         ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.nres * (L.n + 1), bytes);
+        if (digits_sum_wanted(L, typed) && c->sum_in_launch) {
+            L.sums_in_launch = 1;
+            dim3 sgrid((L.n_elem + kSumElems - 1) / kSumElems, L.n);
+            with_digit_set(typed, [&](auto ds) {
+                typedef decltype(ds) DS;
+                hipLaunchKernelGGL((k_cast_digits_sum_wide<typename DS::MC, typename DS::M1>), sgrid, dim3(kSumElems * L.nres), 0, s, C, L);
+            });
+            DASH_HIP(hipGetLastError());
+            return DASH_OK;
+        }
         dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)(L.nres * L.n)), L.nres, L.n);
         with_digit_set(typed, [&](auto ds) {
             typedef decltype(ds) DS;

@@ -34,6 +34,27 @@ __global__ __launch_bounds__(kThreads) void k_digits_eval_wide(const DigitsLaunc
         digits_eval_wide_body<MC, M1>(L, tile, blockIdx.y, blockIdx.z + 1, threadIdx.x, T);
 }
 
+// few elements, digit sets with compile-time moduli: the digit gates add up their outputs themselves (digits_sum_phase1/2).
+// Block = 64 elements x the residues (a wave each), blockIdx.y = digit - 1.
+template <class MC, class M1>
+__global__ __launch_bounds__(1024) void k_digits_sum_wide(const DigitsLaunch L) {
+    __shared__ uint32_t tt[kTabWords];
+    __shared__ uint32_t acc[kSumElems * kSumDw * 2];
+    for (int i = threadIdx.x; i < kSumElems * kSumDw * 2; i += blockDim.x) acc[i] = 0;
+    const LdsTab T = load_ttab(tt, L.ttab);                  // (ends with a barrier: the accumulator is clear after it)
+    // (the wave's number through a scalar register: the residue's record is then read with scalar loads, like a blockIdx)
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), el = threadIdx.x & 63u, j = blockIdx.y + 1;
+    if constexpr (cmod_m<MC>::value != 0) {
+        digits_sum_phase1<MC, M1>(NoCast{}, L, blockIdx.x, wave, j, el, T, acc);
+        __syncthreads();                                     // every lane of the block gets here: phase 1 returns, it does not exit
+        if (wave == 0) digits_sum_phase2<MC, M1>(L, blockIdx.x, j, el, acc);
+    }
+}
+// whether a wide launch can take that form
+bool digits_sum_wanted(const DigitsLaunch& L, int typed) {
+    return typed != 0 && L.n >= 2 && L.sum1 != nullptr && L.nres * kSumElems <= 1024;
+}
+
 int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
     bool uniform = false;
     double bytes = 0;
@@ -44,6 +65,16 @@ int launch_digits_eval(const dash_ctx* c, DigitsLaunch& L, hipStream_t s) {
     ProfScope ps(c->prof, DASH_PROF_EVAL, s, (double)L.n_elem * L.nres * L.n, bytes);
     if ((uint64_t)L.n_elem * L.nres * L.n <= c->wide_max_lanes) {
         // few elements: the launch does not fill the chip, its time is the chain of hashes of one lane
+        if (digits_sum_wanted(L, typed) && c->sum_in_launch) {
+            L.sums_in_launch = 1;
+            dim3 sgrid((L.n_elem + kSumElems - 1) / kSumElems, L.n);
+            with_digit_set(typed, [&](auto ds) {
+                typedef decltype(ds) DS;
+                hipLaunchKernelGGL((k_digits_sum_wide<typename DS::MC, typename DS::M1>), sgrid, dim3(kSumElems * L.nres), 0, s, L);
+            });
+            DASH_HIP(hipGetLastError());
+            return DASH_OK;
+        }
         dim3 grid(grid_x_for((L.n_elem + kThreads - 1) / kThreads, (int)(L.nres * L.n)), L.nres, L.n);
         with_digit_set(typed, [&](auto ds) {
             typedef decltype(ds) DS;

@@ -66,6 +66,8 @@ struct dash_ctx {
     uint64_t fused_min_elems[2];     // [garble, eval]: sign gadgets over this many elements or more run their digit gates in
                                      // the fused kernels (a lane walks the n gates of a residue); smaller ones one gate per lane
     uint64_t wide_max_lanes;         // evaluator: sign gadgets of at most this many digit gates run them one per lane
+    int sum_in_launch;               // evaluator: digit gates of few elements add up their outputs in their own launch (1) or leave
+                                     // it to a free-gate launch (0)
     uint64_t quad_max_lanes;         // evaluator: carry chains of at most this many lanes (4 per element) run four lanes per element
     uint64_t few_rows_max;           // garbler: launches of at most this many rows take the forms for few rows (a lane per row of the
                                      // digit gates; gates of different output moduli in one launch)
@@ -89,6 +91,7 @@ int launch_digits_garble(const dash_ctx* c, DigitsLaunch& L, hipStream_t s);
 int launch_cast_halve(const dash_ctx* c, CastLaunch& L, int njobs, hipStream_t s);
 int launch_cast_digits_eval(const dash_ctx* c, CastLaunch& C, int njobs, DigitsLaunch& L, hipStream_t s);
 int launch_hg_finish(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
+bool digits_sum_wanted(const DigitsLaunch& L, int typed);
 bool hg_eval_quad_wanted(const dash_ctx* c, uint32_t n_elem);
 int launch_hg_eval_quad(const dash_ctx* c, HgLaunch& L, int njobs, hipStream_t s);
 

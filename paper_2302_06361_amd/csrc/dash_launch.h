@@ -187,6 +187,11 @@ struct DigitsLaunch {
                                           // n_elem * p_i * row_prefix[j] bytes after segment (i, 1)
     uint64_t out_prefix[kMaxChain + 1];   // wire (i, j) starts this many bytes after wire (i, 1)
     int64_t out_cs;                       // chunk stride of the output wires
+    // evaluator, optional: the wires S_j = sum over the residues of the digit wires (i, j) mod m_j, which the launch
+    // writes as well when it takes the form that adds them up itself (then it sets sums_in_launch and stores no digit wire)
+    uint8_t* sum1;                        // label tensor of S_1 (chunk stride out_cs), or null
+    uint64_t sum_prefix[kMaxChain + 1];   // S_j starts this many bytes after S_1
+    uint32_t sums_in_launch;
     DigitsRes res[16];
 };
 

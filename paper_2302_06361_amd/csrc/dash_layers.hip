@@ -186,6 +186,7 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         if (db.status) return db.status;
     }
     GateBatcher gb(c, garble, E, layer, elem_base, s);
+    bool sums_done = false;
     // digit gates: residue i -> digit j of its rounded CRT fraction.  The n gates of a residue share their input
     // label: one launch for all k n gates, whose lanes form and compress a label once for n rows (garbler) or n
     // gates (evaluator).  Small gadgets keep one gate per lane (n times the lanes, a chain n times shorter).
@@ -220,8 +221,17 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
                 if (c->phi_digit[i][j] != R.phi + (size_t)(j - 1) * c->prime[i]) return DASH_EINVAL;
             }
         }
+        if (!garble && n >= 2) {      // where the launch may write the digit sums itself (it says so in sums_in_launch)
+            bool regular = true;
+            for (int j = 1; j <= n; j++) {
+                DL.sum_prefix[j] = (uint64_t)(w.S[j].p - w.S[1].p);
+                if (w.S[j].p < w.S[1].p || w.S[j].cs != DL.out_cs || w.S[j].es != 16u) regular = false;
+            }
+            if (regular) DL.sum1 = w.S[1].p;
+        }
         const int st = garble ? launch_digits_garble(c, DL, s) : pre ? launch_cast_digits_eval(c, *pre, pre_jobs, DL, s) : launch_digits_eval(c, DL, s);
         if (st) return st;
+        sums_done = DL.sums_in_launch != 0;
     }
     // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
     // The garbler knows every zero label up front, so it sums all digits first and garbles the n
@@ -261,15 +271,17 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
     if (n >= 2) {
         // evaluator: all digit sums (without carries) in one free-gate launch, then the whole chain in one (adding the
         // digit wires inside the chain's lanes instead was measured slower: one lane per element, its loads in a row)
-        AffineBatcher ab(c, E, s);
-        for (int j = n; j >= 1; j--) {
-            Term t[kMaxTerms];
-            int nt = 0;
-            for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
-            ab.add(c->mj[j], w.S[j], t, nt);
+        if (!sums_done) {
+            AffineBatcher ab(c, E, s);
+            for (int j = n; j >= 1; j--) {
+                Term t[kMaxTerms];
+                int nt = 0;
+                for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
+                ab.add(c->mj[j], w.S[j], t, nt);
+            }
+            ab.flush();
+            if (ab.status) return ab.status;
         }
-        ab.flush();
-        if (ab.status) return ab.status;
         ChainLaunch CL;
         memset(&CL, 0, sizeof(CL));
         CL.n_elem = E; CL.layer = layer; CL.elem_base = elem_base; CL.n = (uint32_t)n;

@@ -3,7 +3,7 @@
 // of libdash.
 //
 // usage: digits_emul <in.bin> <out.bin>
-//   in : int32 n n_elem rule layer variant(0 run-time constants, else the index of the digit set's compile-time kernels: 1 <96,26>, 2 <204,46>, 3 <91,10>, 4 <90,22>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate, 3 garble with a lane per row); uint64 elem_base;
+//   in : int32 n n_elem rule layer variant(0 run-time constants, else the index of the digit set's compile-time kernels: 1 <96,26>, 2 <204,46>, 3 <91,10>, 4 <90,22>) nres slot0 mode(0 evaluate, 1 garble, 2 evaluate with a lane per digit gate, 3 garble with a lane per row, 4 evaluate with the sums over the residues formed in the same pass: out = for j: u8 S_j[n_elem][lam(m_j)]); uint64 elem_base;
 //        int32 m[n] (digit 1..n); int32 p[nres];
 //        for t < nres: u8 label_t[n_elem][lam(p_t)]            (active labels; garble: zero labels)
 //      evaluate:
@@ -40,6 +40,7 @@ int main(int argc, char** argv) {
     const int n = hd[0], rule = hd[2], layer = hd[3], variant = hd[4], nres = hd[5], slot0 = hd[6], garble = hd[7] == 1 || hd[7] == 3;
     const bool wide_rows = hd[7] == 3;      // garble with one lane per ciphertext row
     const bool wide = hd[7] == 2;      // evaluate with one lane per digit gate
+    const bool sums = hd[7] == 4;      // evaluate, the digit gates adding up their outputs (compile-time digit sets)
     const uint32_t E = (uint32_t)hd[1];
     if (n < 1 || n > kMaxChain || nres < 1 || nres > 16) return 2;
     std::vector<int32_t> m(n + 1), p(nres);
@@ -132,6 +133,43 @@ int main(int argc, char** argv) {
         f = fopen(argv[2], "wb");
         if (!f) return 2;
         for (int t = 0; t < nres; t++) fwrite(table[t].data(), 1, table[t].size(), f);      // [j][e][a][pitch_j] per residue
+        fclose(f);
+        return 0;
+    }
+    if (sums) {
+        if (variant == 0) return 2;
+        size_t sum_bytes = 0;
+        for (int j = 1; j <= n; j++) { L.sum_prefix[j] = sum_bytes; sum_bytes += (size_t)mods[m[j]].nchunk * E * 16; }
+        std::vector<uint8_t> S(sum_bytes, 0xEE);
+        L.sum1 = S.data();
+        const uint32_t blocks = (E + kSumElems - 1) / kSumElems;
+        for (uint32_t bx = 0; bx < blocks; bx++)
+            for (uint32_t j = 0; j <= (uint32_t)n + 1; j++) {       // (digit 0 and n + 1: lanes that must do nothing)
+                std::vector<uint32_t> acc((size_t)kSumElems * kSumDw * 2, 0);
+                with_digit_set(variant, [&](auto ds) {
+                    typedef decltype(ds) DS;
+                    if constexpr (cmod_m<typename DS::MC>::value != 0) {
+                        for (uint32_t by = 0; by < (uint32_t)nres; by++)
+                            for (uint32_t el = 0; el < (uint32_t)kSumElems; el++)
+                                digits_sum_phase1<typename DS::MC, typename DS::M1>(NoCast{}, L, bx, by, j, el, T, acc.data());
+                        for (uint32_t el = 0; el < (uint32_t)kSumElems; el++) digits_sum_phase2<typename DS::MC, typename DS::M1>(L, bx, j, el, acc.data());
+                    }
+                });
+            }
+        f = fopen(argv[2], "wb");
+        if (!f) return 2;
+        for (int j = 1; j <= n; j++) {
+            const ModInfo& M = mods[m[j]];
+            std::vector<uint8_t> c((size_t)E * M.lam);
+            const uint8_t* base = S.data() + L.sum_prefix[j];
+            for (uint32_t e = 0; e < E; e++)
+                for (uint32_t d = 0; d < M.nchunk * 16; d++) {
+                    const uint8_t v = base[((size_t)(d / 16) * E + e) * 16 + d % 16];
+                    if (d < M.lam) c[(size_t)e * M.lam + d] = v;
+                    else if (v != 0) return 3;      // digits past lambda must be zero
+                }
+            fwrite(c.data(), 1, c.size(), f);
+        }
         fclose(f);
         return 0;
     }

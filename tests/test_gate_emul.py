@@ -204,6 +204,49 @@ def test_digit_gates_one_per_lane_under_sanitizers(digits_emul, tmp_path):
     run_digits(digits_emul, tmp_path, [13], [26], 0, 5, wide=True)
 
 
+def run_digits_sums(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40):
+    """the form for few elements in which the digit gates add up their outputs themselves: wire S_j must be the sum over
+    the residues of the oracle's gate outputs (t, j), mod m_j (Appendix, Garbled Mixed-Radix Addition: the free sums)"""
+    orc = capi.Oracle(workloads.PRIMES[:8], workloads.DIGITS[8], SEED, rule)
+    n = len(m)
+    g = np.random.default_rng(3 * sum(m) + n_elem + len(primes))
+    acts = [workloads.uniform_labels(g, n_elem, orc.lam(p), p) for p in primes]
+    tabs = []
+    for p in primes:
+        row = []
+        for mj in m:
+            lam_o = orc.lam(mj)
+            t = np.zeros((n_elem, p, capi.pitch(lam_o)), np.uint8)
+            t[:, :, :lam_o] = g.integers(0, mj, (n_elem, p, lam_o))
+            row.append(t)
+        tabs.append(row)
+    blob = struct.pack("<8iQ", n, n_elem, rule, layer, variant, len(primes), slot0, 4, elem_base)
+    blob += struct.pack("<%di" % n, *m) + struct.pack("<%di" % len(primes), *primes)
+    blob += b"".join(a.tobytes() for a in acts)
+    blob += b"".join(t.tobytes() for row in tabs for t in row)
+    fin, fout = str(tmp_path / "sin.bin"), str(tmp_path / "sout.bin")
+    open(fin, "wb").write(blob)
+    r = subprocess.run([digits_emul, fin, fout], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr[-3000:])
+    got = np.fromfile(fout, np.uint8)
+    at = 0
+    for j, mj in enumerate(m):
+        lam_o = orc.lam(mj)
+        want = np.zeros((n_elem, lam_o), np.int64)
+        for t, p in enumerate(primes):
+            want += orc.proj_eval(p, mj, acts[t], tabs[t][j], layer, slot0 + t * n + j, elem_base)
+        assert (got[at:at + n_elem * lam_o].reshape(n_elem, lam_o) == want % mj).all(), mj
+        at += n_elem * lam_o
+    assert at == got.size
+
+
+def test_digit_gates_with_their_sums_under_sanitizers(digits_emul, tmp_path):
+    run_digits_sums(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19], [26] + [96] * 6, 1, 150)
+    run_digits_sums(digits_emul, tmp_path, [3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37], [46] + [204] * 10, 2, 70)      # the scaling gadget's 11 residues
+    run_digits_sums(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17], [10] + [91] * 5, 3, 65)
+    run_digits_sums(digits_emul, tmp_path, [2, 3, 5, 7, 11, 13, 17, 19, 23], [22] + [90] * 8, 4, 1)
+
+
 def run_digits_garble(digits_emul, tmp_path, primes, m, variant, n_elem, rule=0, elem_base=2 ** 32 + 9, layer=6, slot0=40, wide=False):
     """the garbler's side of the same gates: rows[colour(l0 + a R_p)] = out0 + phi_j(a) R_{m_j} + H(l0 + a R_p), every
     table segment against the oracle's projection gate with the same zero labels and function table"""

@@ -110,16 +110,19 @@ def test_activation_bank_replicated_tables_forced(monkeypatch, k):
     run_activation(k, "scale", X[:333], repeat=2, elem_base=77)
 
 
-@pytest.mark.parametrize("wide", ["0", "1000000000000"])
-def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide):
+@pytest.mark.parametrize("wide,sums", [("0", "1"), ("1000000000000", "1"), ("1000000000000", "0")])
+def test_activation_both_forms_of_the_evaluators_digit_gates(monkeypatch, wide, sums):
     """The evaluator runs the digit gates of a sign gadget one lane per (element, residue, digit) for gadgets over few
     elements and one lane per (element, residue) with n hashes, fused with the scaling gadget's cast step, for the rest;
     the garbler likewise has a form of its launches for few rows (a lane per row of the digit gates; gates of different
     output moduli in one launch, each job with its modulus' compile-time code) and one for many: both forms forced on
-    the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the oracle."""
+    the same layers (4 KB tables), compile-time and run-time digit sets, every byte against the oracle.  With one digit
+    gate per lane and a digit set with compile-time moduli the launch also forms the sums over the residues (the free
+    gates of the mixed-radix addition) and stores no digit wire; that is switched off in the third case."""
     monkeypatch.setenv("DASH_WIDE_MAX_LANES", wide)
     monkeypatch.setenv("DASH_GARBLE_FEW_ROWS", wide)
     monkeypatch.setenv("DASH_QUAD_MAX_LANES", wide)      # carry chain: four lanes per element that share each AES, or one
+    monkeypatch.setenv("DASH_SUM_IN_LAUNCH", sums)       # one digit gate per lane: the launch adds up the digit wires itself, or not
     for k in (7, 8, 9, 12):
         P = int(np.prod(workloads.PRIMES[:k]))
         X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P - 1], np.random.default_rng(300 + k).integers(0, P, 296)])
