@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kThreads) void k_affine(const AffineLaunch L) {
 }
 
 int launch_affine(const dash_ctx* c, AffineLaunch& L, int njobs, hipStream_t s) {
+    static_assert(sizeof(AffineLaunch) <= 4096, "kernel argument block");
     if (njobs < 1 || njobs > kMaxJobs) return DASH_EINVAL;
     if (L.n_elem == 0) return DASH_OK;
     if (L.n_elem > (1u << 28)) return DASH_ESIZE;      // lane offsets into a chunk are 32-bit byte offsets

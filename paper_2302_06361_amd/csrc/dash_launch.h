@@ -9,7 +9,7 @@ namespace dash {
 
 constexpr int kMaxJobs = 16;    // gate batches per launch (blockIdx.y)
 constexpr int kMaxDrawJobs = 64;   // label draws per launch: all fresh zero labels of a base-8 sign gadget (their jobs are small)
-constexpr int kMaxTerms = 64;   // label terms per launch, shared by its jobs
+constexpr int kMaxTerms = 96;   // label terms per launch, shared by its jobs
 constexpr int kThreads = 256;
 constexpr int kMaxChain = 16;   // mixed-radix digits of the sign gadget
 

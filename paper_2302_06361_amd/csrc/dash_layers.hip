@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <functional>
 #include <vector>
 
 #include "dash_internal.h"
@@ -171,10 +172,13 @@ bool few_rows(const dash_ctx* c, uint64_t rows) { return rows <= c->few_rows_max
 
 int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64_t elem_base, const LView* x, int first_res,
               int negate, uint32_t slot_base, uint8_t* seg, const SignWires& w, hipStream_t s, const LView* up = nullptr,
-              const LView* up_one = nullptr, uint32_t up_coef = 0, CastLaunch* pre = nullptr, int pre_jobs = 0, bool drawn = false) {
+              const LView* up_one = nullptr, uint32_t up_coef = 0, CastLaunch* pre = nullptr, int pre_jobs = 0, bool drawn = false,
+              const std::function<void(AffineBatcher&)>* pre_affine = nullptr, const std::vector<GateJob>* extra_gates = nullptr) {
     // pre (evaluator of the scaling gadget): the cast-and-halve step that produces x[first_res..]; it runs in the
     // launch of the digit gates when they are fused, else in a launch of its own before them
     // drawn (garbler): the caller has drawn the zero labels (sign_draws) in a launch of its own
+    // pre_affine, extra_gates (garbler): free gates and projection gates of the caller that depend on drawn labels only; they
+    // share the gadget's free-gate launch and, where the launches have few rows, its launch of the carry chain's gates
     const int k = c->k, n = c->n;
     size_t off[DASH_MAX_PRIMES * DASH_MAX_DIGITS + DASH_MAX_DIGITS], cum = 0;
     for (int sl = 0; sl < sign_nslots(c); sl++) { off[sl] = cum * E; cum += sign_slot_bytes(c, sl, first_res); }
@@ -184,6 +188,26 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         sign_draws(c, db, first_res, slot_base, w);
         db.flush();
         if (db.status) return db.status;
+    }
+    // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1.  The garbler knows every
+    // zero label up front (all are drawn), so it forms all digit sums first, in one free-gate launch, and garbles the n gates
+    // of the chain in one launch at the end; the evaluator has to follow the chain.
+    if (garble) {
+        AffineBatcher ab(c, E, s);
+        if (pre_affine) (*pre_affine)(ab);
+        for (int j = n; j >= 1; j--) {
+            Term t[kMaxTerms];
+            int nt = 0;
+            for (int i = first_res; i < k; i++) t[nt++] = Term{w.A[i][j], 1};
+            if (j < n) t[nt++] = Term{w.C[j], 1};
+            ab.add(c->mj[j], w.S[j], t, nt);
+        }
+        if (up) {       // the output wire's zero label is drawn, so its shifted copy can be formed here already
+            Term tu[2] = {Term{w.bit, 1}, Term{*up_one, up_coef}};
+            ab.add(2, *up, tu, 2);
+        }
+        ab.flush();
+        if (ab.status) return ab.status;
     }
     GateBatcher gb(c, garble, E, layer, elem_base, s);
     bool sums_done = false;
@@ -233,9 +257,6 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         if (st) return st;
         sums_done = DL.sums_in_launch != 0;
     }
-    // mixed-radix addition, least significant digit first: carry out of digit j into digit j-1
-    // The garbler knows every zero label up front, so it sums all digits first and garbles the n
-    // gates of the chain in one launch; the evaluator has to follow the chain.
     auto sum_digit = [&](AffineBatcher& ab, int j) {
         Term t[kMaxTerms];
         int nt = 0;
@@ -253,17 +274,21 @@ int sign_core(const dash_ctx* c, bool garble, uint32_t E, uint32_t layer, uint64
         }
     };
     if (garble) {
-        AffineBatcher ab(c, E, s);
-        for (int j = n; j >= 1; j--) sum_digit(ab, j);
-        if (up) {       // the output wire's zero label is drawn, so its shifted copy can be formed here already
-            Term tu[2] = {Term{w.bit, 1}, Term{*up_one, up_coef}};
-            ab.add(2, *up, tu, 2);
+        uint64_t rows = 0, extra_rows = 0;
+        for (int j = 1; j <= n; j++) rows += (uint64_t)E * c->mj[j];
+        if (extra_gates) for (const GateJob& J : *extra_gates) extra_rows += (uint64_t)E * J.p;
+        gb.mixed = few_rows(c, rows + extra_rows);
+        if (extra_gates) {
+            if (gb.mixed) {
+                for (const GateJob& J : *extra_gates) gb.add(J);
+            } else {      // a launch of their own, mixed if they are few; else one per output modulus, its compile-time code
+                GateBatcher ge(c, true, E, layer, elem_base, s, few_rows(c, extra_rows));
+                for (const GateJob& J : *extra_gates) ge.add(J);
+                ge.flush();
+                if (ge.status) return ge.status;
+                gb.mixed = few_rows(c, rows);
+            }
         }
-        ab.flush();
-        if (ab.status) return ab.status;
-        uint64_t chain_rows = 0;
-        for (int j = 1; j <= n; j++) chain_rows += (uint64_t)E * c->mj[j];
-        gb.mixed = few_rows(c, chain_rows);
         for (int j = n; j >= 1; j--) chain_gate(j);
         gb.flush();
         return gb.status;
@@ -488,6 +513,9 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
         // b of this repetition alternates between two buffer sets (the halving reads the one before)
         LView* bnew = rep & 1 ? pl.buf[0] : pl.b;
         const LView* bold = rep & 1 ? pl.b : pl.buf[0];
+        // the shifted mod-2 wire likewise: this repetition reads one buffer (its cast gates: the garbler's run in the gadget's
+        // last launch) while the sign gadget writes the next repetition's into the other
+        const LView up_cur = rep & 1 ? pl.buf[1][0] : pl.up, up_next = rep & 1 ? pl.up : pl.buf[1][0];
         auto addc_of = [&](uint32_t p) { return rep == 0 ? 0u : (uint32_t)((p - quarter % p) % p); };
         size_t cum = 0;
         if (garble) {
@@ -496,25 +524,28 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
             sign_draws(c, db, 1, sb + (k - 1), pl.w);
             db.flush();
             if (db.status) return db.status;
-            GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, (uint64_t)E * 2 * (k - 1)));
+            // the cast gates and the halving of the zero labels depend on drawn labels only: they go into the sign gadget's
+            // launches (its free-gate launch; its carry-chain launch where the rows are few)
+            std::vector<GateJob> casts;
             for (int i = 1; i < k; i++) {
-                gb.add(phi_job(2, c->prime[i], pl.up, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
+                casts.push_back(phi_job(2, c->prime[i], up_cur, c->phi_ident, sb + (i - 1), pl.cast[i], tb + cum * E));
                 cum += 2 * pitch_of(c, c->prime[i]);
             }
-            gb.flush();
-            if (gb.status) return gb.status;
-            AffineBatcher ab(c, E, s);
-            for (int i = 1; i < k; i++) {
-                const uint32_t p = c->prime[i], inv2 = (p + 1) / 2, addc = addc_of(p);
-                Term t[3] = {Term{rep == 0 ? x[i] : bold[i], inv2}, Term{pl.cast[i], p - inv2}, Term{one[i], (inv2 * addc) % p}};
-                ab.add(p, bnew[i], t, addc ? 3 : 2);
-            }
-            ab.flush();
-            if (ab.status) return ab.status;
+            const std::function<void(AffineBatcher&)> halving = [&](AffineBatcher& ab) {
+                for (int i = 1; i < k; i++) {
+                    const uint32_t p = c->prime[i], inv2 = (p + 1) / 2, addc = addc_of(p);
+                    Term t[3] = {Term{rep == 0 ? x[i] : bold[i], inv2}, Term{pl.cast[i], p - inv2}, Term{one[i], (inv2 * addc) % p}};
+                    ab.add(p, bnew[i], t, addc ? 3 : 2);
+                }
+            };
+            const uint32_t upc = (c0 + 1) % 2;
+            const int st = sign_core(c, true, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &up_next,
+                                     last ? nullptr : &one[0], upc, nullptr, 0, true, &halving, &casts);
+            if (st) return st;
         } else {
             CastLaunch CL;
             memset(&CL, 0, sizeof(CL));
-            CL.n_elem = E; CL.layer = layer; CL.elem_base = eb; CL.y = pl.up;
+            CL.n_elem = E; CL.layer = layer; CL.elem_base = eb; CL.y = up_cur;
             int nj = 0;
             for (int i = 1; i < k; i++) {
                 const uint32_t p = c->prime[i];
@@ -529,14 +560,8 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
             }
             // (k - 1 <= kMaxJobs: one launch, which sign_core merges with the digit gates' when those are fused)
             const uint32_t upc = (c0 + 1) % 2;
-            const int st = sign_core(c, false, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
+            const int st = sign_core(c, false, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &up_next,
                                      last ? nullptr : &one[0], upc, &CL, nj);
-            if (st) return st;
-        }
-        if (garble) {
-            const uint32_t upc = (c0 + 1) % 2;
-            const int st = sign_core(c, true, E, layer, eb, bnew, 1, 0, sb + (k - 1), tb + cum * E, pl.w, s, last ? nullptr : &pl.up,
-                                     last ? nullptr : &one[0], upc, nullptr, 0, true);
             if (st) return st;
         }
         if (last) {
