@@ -137,7 +137,8 @@ int dash_weights_prepare(dash_ctx *ctx, const int32_t *w, int out_c, int K, void
 /* Gb, one layer: from the zero labels of the layer's input wires produce the zero labels of its
  * output wires and (RELU, SCALE, SIGN, PROJ) its ciphertext tables.  Fresh zero labels come from
  * the PRG, addressed by (layer_id, slot, element).  tables / scratch: device, sizes from
- * dash_layer_sizes (may be NULL when the size is 0). */
+ * dash_layer_sizes (may be NULL when the size is 0).  For RELU, SCALE and SIGN out_zero may be the same bundle as in_zero
+ * (in place; likewise out_act and in_act of dash_eval_layer); bundles that overlap only in part are not supported. */
 int dash_garble_layer(dash_ctx *ctx, const dash_layer *layer, const dash_labels *in_zero, dash_labels *out_zero,
                       void *tables, void *scratch, void *hip_stream);
 /* Ev, one layer: from the active labels of the input wires and the tables produce the active

@@ -368,9 +368,6 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
     plan_relu(c, ar, E, pl);
     LView x[DASH_MAX_PRIMES];
     for (int i = 0; i < k; i++) x[i] = view_of(in, i);
-    // pos = [X < P/2]
-    int st = sign_core(c, garble, E, layer, eb, x, 0, 1, 0, tables, pl.w, s);
-    if (st) return st;
     size_t cum = sign_bytes(c, 0);
     uint8_t *G[DASH_MAX_PRIMES], *Eh[DASH_MAX_PRIMES], *S[DASH_MAX_PRIMES];
     for (int i = 0; i < k; i++) {
@@ -379,8 +376,12 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         Eh[i] = tables + cum * E; cum += 2 * pit;
         S[i] = tables + cum * E; cum += 8;
     }
+    // pos = [X < P/2] by the sign gadget, then the half gates
     if (garble) {
+        // every zero label and mask is drawn first; the half gates and the zero label of the product depend on drawn labels
+        // only, so they go into the sign gadget's launches (sign_core: pre_affine, extra_gates)
         DrawBatcher db(c, E, layer, eb, s);
+        sign_draws(c, db, 0, 0, pl.w);
         for (int i = 0; i < k; i++) {
             db.add(c->prime[i], DOM_GATE, ns + 3 * i, pl.U[i]);
             db.add(c->prime[i], DOM_GATE, ns + 3 * i + 1, pl.V[i]);
@@ -388,34 +389,42 @@ int relu_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels*
         }
         db.flush();
         if (db.status) return db.status;
-        uint64_t hg_rows = 0;
-        for (int i = 0; i < k; i++) hg_rows += (uint64_t)E * (c->prime[i] + 4);
-        // (few rows: everything in launches that mix output moduli; else one launch per output modulus, its compile-time code)
-        GateBatcher gb(c, true, E, layer, eb, s, few_rows(c, hg_rows)), gb2(c, true, E, layer, eb, s, few_rows(c, hg_rows));
+        std::vector<GateJob> halves;
         for (int i = 0; i < k; i++) {
             int p = c->prime[i];
             GateJob J = phi_job(p, p, x[i], nullptr, ns + 3 * i, pl.U[i], G[i]);          // garbler half: a -> a*r
             J.mode = PAY_MULR; J.r = pl.r[i];
-            gb.add(J);
+            halves.push_back(J);
             J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 1, pl.V[i], Eh[i]);         // evaluator half: -(b+r)*x0
             J.mode = PAY_EHALF; J.r = pl.r[i]; J.x0 = x[i];
-            gb2.add(J);
+            halves.push_back(J);
             J = phi_job(2, p, pl.w.bit, nullptr, ns + 3 * i + 2, pl.V[i], S[i]);          // b + r for the evaluator
             J.mode = PAY_SHORT; J.r = pl.r[i];
-            gb2.add(J);
+            halves.push_back(J);
         }
-        gb.flush();
-        gb2.flush();
-        if (gb.status) return gb.status;
-        if (gb2.status) return gb2.status;
-        AffineBatcher ab(c, E, s);                                                    // zero label of the product: V0 - U0
+        const std::function<void(AffineBatcher&)> product = [&](AffineBatcher& ab) {         // zero label of the product: V0 - U0
+            for (int i = 0; i < k; i++) {
+                Term t[2] = {Term{pl.V[i], 1}, Term{pl.U[i], (uint32_t)c->prime[i] - 1}};
+                ab.add(c->prime[i], view_of(out, i), t, 2);
+            }
+        };
+        // (a caller that garbles in place, out over in, gets the product's label written after the last read of in)
+        bool in_place = false;
         for (int i = 0; i < k; i++) {
-            Term t[2] = {Term{pl.V[i], 1}, Term{pl.U[i], (uint32_t)c->prime[i] - 1}};
-            ab.add(c->prime[i], view_of(out, i), t, 2);
+            const uint8_t *a = (const uint8_t*)in->data[i], *b = (const uint8_t*)out->data[i];
+            const int64_t la = in->chunk_stride[i] * c->mods[c->prime[i]].nchunk, lb = out->chunk_stride[i] * c->mods[c->prime[i]].nchunk;
+            if (a < b + lb && b < a + la) in_place = true;
         }
+        const int st = sign_core(c, true, E, layer, eb, x, 0, 1, 0, tables, pl.w, s, nullptr, nullptr, 0, nullptr, 0, true,
+                                 in_place ? nullptr : &product, &halves);
+        if (st || !in_place) return st;
+        AffineBatcher ab(c, E, s);
+        product(ab);
         ab.flush();
         return ab.status;
     }
+    int st = sign_core(c, false, E, layer, eb, x, 0, 1, 0, tables, pl.w, s);
+    if (st) return st;
     HgLaunch H;
     memset(&H, 0, sizeof(H));
     H.n_elem = E; H.layer = layer; H.elem_base = eb;

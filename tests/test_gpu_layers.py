@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wire=500, digits=None, exact=True, lam=None,
-                   default_digits=False):
+                   default_digits=False, in_place=False):
     from paper_2302_06361_amd import Labels, Layer, RELU, SCALE, SIGN
     if default_digits:      # the library picks the digit set; the oracle is built from what it reports
         from paper_2302_06361_amd import Context
@@ -43,7 +43,7 @@ def run_activation(k, kind, X, repeat=1, rule=0, layer=6, elem_base=0, first_wir
     oe, tb, sb = ctx.layer_sizes(lay)
     assert oe == n and tb == rt.size
     tz, ta = upload_bundle(ctx, zero), upload_bundle(ctx, act)
-    oz, oa = Labels(ctx, n, zero=True), Labels(ctx, n, zero=True)
+    oz, oa = (tz, ta) if in_place else (Labels(ctx, n, zero=True), Labels(ctx, n, zero=True))      # in place: out over in
     tables = torch.zeros(max(tb, 4), dtype=torch.uint8, device=ctx.device)[:tb]
     scratch = torch.zeros(sb + 256, dtype=torch.uint8, device=ctx.device)
     ctx.garble_layer(lay, tz, oz, tables, scratch)
@@ -159,6 +159,15 @@ def test_activation_default_digit_sets(k):
     X = np.concatenate([[0, 1, P // 2 - 1, P // 2, P // 2 + 1, P - 1], g.integers(0, P, 194)])
     run_activation(k, "relu", X, default_digits=True)
     run_activation(k, "scale", X, repeat=2, default_digits=True)
+
+
+def test_activation_in_place():
+    """output bundle = input bundle, for the garbler and for the evaluator: the garbler writes the output's zero labels
+    only after its last read of the input's"""
+    P = int(np.prod(workloads.PRIMES[:8]))
+    X = np.random.default_rng(61).integers(0, P, 200)
+    for kind, rep in (("relu", 1), ("scale", 3), ("sign", 1)):
+        run_activation(8, kind, X, repeat=rep, in_place=True)
 
 
 def test_activation_single_element():
