@@ -508,10 +508,14 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
     LView x[DASH_MAX_PRIMES];
     for (int i = 0; i < k; i++) x[i] = view_of(in, i);
     const uint32_t c0 = (uint32_t)((2 - quarter % 2) % 2);
-    {
-        AffineBatcher ab(c, E, s);
-        Term t[2] = {Term{x[0], 1}, Term{one[0], 1}};      // ShiftUp: + P/2, i.e. +1 on the mod-2 residue only
+    // ShiftUp: + P/2, i.e. +1 on the mod-2 residue only (the garbler forms it in its first free-gate launch)
+    auto shift_up = [&](AffineBatcher& ab) {
+        Term t[2] = {Term{x[0], 1}, Term{one[0], 1}};
         ab.add(2, pl.up, t, 2);
+    };
+    if (!garble) {
+        AffineBatcher ab(c, E, s);
+        shift_up(ab);
         ab.flush();
         if (ab.status) return ab.status;
     }
@@ -541,6 +545,7 @@ int scale_layer(dash_ctx* c, const dash_layer* L, bool garble, const dash_labels
                 cum += 2 * pitch_of(c, c->prime[i]);
             }
             const std::function<void(AffineBatcher&)> halving = [&](AffineBatcher& ab) {
+                if (rep == 0) shift_up(ab);
                 for (int i = 1; i < k; i++) {
                     const uint32_t p = c->prime[i], inv2 = (p + 1) / 2, addc = addc_of(p);
                     Term t[3] = {Term{rep == 0 ? x[i] : bold[i], inv2}, Term{pl.cast[i], p - inv2}, Term{one[i], (inv2 * addc) % p}};
