@@ -170,6 +170,16 @@ def test_activation_in_place():
         run_activation(8, kind, X, repeat=rep, in_place=True)
 
 
+@pytest.mark.parametrize("n", [63, 64, 65, 129])
+def test_activation_sizes_around_a_block_of_the_small_gadget_kernels(n):
+    """the kernels for gadgets over few elements work on blocks of 64 elements (digit gates that add up their outputs) and
+    on quads of lanes (carry chain, half gate): sizes just below, at and above a block"""
+    P = int(np.prod(workloads.PRIMES[:8]))
+    X = np.random.default_rng(500 + n).integers(0, P, n)
+    run_activation(8, "relu", X, elem_base=7)
+    run_activation(8, "scale", X, repeat=2, elem_base=2 ** 33)
+
+
 def test_activation_single_element():
     run_activation(8, "relu", np.array([12345]))
     run_activation(8, "scale", np.array([9699689]), repeat=3)
